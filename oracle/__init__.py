@@ -1,0 +1,180 @@
+"""FP64 CPU oracle for the local GEMM / forward-convolution kernels.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()``
+and by the ``cpu_baseline`` leg of ``bench.py``; never by the product package.
+The arithmetic lives in ``dmath_oracle.c`` (plain C, FP64 sums in the order of
+the definitions); this module only marshals numpy arrays into it.
+
+Every function takes FP32 arrays (the same bytes the GPU sees) and returns
+``(ref, mag)`` as FP64 arrays: the reference value and the companion sum of
+absolute values used by the bound ``|gpu-ref| <= 4*K*2^-24*mag + 1e-6``.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+_i64 = ctypes.c_int64
+_dbl = ctypes.c_double
+_fp = ctypes.POINTER(ctypes.c_float)
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_int64)
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        lib = ctypes.CDLL(path)
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_gemm.restype = ctypes.c_int
+        lib.oracle_gemm.argtypes = [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _dbl, _fp, _i64,
+                                    _fp, _i64, _dbl, _fp, _i64, _dp, _dp]
+        lib.oracle_gemm_points.restype = ctypes.c_int
+        lib.oracle_gemm_points.argtypes = [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _dbl, _fp,
+                                           _i64, _fp, _i64, _dbl, _fp, _i64, _i64, _ip, _ip, _dp, _dp]
+        lib.oracle_conv2d_fwd.restype = ctypes.c_int
+        lib.oracle_conv2d_fwd.argtypes = [_i64] * 11 + [_dbl, _fp, _fp, _dbl, _fp, _dp, _dp]
+        lib.oracle_conv2d_fwd_points.restype = ctypes.c_int
+        lib.oracle_conv2d_fwd_points.argtypes = [_i64] * 11 + [_dbl, _fp, _fp, _dbl, _fp, _i64, _ip,
+                                                               _dp, _dp]
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _f32(a, name):
+    if a is None:
+        return None
+    if not isinstance(a, np.ndarray) or a.dtype != np.float32:
+        raise TypeError("%s must be a float32 numpy array" % name)
+    if not a.flags["C_CONTIGUOUS"]:
+        raise ValueError("%s must be C-contiguous (use the ld arguments for windows)" % name)
+    return a
+
+
+def _ptr(a):
+    return a.ctypes.data_as(_fp) if a is not None else ctypes.cast(None, _fp)
+
+
+def _need(a, count, name):
+    """The flat buffer must hold every element the definition may touch."""
+    if a is None:
+        if count > 0:
+            raise ValueError("%s is required" % name)
+        return
+    if a.size < count:
+        raise ValueError("%s holds %d elements, the call reads %d" % (name, a.size, count))
+
+
+def _extent(rows, cols, ld):
+    return 0 if rows == 0 or cols == 0 else (rows - 1) * ld + cols
+
+
+def _check_gemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0, ldc):
+    A = _f32(A, "A")
+    B = _f32(B, "B")
+    C0 = _f32(C0, "C0")
+    if alpha != 0.0:
+        _need(A, _extent(K, M, lda) if transA else _extent(M, K, lda), "A")
+        _need(B, _extent(N, K, ldb) if transB else _extent(K, N, ldb), "B")
+    if beta != 0.0:
+        _need(C0, _extent(M, N, ldc), "C0")
+    return A, B, C0
+
+
+def gemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta=0.0, C0=None, ldc=None):
+    """ref, mag (M x N float64) of alpha*op(A)*op(B) + beta*C0, row-major with leading dims."""
+    ldc = N if ldc is None else ldc
+    A, B, C0 = _check_gemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0, ldc)
+    ref = np.empty((M, N), dtype=np.float64)
+    mag = np.empty((M, N), dtype=np.float64)
+    rc = _load().oracle_gemm(int(bool(transA)), int(bool(transB)), M, N, K, float(alpha), _ptr(A), lda,
+                             _ptr(B), ldb, float(beta), _ptr(C0), ldc,
+                             ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
+    if rc != 0:
+        raise RuntimeError("oracle_gemm rejected its arguments")
+    return ref, mag
+
+
+def gemm_points(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0, ldc, pi, pj):
+    """Same sums at the output positions (pi[t], pj[t]) only."""
+    A, B, C0 = _check_gemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0, ldc)
+    pi = np.ascontiguousarray(pi, dtype=np.int64)
+    pj = np.ascontiguousarray(pj, dtype=np.int64)
+    assert pi.shape == pj.shape and pi.ndim == 1
+    ref = np.empty(pi.shape, dtype=np.float64)
+    mag = np.empty(pi.shape, dtype=np.float64)
+    rc = _load().oracle_gemm_points(int(bool(transA)), int(bool(transB)), M, N, K, float(alpha), _ptr(A),
+                                    lda, _ptr(B), ldb, float(beta), _ptr(C0), ldc, pi.size,
+                                    pi.ctypes.data_as(_ip), pj.ctypes.data_as(_ip),
+                                    ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
+    if rc != 0:
+        raise RuntimeError("oracle_gemm_points rejected its arguments")
+    return ref, mag
+
+
+def conv_out_shape(H, W, R, S, pad_h, pad_w, stride_h, stride_w):
+    P = (H + 2 * pad_h - R) // stride_h + 1 if H + 2 * pad_h - R >= 0 else 0
+    Q = (W + 2 * pad_w - S) // stride_w + 1 if W + 2 * pad_w - S >= 0 else 0
+    return P, Q
+
+
+def _check_conv(x, w, y0, N, C, H, W, Kout, R, S, P, Q, alpha, beta):
+    x = _f32(x, "x")
+    w = _f32(w, "w")
+    y0 = _f32(y0, "y0")
+    if alpha != 0.0:
+        _need(x, N * C * H * W, "x")
+        _need(w, Kout * C * R * S, "w")
+    if beta != 0.0:
+        _need(y0, N * Kout * P * Q, "y0")
+    return x, w, y0
+
+
+def conv2d_fwd(x, w, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=0.0, y0=None):
+    """ref, mag (N x Kout x P x Q float64) of the direct forward convolution of x[N,C,H,W] with w[Kout,C,R,S]."""
+    N, C, H, W = x.shape
+    Kout, C2, R, S = w.shape
+    assert C == C2
+    P, Q = conv_out_shape(H, W, R, S, pad[0], pad[1], stride[0], stride[1])
+    x, w, y0 = _check_conv(x, w, y0, N, C, H, W, Kout, R, S, P, Q, alpha, beta)
+    ref = np.empty((N, Kout, P, Q), dtype=np.float64)
+    mag = np.empty((N, Kout, P, Q), dtype=np.float64)
+    rc = _load().oracle_conv2d_fwd(N, C, H, W, Kout, R, S, pad[0], pad[1], stride[0], stride[1],
+                                   float(alpha), _ptr(x), _ptr(w), float(beta), _ptr(y0),
+                                   ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
+    if rc != 0:
+        raise RuntimeError("oracle_conv2d_fwd rejected its arguments")
+    return ref, mag
+
+
+def conv2d_fwd_points(x, w, idx, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=0.0, y0=None):
+    """Same sums at the flat offsets idx into the N x Kout x P x Q output."""
+    N, C, H, W = x.shape
+    Kout, C2, R, S = w.shape
+    assert C == C2
+    P, Q = conv_out_shape(H, W, R, S, pad[0], pad[1], stride[0], stride[1])
+    x, w, y0 = _check_conv(x, w, y0, N, C, H, W, Kout, R, S, P, Q, alpha, beta)
+    idx = np.ascontiguousarray(idx, dtype=np.int64)
+    ref = np.empty(idx.shape, dtype=np.float64)
+    mag = np.empty(idx.shape, dtype=np.float64)
+    rc = _load().oracle_conv2d_fwd_points(N, C, H, W, Kout, R, S, pad[0], pad[1], stride[0], stride[1],
+                                          float(alpha), _ptr(x), _ptr(w), float(beta), _ptr(y0),
+                                          idx.size, idx.ctypes.data_as(_ip),
+                                          ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
+    if rc != 0:
+        raise RuntimeError("oracle_conv2d_fwd_points rejected its arguments")
+    return ref, mag
+
+
+def bound(K, mag):
+    """Acceptance bound on |gpu - ref| per element: 4*K*2^-24*mag + 1e-6."""
+    return 4.0 * K * 2.0 ** -24 * mag + 1e-6

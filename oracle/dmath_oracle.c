@@ -1,0 +1,275 @@
+/*
+ * CPU oracle for the per-GPU dense kernels of a distributed math library
+ * (dMath, arXiv 1604.01416).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing on the product path links, loads or calls
+ * this file; it shares no code, header, table or helper with the HIP library.
+ * It exists so that the GPU results can be checked against the plain
+ * definitions of the operations, evaluated in FP64.
+ *
+ * What it computes
+ *   - GEMM, the local block update every worker issues per stage of the cyclic
+ *     matrix multiplication (section "Matrix Multiplication"; timed for one GPU
+ *     in table "Matrix Multiplication Performance"), with the transposed
+ *     variants the same section asks for and the fully-connected-layer forms of
+ *     figure "cyclic_gemm_cache_fwd" (Y = W^T X, grad X = W grad Y):
+ *         ref[i][j] = alpha * sum_{k<K} opA(i,k) * opB(k,j)  +  beta * C0[i][j]
+ *     row-major storage, opA(i,k) = A[i*lda+k] (N) or A[k*lda+i] (T), same for B.
+ *   - Forward convolution, the DNN primitive named in the abstract and in
+ *     section "Introduction" (data-parallel, needs no communication); the paper
+ *     leaves the formula to the DNN library it calls, so the reading used is the
+ *     usual DNN one: cross-correlation (no kernel flip), zero padding, dilation
+ *     1, one group, no bias, NCHW input, KCRS filters, NKPQ output:
+ *         ref[n][j][p][q] = alpha * sum_{c,r,s} x[n][c][p*sh+r-ph][q*sw+s-pw] * w[j][c][r][s]
+ *                           + beta * y0[n][j][p][q]
+ *   - For both, the companion magnitude sum (same expression with every factor
+ *     replaced by its absolute value) that the acceptance bound
+ *         |gpu - ref| <= 4*K*2^-24 * mag + 1e-6
+ *     needs.
+ *
+ * Conventions where the paper is silent (reference-BLAS ones): beta == 0 means
+ * C0 / y0 is never read (NaN there does not propagate); alpha == 0 means A and B
+ * (x and w) are never read.
+ *
+ * Arithmetic: inputs are FP32 and are promoted exactly to FP64; every product
+ * and sum is FP64, terms added in ascending k (GEMM) or ascending (c, r, s)
+ * (convolution).  No blocking, no reordering.  OpenMP only splits the
+ * independent output rows / output planes across threads.
+ *
+ * Parity status: every function here is pinned by tests that do not use this
+ * file to produce the expected value (integer-exact cases against int64
+ * arithmetic, identity / permutation / rank-1 / all-ones closed forms,
+ * transposition identities, delta filters, tap-count closed forms, brute force
+ * in Python, and library float64 matmul / conv2d).
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static inline double a_elem(const float *A, int64_t lda, int tA, int64_t i, int64_t k)
+{
+    return (double)(tA ? A[k * lda + i] : A[i * lda + k]);
+}
+
+static inline double b_elem(const float *B, int64_t ldb, int tB, int64_t k, int64_t j)
+{
+    return (double)(tB ? B[j * ldb + k] : B[k * ldb + j]);
+}
+
+/*
+ * Full GEMM.  ref and mag are dense M x N (row stride N) FP64 outputs; mag may
+ * be NULL.  C0 may be NULL when beta == 0.  Returns 0, or 1 on a bad argument.
+ */
+int oracle_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                double alpha, const float *A, int64_t lda,
+                const float *B, int64_t ldb,
+                double beta, const float *C0, int64_t ldc,
+                double *ref, double *mag)
+{
+    if (M < 0 || N < 0 || K < 0 || !ref) return 1;
+    if (beta != 0.0 && !C0 && M > 0 && N > 0) return 1;
+    if (alpha != 0.0 && K > 0 && M > 0 && N > 0 && (!A || !B)) return 1;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < M; ++i) {
+        double *s = (double *)calloc((size_t)(N > 0 ? N : 1), sizeof(double));
+        double *t = (double *)calloc((size_t)(N > 0 ? N : 1), sizeof(double));
+        if (!s || !t) {
+#pragma omp atomic write
+            fail = 1;
+            free(s);
+            free(t);
+            continue;
+        }
+        if (alpha != 0.0) {
+            for (int64_t k = 0; k < K; ++k) {
+                const double a = a_elem(A, lda, transA, i, k);
+                const double fa = fabs(a);
+                for (int64_t j = 0; j < N; ++j) {
+                    const double b = b_elem(B, ldb, transB, k, j);
+                    s[j] += a * b;
+                    t[j] += fa * fabs(b);
+                }
+            }
+        }
+        for (int64_t j = 0; j < N; ++j) {
+            double r = (alpha != 0.0) ? alpha * s[j] : 0.0;
+            double m = (alpha != 0.0) ? fabs(alpha) * t[j] : 0.0;
+            if (beta != 0.0) {
+                const double c0 = (double)C0[i * ldc + j];
+                r += beta * c0;
+                m += fabs(beta) * fabs(c0);
+            }
+            ref[i * N + j] = r;
+            if (mag) mag[i * N + j] = m;
+        }
+        free(s);
+        free(t);
+    }
+    return fail;
+}
+
+/*
+ * GEMM at chosen output positions (pi[p], pj[p]), p < npts: the same sums, one
+ * output element at a time, so that problems too large for the full routine can
+ * still be checked on a sample.
+ */
+int oracle_gemm_points(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                       double alpha, const float *A, int64_t lda,
+                       const float *B, int64_t ldb,
+                       double beta, const float *C0, int64_t ldc,
+                       int64_t npts, const int64_t *pi, const int64_t *pj,
+                       double *ref, double *mag)
+{
+    if (M < 0 || N < 0 || K < 0 || npts < 0 || !ref) return 1;
+    for (int64_t p = 0; p < npts; ++p)
+        if (pi[p] < 0 || pi[p] >= M || pj[p] < 0 || pj[p] >= N) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < npts; ++p) {
+        const int64_t i = pi[p], j = pj[p];
+        double s = 0.0, t = 0.0;
+        if (alpha != 0.0) {
+            for (int64_t k = 0; k < K; ++k) {
+                const double a = a_elem(A, lda, transA, i, k);
+                const double b = b_elem(B, ldb, transB, k, j);
+                s += a * b;
+                t += fabs(a) * fabs(b);
+            }
+        }
+        double r = (alpha != 0.0) ? alpha * s : 0.0;
+        double m = (alpha != 0.0) ? fabs(alpha) * t : 0.0;
+        if (beta != 0.0) {
+            const double c0 = (double)C0[i * ldc + j];
+            r += beta * c0;
+            m += fabs(beta) * fabs(c0);
+        }
+        ref[p] = r;
+        if (mag) mag[p] = m;
+    }
+    return 0;
+}
+
+static inline int64_t conv_out_dim(int64_t in, int64_t pad, int64_t filt, int64_t stride)
+{
+    const int64_t span = in + 2 * pad - filt;
+    if (span < 0) return 0;
+    return span / stride + 1;
+}
+
+/* One output element of the direct convolution: loops over (c, r, s) only. */
+static inline void conv_point(int64_t C, int64_t H, int64_t W, int64_t R, int64_t S,
+                              int64_t ph, int64_t pw, int64_t sh, int64_t sw,
+                              const float *x_img, const float *w_filt,
+                              int64_t p, int64_t q, double *sum, double *msum)
+{
+    double s_acc = 0.0, t_acc = 0.0;
+    for (int64_t c = 0; c < C; ++c)
+        for (int64_t r = 0; r < R; ++r)
+            for (int64_t s = 0; s < S; ++s) {
+                const int64_t ih = p * sh + r - ph;
+                const int64_t iw = q * sw + s - pw;
+                if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+                const double xv = (double)x_img[(c * H + ih) * W + iw];
+                const double wv = (double)w_filt[(c * R + r) * S + s];
+                s_acc += xv * wv;
+                t_acc += fabs(xv) * fabs(wv);
+            }
+    *sum = s_acc;
+    *msum = t_acc;
+}
+
+/*
+ * Full direct convolution (loops n, j, p, q, c, r, s).  ref / mag are dense
+ * N x Kout x P x Q FP64; mag may be NULL; y0 may be NULL when beta == 0.
+ */
+int oracle_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W,
+                      int64_t Kout, int64_t R, int64_t S,
+                      int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w,
+                      double alpha, const float *x, const float *w,
+                      double beta, const float *y0, double *ref, double *mag)
+{
+    if (N < 0 || C < 0 || H < 0 || W < 0 || Kout < 0 || R < 1 || S < 1) return 1;
+    if (pad_h < 0 || pad_w < 0 || stride_h < 1 || stride_w < 1 || !ref) return 1;
+    const int64_t P = conv_out_dim(H, pad_h, R, stride_h);
+    const int64_t Q = conv_out_dim(W, pad_w, S, stride_w);
+    if (beta != 0.0 && !y0 && N * Kout * P * Q > 0) return 1;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t j = 0; j < Kout; ++j) {
+            const float *x_img = x + n * C * H * W;
+            const float *w_filt = w + j * C * R * S;
+            for (int64_t p = 0; p < P; ++p)
+                for (int64_t q = 0; q < Q; ++q) {
+                    const int64_t o = ((n * Kout + j) * P + p) * Q + q;
+                    double s = 0.0, t = 0.0;
+                    if (alpha != 0.0)
+                        conv_point(C, H, W, R, S, pad_h, pad_w, stride_h, stride_w,
+                                   x_img, w_filt, p, q, &s, &t);
+                    double r = (alpha != 0.0) ? alpha * s : 0.0;
+                    double m = (alpha != 0.0) ? fabs(alpha) * t : 0.0;
+                    if (beta != 0.0) {
+                        const double c0 = (double)y0[o];
+                        r += beta * c0;
+                        m += fabs(beta) * fabs(c0);
+                    }
+                    ref[o] = r;
+                    if (mag) mag[o] = m;
+                }
+        }
+    return 0;
+}
+
+/* Convolution at chosen flat output offsets idx[p] into the N x Kout x P x Q array. */
+int oracle_conv2d_fwd_points(int64_t N, int64_t C, int64_t H, int64_t W,
+                             int64_t Kout, int64_t R, int64_t S,
+                             int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w,
+                             double alpha, const float *x, const float *w,
+                             double beta, const float *y0,
+                             int64_t npts, const int64_t *idx, double *ref, double *mag)
+{
+    if (N < 0 || C < 0 || H < 0 || W < 0 || Kout < 0 || R < 1 || S < 1) return 1;
+    if (pad_h < 0 || pad_w < 0 || stride_h < 1 || stride_w < 1 || !ref || npts < 0) return 1;
+    const int64_t P = conv_out_dim(H, pad_h, R, stride_h);
+    const int64_t Q = conv_out_dim(W, pad_w, S, stride_w);
+    const int64_t total = N * Kout * P * Q;
+    for (int64_t t = 0; t < npts; ++t)
+        if (idx[t] < 0 || idx[t] >= total) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < npts; ++t) {
+        int64_t o = idx[t];
+        const int64_t q = o % Q;
+        o /= Q;
+        const int64_t p = o % P;
+        o /= P;
+        const int64_t j = o % Kout;
+        const int64_t n = o / Kout;
+        double s = 0.0, m = 0.0;
+        if (alpha != 0.0)
+            conv_point(C, H, W, R, S, pad_h, pad_w, stride_h, stride_w,
+                       x + n * C * H * W, w + j * C * R * S, p, q, &s, &m);
+        double r = (alpha != 0.0) ? alpha * s : 0.0;
+        double mm = (alpha != 0.0) ? fabs(alpha) * m : 0.0;
+        if (beta != 0.0) {
+            const double c0 = (double)y0[idx[t]];
+            r += beta * c0;
+            mm += fabs(beta) * fabs(c0);
+        }
+        ref[t] = r;
+        if (mag) mag[t] = mm;
+    }
+    return 0;
+}

@@ -1,0 +1,368 @@
+"""Pins for the FP64 CPU oracle: none of the expected values below comes from the oracle.
+
+Each test fixes the oracle against something the mathematics fixes: hand-worked
+fixtures, exact integer arithmetic, identity / permutation / rank-1 / all-ones
+closed forms, transposition identities, padding and NaN conventions, linearity,
+the chain invariant of the stage-by-stage block update (dMath paper, section
+"Matrix Multiplication"), delta filters, tap counts, brute force written a
+second time in Python, and the float64 library routines of numpy / torch.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _read_fixture(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            out[key] = [float(v) for v in vals]
+    return out
+
+
+def _store(op_matrix, trans, ld_extra=0, fill=np.nan):
+    """Store op(X) the way the API expects it: X itself (N) or X^T (T), with padded rows."""
+    m = op_matrix.T if trans else op_matrix
+    rows, cols = m.shape
+    ld = cols + ld_extra
+    buf = np.full((rows, ld), fill, dtype=np.float32)
+    buf[:, :cols] = m
+    return np.ascontiguousarray(buf), ld
+
+
+# ----------------------------------------------------------------------------- GEMM
+
+def test_gemm_hand_worked_fixture_all_transposes():
+    fx = _read_fixture("gemm_hand_worked.txt")
+    M, N, K = int(fx["M"][0]), int(fx["N"][0]), int(fx["K"][0])
+    A = np.array(fx["A"], dtype=np.float32).reshape(M, K)
+    B = np.array(fx["B"], dtype=np.float32).reshape(K, N)
+    C0 = np.array(fx["C0"], dtype=np.float32).reshape(M, N)
+    want = np.array(fx["ref"]).reshape(M, N)
+    want_mag = np.array(fx["mag"]).reshape(M, N)
+    for tA, tB in itertools.product((0, 1), (0, 1)):
+        a, lda = _store(A, tA)
+        b, ldb = _store(B, tB)
+        ref, mag = oracle.gemm(tA, tB, M, N, K, fx["alpha"][0], a, lda, b, ldb, fx["beta"][0], C0, N)
+        assert np.array_equal(ref, want), (tA, tB)
+        assert np.array_equal(mag, want_mag), (tA, tB)
+
+
+@pytest.mark.parametrize("tA,tB", list(itertools.product((0, 1), (0, 1))))
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (3, 5, 7), (17, 33, 64), (64, 31, 256)])
+def test_gemm_integer_exact(tA, tB, M, N, K):
+    rng = np.random.default_rng(100 + M + 7 * N + 13 * K + 2 * tA + tB)
+    Ai = rng.integers(-8, 9, size=(M, K))
+    Bi = rng.integers(-8, 9, size=(K, N))
+    Ci = rng.integers(-8, 9, size=(M, N))
+    alpha, beta = 3, -2
+    want = alpha * (Ai.astype(np.int64) @ Bi.astype(np.int64)) + beta * Ci
+    want_mag = abs(alpha) * (np.abs(Ai) @ np.abs(Bi)) + abs(beta) * np.abs(Ci)
+    a, lda = _store(Ai.astype(np.float32), tA, ld_extra=3)
+    b, ldb = _store(Bi.astype(np.float32), tB, ld_extra=2)
+    c, ldc = _store(Ci.astype(np.float32), 0, ld_extra=5)
+    ref, mag = oracle.gemm(tA, tB, M, N, K, alpha, a, lda, b, ldb, beta, c, ldc)
+    assert np.array_equal(ref, want.astype(np.float64))
+    assert np.array_equal(mag, want_mag.astype(np.float64))
+    # the point-wise routine gives the same numbers
+    pi, pj = np.divmod(np.arange(M * N), N)
+    rp, mp = oracle.gemm_points(tA, tB, M, N, K, alpha, a, lda, b, ldb, beta, c, ldc, pi, pj)
+    assert np.array_equal(rp.reshape(M, N), ref)
+    assert np.array_equal(mp.reshape(M, N), mag)
+
+
+def test_gemm_identity_and_permutation():
+    rng = np.random.default_rng(1)
+    n, m = 9, 6
+    B = rng.standard_normal((n, m)).astype(np.float32)
+    C0 = rng.standard_normal((n, m)).astype(np.float32)
+    eye = np.eye(n, dtype=np.float32)
+    ref, _ = oracle.gemm(0, 0, n, m, n, 0.5, eye, n, B, m, 2.0, C0, m)
+    assert np.array_equal(ref, 0.5 * B.astype(np.float64) + 2.0 * C0.astype(np.float64))
+    A = rng.standard_normal((m, n)).astype(np.float32)
+    ref, _ = oracle.gemm(0, 0, m, n, n, 1.0, A, n, eye, n, 0.0, None, n)
+    assert np.array_equal(ref, A.astype(np.float64))
+    perm = rng.permutation(n)
+    Pm = np.zeros((n, n), dtype=np.float32)
+    Pm[np.arange(n), perm] = 1.0          # row i of P*B is row perm[i] of B
+    ref, _ = oracle.gemm(0, 0, n, m, n, 1.0, Pm, n, B, m, 0.0, None, m)
+    assert np.array_equal(ref, B[perm].astype(np.float64))
+    ref, _ = oracle.gemm(0, 0, m, n, n, 1.0, A, n, Pm, n, 0.0, None, n)
+    want = np.zeros((m, n))
+    want[:, perm] = A                      # column perm[i] of A*P is column i of A
+    assert np.array_equal(ref, want)
+    # a transposed permutation is its inverse: catches a swapped transpose flag
+    ref, _ = oracle.gemm(1, 0, n, m, n, 1.0, Pm, n, B, m, 0.0, None, m)
+    want = np.zeros((n, m))
+    want[perm] = B
+    assert np.array_equal(ref, want)
+
+
+def test_gemm_rank1_and_all_ones():
+    u = np.array([1, -2, 4, 0.5, 8], dtype=np.float32)
+    z = np.array([2, 0.25, -1, 16], dtype=np.float32)
+    ref, mag = oracle.gemm(0, 0, 5, 4, 1, 1.0, u.reshape(5, 1).copy(), 1, z.reshape(1, 4).copy(), 4)
+    assert np.array_equal(ref, np.outer(u, z).astype(np.float64))
+    assert np.array_equal(mag, np.abs(np.outer(u, z)).astype(np.float64))
+    K = 37
+    A = np.repeat(u.reshape(5, 1), K, axis=1).copy()      # u * 1^T
+    B = np.repeat(z.reshape(1, 4), K, axis=0).copy()      # 1 * z^T
+    ref, _ = oracle.gemm(0, 0, 5, 4, K, 1.0, A, K, B, 4)
+    assert np.array_equal(ref, K * np.outer(u, z).astype(np.float64))
+    rng = np.random.default_rng(5)
+    Bi = rng.integers(-5, 6, size=(K, 4)).astype(np.float32)
+    ones = np.ones((3, K), dtype=np.float32)
+    ref, _ = oracle.gemm(0, 0, 3, 4, K, 1.0, ones, K, Bi, 4)
+    assert np.array_equal(ref, np.tile(Bi.sum(axis=0, dtype=np.float64), (3, 1)))
+
+
+@pytest.mark.parametrize("tA,tB", list(itertools.product((0, 1), (0, 1))))
+def test_gemm_transposition_identities(tA, tB):
+    rng = np.random.default_rng(7)
+    M, N, K = 13, 11, 29
+    A = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+    B = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    base, base_mag = oracle.gemm(0, 0, M, N, K, 1.0, A, K, B, N)
+    a, lda = _store(A, tA, ld_extra=4)
+    b, ldb = _store(B, tB, ld_extra=1)
+    ref, mag = oracle.gemm(tA, tB, M, N, K, 1.0, a, lda, b, ldb)
+    assert np.array_equal(ref, base)      # same products, same k order: identical bits
+    assert np.array_equal(mag, base_mag)
+    # C^T = B^T A^T: op(B)^T stored as given, roles swapped
+    refT, _ = oracle.gemm(1 - tB, 1 - tA, N, M, K, 1.0, b, ldb, a, lda)
+    assert np.array_equal(refT, base.T)
+
+
+def test_gemm_padding_is_never_read_and_nan_conventions():
+    rng = np.random.default_rng(11)
+    M, N, K = 7, 5, 9
+    A = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+    B = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    C0 = rng.uniform(-1, 1, (M, N)).astype(np.float32)
+    tight, _ = oracle.gemm(0, 0, M, N, K, 1.5, A, K, B, N, 0.5, C0, N)
+    a, lda = _store(A, 0, ld_extra=6)        # padding is NaN
+    b, ldb = _store(B, 0, ld_extra=2)
+    c, ldc = _store(C0, 0, ld_extra=3)
+    ref, mag = oracle.gemm(0, 0, M, N, K, 1.5, a, lda, b, ldb, 0.5, c, ldc)
+    assert np.array_equal(ref, tight) and np.isfinite(mag).all()
+    # beta == 0: C0 full of NaN must not show up
+    nanC = np.full((M, N), np.nan, dtype=np.float32)
+    ref0, _ = oracle.gemm(0, 0, M, N, K, 1.0, A, K, B, N, 0.0, nanC, N)
+    assert np.isfinite(ref0).all()
+    assert np.allclose(ref0, A.astype(np.float64) @ B.astype(np.float64), rtol=1e-14, atol=0)
+    # alpha == 0: A, B full of NaN must not show up, result is beta*C0
+    nanA = np.full((M, K), np.nan, dtype=np.float32)
+    ref1, mag1 = oracle.gemm(0, 0, M, N, K, 0.0, nanA, K, nanA[:K, :N].copy(), N, -2.0, C0, N)
+    assert np.array_equal(ref1, -2.0 * C0.astype(np.float64))
+    assert np.array_equal(mag1, 2.0 * np.abs(C0.astype(np.float64)))
+    # K == 0
+    ref2, _ = oracle.gemm(0, 0, M, N, 0, 1.0, A, K, B, N, 3.0, C0, N)
+    assert np.array_equal(ref2, 3.0 * C0.astype(np.float64))
+    # empty outputs
+    r, m = oracle.gemm(0, 0, 0, N, K, 1.0, A, K, B, N)
+    assert r.shape == (0, N)
+
+
+def test_gemm_linearity_power_of_two_alpha():
+    rng = np.random.default_rng(13)
+    M, N, K = 8, 6, 50
+    A = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+    B = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    r1, _ = oracle.gemm(0, 0, M, N, K, 1.0, A, K, B, N)
+    r4, _ = oracle.gemm(0, 0, M, N, K, 4.0, A, K, B, N)
+    rA, _ = oracle.gemm(0, 0, M, N, K, 1.0, (4 * A).astype(np.float32), K, B, N)
+    assert np.array_equal(r4, 4.0 * r1)
+    assert np.array_equal(rA, 4.0 * r1)
+
+
+def test_gemm_matches_brute_force_python_and_numpy():
+    rng = np.random.default_rng(17)
+    M, N, K = 4, 3, 6
+    alpha, beta = 0.75, -1.25
+    for tA, tB in itertools.product((0, 1), (0, 1)):
+        A = rng.standard_normal((M, K)).astype(np.float32)
+        B = rng.standard_normal((K, N)).astype(np.float32)
+        C0 = rng.standard_normal((M, N)).astype(np.float32)
+        a, lda = _store(A, tA, ld_extra=2)
+        b, ldb = _store(B, tB, ld_extra=1)
+        ref, mag = oracle.gemm(tA, tB, M, N, K, alpha, a, lda, b, ldb, beta, C0, N)
+        for i in range(M):
+            for j in range(N):
+                s = 0.0
+                t = 0.0
+                for k in range(K):
+                    av = float(a[k, i]) if tA else float(a[i, k])
+                    bv = float(b[j, k]) if tB else float(b[k, j])
+                    s += av * bv
+                    t += abs(av) * abs(bv)
+                assert ref[i, j] == alpha * s + beta * float(C0[i, j])
+                assert mag[i, j] == abs(alpha) * t + abs(beta) * abs(float(C0[i, j]))
+    M, N, K = 40, 50, 300
+    A = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+    B = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    ref, _ = oracle.gemm(0, 0, M, N, K, 1.0, A, K, B, N)
+    lib = np.matmul(A.astype(np.float64), B.astype(np.float64))
+    assert np.max(np.abs(ref - lib)) <= 1e-12 * np.max(np.abs(lib))
+
+
+def test_chain_of_accumulate_steps_equals_one_product():
+    """Summing the per-stage local updates equals the one-shot product (section "Matrix Multiplication")."""
+    rng = np.random.default_rng(19)
+    m, kp, steps = 24, 8, 16
+    C0 = rng.standard_normal((m, m)).astype(np.float32)
+    As = [rng.uniform(-1, 1, (m, kp)).astype(np.float32) for _ in range(steps)]
+    Bs = [rng.uniform(-1, 1, (kp, m)).astype(np.float32) for _ in range(steps)]
+    Acat = np.ascontiguousarray(np.concatenate(As, axis=1))
+    Bcat = np.ascontiguousarray(np.concatenate(Bs, axis=0))
+    one, one_mag = oracle.gemm(0, 0, m, m, kp * steps, 1.0, Acat, kp * steps, Bcat, m, 1.0, C0, m)
+    acc = C0.astype(np.float64)
+    acc_mag = np.abs(acc)
+    for a, b in zip(As, Bs):
+        step, step_mag = oracle.gemm(0, 0, m, m, kp, 1.0, a, kp, b, m)
+        acc = acc + step
+        acc_mag = acc_mag + step_mag
+    assert np.max(np.abs(acc - one)) <= 1e-9 * np.max(np.abs(one))
+    assert np.max(np.abs(acc_mag - one_mag)) <= 1e-9 * np.max(np.abs(one_mag))
+
+
+def test_gemm_points_on_a_window_with_leading_dimensions():
+    rng = np.random.default_rng(23)
+    big = rng.integers(-4, 5, size=(20, 30)).astype(np.float32)
+    # A = big[2:9, 3:14] (7 x 11), B = big[5:16, 10:16] (11 x 6), both windows of one buffer
+    A = big.reshape(-1)[2 * 30 + 3:]
+    B = big.reshape(-1)[5 * 30 + 10:]
+    want = big[2:9, 3:14].astype(np.int64) @ big[5:16, 10:16].astype(np.int64)
+    ref, _ = oracle.gemm(0, 0, 7, 6, 11, 1.0, np.ascontiguousarray(A), 30, np.ascontiguousarray(B), 30)
+    assert np.array_equal(ref, want.astype(np.float64))
+
+
+# ----------------------------------------------------------------------------- convolution
+
+def _conv_brute(x, w, pad, stride):
+    """Second, independent statement of the definition: python loops in float64."""
+    N, C, H, W = x.shape
+    Kout, _, R, S = w.shape
+    P = (H + 2 * pad[0] - R) // stride[0] + 1
+    Q = (W + 2 * pad[1] - S) // stride[1] + 1
+    xp = np.zeros((N, C, H + 2 * pad[0], W + 2 * pad[1]))
+    xp[:, :, pad[0]:pad[0] + H, pad[1]:pad[1] + W] = x
+    y = np.zeros((N, Kout, P, Q))
+    for n in range(N):
+        for j in range(Kout):
+            for p in range(P):
+                for q in range(Q):
+                    win = xp[n, :, p * stride[0]:p * stride[0] + R, q * stride[1]:q * stride[1] + S]
+                    y[n, j, p, q] = float(np.sum(win * w[j].astype(np.float64)))
+    return y
+
+
+def test_conv_hand_worked_fixture():
+    fx = _read_fixture("conv_hand_worked.txt")
+    x = np.array(fx["x"], dtype=np.float32).reshape(1, 1, 3, 3)
+    w = np.array(fx["w"], dtype=np.float32).reshape(1, 1, 2, 2)
+    ref, mag = oracle.conv2d_fwd(x, w, pad=(0, 0), stride=(1, 1))
+    assert np.array_equal(ref.reshape(-1), np.array(fx["y_pad0_stride1"]))
+    assert np.array_equal(mag, ref)          # all entries positive
+    ref, _ = oracle.conv2d_fwd(x, w, pad=(1, 1), stride=(2, 2))
+    assert ref.shape == (1, 1, 2, 2)
+    assert np.array_equal(ref.reshape(-1), np.array(fx["y_pad1_stride2"]))
+
+
+def test_conv_1x1_is_a_gemm_per_image():
+    rng = np.random.default_rng(29)
+    N, C, H, W, Kout = 3, 10, 5, 4, 7
+    x = rng.integers(-4, 5, size=(N, C, H, W)).astype(np.float32)
+    w = rng.integers(-4, 5, size=(Kout, C, 1, 1)).astype(np.float32)
+    ref, _ = oracle.conv2d_fwd(x, w)
+    for n in range(N):
+        want = w.reshape(Kout, C).astype(np.int64) @ x[n].reshape(C, H * W).astype(np.int64)
+        assert np.array_equal(ref[n].reshape(Kout, H * W), want.astype(np.float64))
+
+
+def test_conv_delta_filters_pin_no_flip():
+    rng = np.random.default_rng(31)
+    N, C, H, W = 2, 4, 6, 5
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    centre = np.zeros((C, C, 3, 3), dtype=np.float32)
+    corner = np.zeros((C, C, 3, 3), dtype=np.float32)
+    for c in range(C):
+        centre[c, c, 1, 1] = 1.0
+        corner[c, c, 0, 0] = 1.0
+    ref, _ = oracle.conv2d_fwd(x, centre, pad=(1, 1))
+    assert np.array_equal(ref, x.astype(np.float64))
+    ref, _ = oracle.conv2d_fwd(x, corner, pad=(1, 1))
+    want = np.zeros((N, C, H, W))
+    want[:, :, 1:, 1:] = x[:, :, :-1, :-1]     # y[p,q] = x[p-1,q-1], zero border
+    assert np.array_equal(ref, want)
+
+
+def test_conv_all_ones_counts_valid_taps():
+    C, H, W, Kout = 5, 6, 7, 3
+    x = np.ones((2, C, H, W), dtype=np.float32)
+    w = np.ones((Kout, C, 3, 3), dtype=np.float32)
+    ref, _ = oracle.conv2d_fwd(x, w, pad=(1, 1))
+    want = np.full((H, W), 9.0)
+    want[0, :] = want[-1, :] = 6.0
+    want[:, 0] = want[:, -1] = 6.0
+    want[0, 0] = want[0, -1] = want[-1, 0] = want[-1, -1] = 4.0
+    assert np.array_equal(ref, np.broadcast_to(C * want, ref.shape))
+
+
+@pytest.mark.parametrize("shape", [
+    dict(N=2, C=3, H=7, W=5, Kout=4, R=3, S=3, pad=(1, 1), stride=(1, 1)),
+    dict(N=1, C=2, H=9, W=6, Kout=3, R=3, S=2, pad=(0, 0), stride=(2, 2)),
+    dict(N=2, C=1, H=8, W=11, Kout=2, R=5, S=3, pad=(2, 1), stride=(2, 3)),
+    dict(N=1, C=4, H=4, W=4, Kout=5, R=1, S=1, pad=(0, 0), stride=(1, 1)),
+])
+def test_conv_matches_brute_force_and_torch(shape):
+    import torch
+    rng = np.random.default_rng(37 + shape["H"])
+    x = rng.standard_normal((shape["N"], shape["C"], shape["H"], shape["W"])).astype(np.float32)
+    w = rng.standard_normal((shape["Kout"], shape["C"], shape["R"], shape["S"])).astype(np.float32)
+    y0 = rng.standard_normal(1000).astype(np.float32)
+    ref, mag = oracle.conv2d_fwd(x, w, pad=shape["pad"], stride=shape["stride"])
+    brute = _conv_brute(x, w, shape["pad"], shape["stride"])
+    assert ref.shape == brute.shape
+    assert np.max(np.abs(ref - brute)) <= 1e-12 * max(1.0, np.max(np.abs(brute)))
+    brute_mag = _conv_brute(np.abs(x), np.abs(w), shape["pad"], shape["stride"])
+    assert np.max(np.abs(mag - brute_mag)) <= 1e-12 * max(1.0, np.max(np.abs(brute_mag)))
+    lib = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(),
+                                     padding=shape["pad"], stride=shape["stride"]).numpy()
+    assert np.max(np.abs(ref - lib)) <= 1e-12 * max(1.0, np.max(np.abs(lib)))
+    # alpha / beta and the point-wise routine
+    y0 = np.ascontiguousarray(y0[:ref.size].reshape(ref.shape))
+    ref2, mag2 = oracle.conv2d_fwd(x, w, pad=shape["pad"], stride=shape["stride"], alpha=2.0, beta=-0.5, y0=y0)
+    assert np.array_equal(ref2, 2.0 * ref - 0.5 * y0.astype(np.float64))
+    assert np.array_equal(mag2, 2.0 * mag + 0.5 * np.abs(y0.astype(np.float64)))
+    idx = np.arange(ref.size)[::3]
+    rp, mp = oracle.conv2d_fwd_points(x, w, idx, pad=shape["pad"], stride=shape["stride"], alpha=2.0,
+                                      beta=-0.5, y0=y0)
+    assert np.array_equal(rp, ref2.reshape(-1)[idx])
+    assert np.array_equal(mp, mag2.reshape(-1)[idx])
+
+
+def test_conv_nan_conventions():
+    x = np.ones((1, 2, 4, 4), dtype=np.float32)
+    w = np.ones((2, 2, 3, 3), dtype=np.float32)
+    nan_y = np.full((1, 2, 4, 4), np.nan, dtype=np.float32)
+    ref, _ = oracle.conv2d_fwd(x, w, pad=(1, 1), beta=0.0, y0=nan_y)
+    assert np.isfinite(ref).all()
+    y0 = np.arange(32, dtype=np.float32).reshape(1, 2, 4, 4)
+    ref, _ = oracle.conv2d_fwd(np.full_like(x, np.nan), w, pad=(1, 1), alpha=0.0, beta=2.0, y0=y0)
+    assert np.array_equal(ref, 2.0 * y0.astype(np.float64))
+
+
+def test_bound_formula():
+    mag = np.array([0.0, 1.0, 2.5])
+    got = oracle.bound(4096, mag)
+    assert np.array_equal(got, 4.0 * 4096 * 2.0 ** -24 * mag + 1e-6)
