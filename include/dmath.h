@@ -1,0 +1,148 @@
+/*
+ * dmath.h - C ABI of the MI355X-native per-GPU dense kernels of a distributed
+ * math library (dMath, arXiv 1604.01416).
+ *
+ * The paper's distributed matrix multiplication (section "Matrix Multiplication")
+ * has every worker issue, per stage, one asynchronous dense multiply on blocks
+ * it holds, accumulating into its block of C; its DNN pipeline adds forward
+ * convolutions that run data-parallel with no communication (abstract, section
+ * "Introduction").  This library is that per-GPU work and nothing else: FP32
+ * in, FP32 accumulate (MFMA), FP32 out, on one gfx950 device.
+ *
+ * General rules for every entry point
+ *   - All matrix / tensor pointers are DEVICE pointers to FP32 data owned by the
+ *     caller; scalars are passed by value from the host.
+ *   - `stream` is a hipStream_t passed as void*; NULL means the default stream.
+ *     Calls enqueue work on that stream and return without synchronising.
+ *   - The library allocates no device memory.  Kernels that need scratch use the
+ *     workspace handed over with dmath_set_workspace(), or fall back to a path
+ *     that needs none.
+ *   - Arguments are validated before anything is launched; a call that returns
+ *     an error has not touched its outputs.  dmath_last_error_arg() gives the
+ *     1-based position of the offending argument of the last failed call made
+ *     by the calling thread.
+ *   - Outputs must not overlap inputs.
+ *   - Results are deterministic: the same call on the same data gives the same
+ *     bits (no atomics in any reduction).
+ */
+#ifndef DMATH_H
+#define DMATH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DMATH_OK = 0,
+    DMATH_ERR_INVALID_ARG = 1, /* negative size, bad leading dimension, bad enum */
+    DMATH_ERR_NULL_PTR = 2,    /* NULL operand that the call would have to touch */
+    DMATH_ERR_UNSUPPORTED = 3, /* valid request outside what is implemented */
+    DMATH_ERR_LAUNCH = 4,      /* the HIP runtime refused the launch */
+    DMATH_ERR_WORKSPACE = 5    /* workspace pointer / size inconsistent */
+} dmath_status;
+
+typedef enum { DMATH_OP_N = 0, DMATH_OP_T = 1 } dmath_op;
+
+/*
+ * Local block multiply, the GEMM each worker runs per stage (section "Matrix
+ * Multiplication"; one-GPU column of table "Matrix Multiplication Performance";
+ * the transposed forms are the variants that section mentions and the fully
+ * connected layer products Y = W^T X, grad X = W grad Y of figure
+ * "cyclic_gemm_cache_fwd"):
+ *
+ *     C[M x N] = alpha * op(A)[M x K] * op(B)[K x N] + beta * C
+ *
+ * ROW-MAJOR storage.  transA == N: A is stored M x K, element (i,k) at
+ * A[i*lda + k], lda >= max(1,K).  transA == T: A is stored K x M, element (i,k)
+ * of op(A) at A[k*lda + i], lda >= max(1,M).  transB == N: B stored K x N,
+ * ldb >= max(1,N); transB == T: B stored N x K, ldb >= max(1,K).  C is M x N
+ * with ldc >= max(1,N).  Leading dimensions let a block be a window of a larger
+ * row panel.  Any 4-byte aligned pointer and any legal leading dimension work;
+ * 16-byte aligned pointers with leading dimensions that are multiples of 4 take
+ * the fast path.
+ *
+ * M == 0 or N == 0: nothing happens.  K == 0 or alpha == 0: C = beta*C and A, B
+ * are not read (they may be NULL).  beta == 0: C is write-only, its old contents
+ * (NaN, Inf) never reach the result.
+ *
+ * Errors: INVALID_ARG for a bad enum, negative size or short leading dimension;
+ * NULL_PTR for a NULL operand that would be read or written; LAUNCH if the
+ * runtime rejects the kernel launch.
+ */
+dmath_status dmath_gemm(dmath_op transA, dmath_op transB,
+                        int64_t M, int64_t N, int64_t K,
+                        float alpha, const float *A, int64_t lda,
+                        const float *B, int64_t ldb,
+                        float beta, float *C, int64_t ldc,
+                        void *stream);
+
+/*
+ * Forward convolution (the DNN primitive of the abstract and of section
+ * "Introduction"; the paper delegates its formula to the DNN library it calls,
+ * so the usual DNN definition is used: cross-correlation, zero padding):
+ *
+ *     y[n][j][p][q] = alpha * sum_{c,r,s} x[n][c][p*stride_h + r - pad_h][q*stride_w + s - pad_w]
+ *                                         * w[j][c][r][s]   +   beta * y[n][j][p][q]
+ *
+ * x is N x C x H x W, w is Kout x C x R x S, y is N x Kout x P x Q, all dense
+ * and packed in that order, with P = (H + 2*pad_h - R)/stride_h + 1 and
+ * Q = (W + 2*pad_w - S)/stride_w + 1 (integer division; the filter must fit:
+ * H + 2*pad_h >= R, W + 2*pad_w >= S).  Taps that fall outside x count as zero.
+ * Dilation 1, one group, no bias.  The product is evaluated as a matrix
+ * multiply whose left operand is generated on the fly from x; the unfolded
+ * matrix is never stored and no workspace is used.
+ *
+ * Empty outputs (N, Kout, P or Q zero) are a no-op; C == 0 or alpha == 0 gives
+ * y = beta*y without reading x or w; beta == 0 makes y write-only.
+ *
+ * Errors: INVALID_ARG for negative sizes, R or S < 1, strides < 1, negative
+ * padding or a filter larger than the padded input; NULL_PTR as for dmath_gemm;
+ * UNSUPPORTED if a tensor has 2^31 or more elements per image-channel plane set
+ * that 32-bit in-kernel offsets cannot address.
+ */
+dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W,
+                              int64_t Kout, int64_t R, int64_t S,
+                              int64_t pad_h, int64_t pad_w,
+                              int64_t stride_h, int64_t stride_w,
+                              float alpha, const float *x, const float *w,
+                              float beta, float *y, void *stream);
+
+/*
+ * Scratch for the split-K path of dmath_gemm (used when the output alone has
+ * too few tiles to fill the device, as for the skinny products of a fully
+ * connected layer).  dmath_gemm_workspace_bytes() returns how many bytes the
+ * call with these arguments would like (0 if it would not split).
+ * dmath_set_workspace() registers a caller-owned device buffer for the current
+ * host thread's later calls; NULL / 0 removes it.  With no workspace, or one
+ * that is too small, dmath_gemm silently uses a path that needs none.  The
+ * buffer must stay valid, and must not be shared by calls running concurrently
+ * on different streams.  WORKSPACE is returned for a NULL pointer with a
+ * non-zero size or a pointer that is not 16-byte aligned.
+ */
+size_t dmath_gemm_workspace_bytes(dmath_op transA, dmath_op transB,
+                                  int64_t M, int64_t N, int64_t K);
+dmath_status dmath_set_workspace(void *device_ptr, size_t bytes);
+
+/*
+ * Tuning hook for benchmarks: force the tile configuration (index into the
+ * library's table, see dmath_config_name) and the split-K factor used by later
+ * dmath_gemm / dmath_conv2d_fwd calls of this thread.  -1 restores the automatic
+ * choice.  A forced split-K larger than 1 still needs a workspace.  Returns
+ * INVALID_ARG for an index outside the table.
+ */
+dmath_status dmath_set_override(int tile_config, int split_k);
+int dmath_num_configs(void);
+const char *dmath_config_name(int tile_config); /* NULL outside the table */
+
+/* 1-based index of the argument rejected by this thread's last failed call, 0 if none. */
+int dmath_last_error_arg(void);
+const char *dmath_status_string(dmath_status status);
+const char *dmath_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMATH_H */

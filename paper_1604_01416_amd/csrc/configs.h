@@ -1,0 +1,33 @@
+// Table of tile configurations.  Each entry is compiled in its own translation unit
+// (tile_instance.hip with -DDMATH_CFG_INDEX=<i>) and reached through the function table below.
+#pragma once
+#include "conv_kernel.h"
+#include "gemm_kernel.h"
+
+namespace dmath {
+
+template <int I> struct CfgAt;
+//                                        BM   BN  BK  waves  stages  min waves per SIMD
+template <> struct CfgAt<0> { typedef TileCfg<256, 128, 16, 4, 1, 3, 2> type; };  // wave tile 64 x 128, 2 workgroups per CU
+template <> struct CfgAt<1> { typedef TileCfg<128, 256, 16, 2, 2, 3, 2> type; };  // wave tile 64 x 128
+template <> struct CfgAt<2> { typedef TileCfg<256, 256, 16, 4, 2, 3, 2> type; };  // 512 threads, one workgroup per CU
+template <> struct CfgAt<3> { typedef TileCfg<128, 128, 16, 2, 2, 3, 2> type; };  // wave tile 64 x 64
+template <> struct CfgAt<4> { typedef TileCfg<64, 64, 16, 2, 2, 2, 2> type; };    // wave tile 32 x 32, small problems
+constexpr int kNumCfg = 5;
+
+struct CfgDesc {
+    const char *name;
+    int BM, BN, BK, NT, lds_bytes;
+    int (*gemm)(const GemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);
+    int (*conv)(const ConvArgs &, bool vec, hipStream_t);
+};
+
+// Defined one per translation unit.
+template <int I> const CfgDesc &cfg_desc();
+template <> const CfgDesc &cfg_desc<0>();
+template <> const CfgDesc &cfg_desc<1>();
+template <> const CfgDesc &cfg_desc<2>();
+template <> const CfgDesc &cfg_desc<3>();
+template <> const CfgDesc &cfg_desc<4>();
+
+}  // namespace dmath

@@ -1,0 +1,193 @@
+// Forward convolution as an implicit GEMM on the same macro-tile as dmath_gemm:
+//
+//     y_mat[Kout x (N*P*Q)] = w_mat[Kout x (C*R*S)] * x_unfolded[(C*R*S) x (N*P*Q)]
+//
+// Rows of the product are output channels (the filters, read in place: w is already a
+// Kout x CRS row-major matrix, contiguous along k), columns are output pixels (n, p, q) in memory
+// order, so a row of the product is contiguous in y inside one image.  The unfolded matrix is
+// never stored: the loader below generates each of its elements from x with the zero halo applied.
+// k = (c*R + r)*S + s, column = (n*P + p)*Q + q.
+#pragma once
+#include "tile_core.h"
+
+namespace dmath {
+
+struct ConvArgs {
+    const float *x;
+    const float *w;
+    float *y;
+    int N, C, H, W, Kout, R, S, P, Q;
+    int pad_h, pad_w, stride_h, stride_w;
+    int RS, PQ;
+    int64_t CRS, NPQ;
+    uint32_t magic_RS, magic_S;  // ceil(2^32 / d) for d > 1 (see fast_div); unused for d == 1
+    float alpha, beta;
+    int tiles_m, tiles_n;
+    int yvec;  // y is 16-byte aligned and P*Q is a multiple of 4
+};
+
+// floor(n / d) for a divisor fixed at launch: with magic = ceil(2^32 / d) the high word of n*magic is
+// exact as long as n * d < 2^32, which the host checks for the ranges used (k < C*R*S + BK by R*S, and
+// a tap index < R*S by S).  d == 1 has no 32-bit magic and is passed through.
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t magic, int d)
+{
+    return d == 1 ? n : __umulhi(n, magic);
+}
+
+// Loader of the generated operand.  Lanes run along the output pixels (contiguous q in x), each
+// thread keeps one column and walks k; k is uniform over a wave, so (c, r, s) and the offset of the
+// tap are scalar work, and only the halo test and the load itself are per lane.
+template <int BN, int BK, int NT, int LD>
+struct LoaderConvX {
+    static constexpr int KG = NT / BN;  // k rows loaded side by side
+    static constexpr int NQ = BK / KG;  // k rows per thread and tile
+    static_assert(NT % BN == 0 && BK % KG == 0 && BN % 64 == 0 && NQ >= 1, "one column per thread");
+    const float *xcol;  // x + n*C*H*W + ih0*W + iw0 (the tap (c=0, r=0, s=0); may lie in the halo)
+    int ih0, iw0;
+    bool col_ok;
+    int col, kg;
+    int knext;  // first k of the next tile to load
+    int H, W, S, RS, HW;
+    int64_t CRS;
+    uint32_t magic_RS, magic_S;
+    float v[NQ];
+
+    __device__ __forceinline__ void init(const ConvArgs &a, int64_t c0, int tid)
+    {
+        col = tid % BN;
+        kg = __builtin_amdgcn_readfirstlane(tid / BN);
+        knext = 0;
+        H = a.H; W = a.W; S = a.S; RS = a.RS; HW = a.H * a.W; CRS = a.CRS;
+        magic_RS = a.magic_RS; magic_S = a.magic_S;
+        int64_t gc = c0 + col;
+        col_ok = gc < a.NPQ;
+        gc = col_ok ? gc : a.NPQ - 1;
+        const int n = (int)(gc / a.PQ);
+        const int pq = (int)(gc - (int64_t)n * a.PQ);
+        const int p = pq / a.Q, q = pq - p * a.Q;
+        ih0 = p * a.stride_h - a.pad_h;
+        iw0 = q * a.stride_w - a.pad_w;
+        xcol = a.x + (int64_t)n * a.C * HW + (int64_t)ih0 * W + iw0;
+    }
+    __device__ __forceinline__ void load_rows(int kbase)
+    {
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) {
+            const uint32_t k = (uint32_t)(kbase + kg + it * KG);
+            const uint32_t c = fast_div(k, magic_RS, RS);
+            const uint32_t rs = k - c * (uint32_t)RS;
+            const uint32_t r = fast_div(rs, magic_S, S);
+            const uint32_t s = rs - r * (uint32_t)S;
+            const int off = (int)c * HW + (int)r * W + (int)s;
+            const bool ok = col_ok && (int64_t)k < CRS && (unsigned)(ih0 + (int)r) < (unsigned)H &&
+                            (unsigned)(iw0 + (int)s) < (unsigned)W;
+            v[it] = ok ? xcol[off] : 0.0f;
+        }
+    }
+    __device__ __forceinline__ void load()
+    {
+        load_rows(knext);
+        knext += BK;
+    }
+    __device__ __forceinline__ void load_tail(int) { load_rows(knext); }
+    __device__ __forceinline__ void store(float *Sm) const
+    {
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) Sm[(kg + it * KG) * LD + col] = v[it];
+    }
+};
+
+template <class Cfg, bool VEC>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(const ConvArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float smem[Cfg::STAGES * Cfg::STAGE_FLOATS];
+
+    const int tiles = a.tiles_m * a.tiles_n;
+    const int pid = xcd_contiguous_id(blockIdx.x, tiles);
+    int tm, tn;
+    tile_coords<8>(pid, a.tiles_m, a.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
+
+    const int T = (int)(a.CRS / Cfg::BK);
+    const int krem = (int)(a.CRS - (int64_t)T * Cfg::BK);
+
+    LoaderK<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, VEC> rl;
+    LoaderConvX<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB> cl;
+    rl.init(a.w, a.CRS, m0, a.Kout, 0, threadIdx.x);
+    cl.init(a, n0, threadIdx.x);
+
+    floatx16 acc[Cfg::MB][Cfg::NB];
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < Cfg::NB; ++bn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
+
+    mainloop<Cfg>(rl, cl, T, krem, acc, smem);
+
+    // Epilogue: the lane's NB columns are NB consecutive output pixels; when P*Q is a multiple of 4
+    // they lie in one image, 16-byte aligned.  Row j of the product is output channel j.
+    typedef typename VecOf<Cfg::NB>::type CV;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
+    const int64_t col = n0 + wn0 + Cfg::NB * i;
+    int64_t yoff[Cfg::NB];  // offset of (n, channel 0, p, q) for each owned column
+#pragma unroll
+    for (int bn = 0; bn < Cfg::NB; ++bn) {
+        int64_t gc = col + bn;
+        gc = gc < a.NPQ ? gc : a.NPQ - 1;
+        const int64_t n = gc / a.PQ;
+        yoff[bn] = n * a.Kout * a.PQ + (gc - n * a.PQ);
+    }
+    const bool full_vec = Cfg::NB == 4 && a.yvec && (col + Cfg::NB <= a.NPQ);
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+            if (row >= a.Kout) continue;
+            float out[Cfg::NB];
+#pragma unroll
+            for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] = a.alpha * acc[bm][bn][r];
+            if (full_vec) {
+                if constexpr (Cfg::NB == 4) {
+                    float *dst = a.y + yoff[0] + row * a.PQ;
+                    if (a.beta != 0.0f) {
+                        const CV old = *reinterpret_cast<const CV *>(dst);
+#pragma unroll
+                        for (int bn = 0; bn < 4; ++bn) out[bn] += a.beta * old[bn];
+                    }
+                    CV o;
+#pragma unroll
+                    for (int bn = 0; bn < 4; ++bn) o[bn] = out[bn];
+                    *reinterpret_cast<CV *>(dst) = o;
+                }
+            } else {
+#pragma unroll
+                for (int bn = 0; bn < Cfg::NB; ++bn) {
+                    if (col + bn < a.NPQ) {
+                        float *dst = a.y + yoff[bn] + row * a.PQ;
+                        float o = out[bn];
+                        if (a.beta != 0.0f) o += a.beta * *dst;
+                        *dst = o;
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <class Cfg>
+int launch_conv_cfg(const ConvArgs &a, bool vec, hipStream_t stream)
+{
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n)), block(Cfg::NT);
+    if (vec)
+        hipLaunchKernelGGL((conv_tile_kernel<Cfg, true>), grid, block, 0, stream, a);
+    else
+        hipLaunchKernelGGL((conv_tile_kernel<Cfg, false>), grid, block, 0, stream, a);
+    return (int)hipGetLastError();
+}
+
+}  // namespace dmath

@@ -1,0 +1,361 @@
+// C ABI of the library (see include/dmath.h): argument validation, the choice of tile
+// configuration / split-K factor from the problem shape, and the two small helper kernels
+// (scaling C when no product is needed, and the fixed-order reduction of split-K slices).
+#include "../../include/dmath.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+
+#include "configs.h"
+
+namespace dmath {
+namespace {
+
+constexpr int kNumCU = 256;  // MI355X
+
+struct ThreadState {
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    int force_cfg = -1;
+    int force_split = -1;
+    int last_error_arg = 0;
+};
+thread_local ThreadState g_state;
+
+const CfgDesc &desc(int i)
+{
+    switch (i) {
+        case 0: return cfg_desc<0>();
+        case 1: return cfg_desc<1>();
+        case 2: return cfg_desc<2>();
+        case 3: return cfg_desc<3>();
+        default: return cfg_desc<4>();
+    }
+}
+
+dmath_status fail(dmath_status s, int arg)
+{
+    g_state.last_error_arg = arg;
+    return s;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// C[row*ldc + col] = beta * C[...] (exact zero when beta == 0, whatever C held).
+__global__ void scale_kernel(float *C, int64_t ldc, int64_t M, int64_t N, float beta)
+{
+    const int64_t total = M * N;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = e / N, col = e - row * N;
+        float *dst = C + row * ldc + col;
+        *dst = (beta == 0.0f) ? 0.0f : beta * *dst;
+    }
+}
+
+// C = alpha * (slice 0 + slice 1 + ... in that order) + beta * C.  Slices are dense M x N.
+__global__ void splitk_reduce_kernel(const float *ws, int splits, int64_t slice_stride, float *C, int64_t ldc,
+                                     int64_t M, int64_t N, float alpha, float beta)
+{
+    const int64_t total = M * N;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = e / N, col = e - row * N;
+        float s = ws[e];
+        for (int z = 1; z < splits; ++z) s += ws[e + z * slice_stride];
+        float *dst = C + row * ldc + col;
+        float o = alpha * s;
+        if (beta != 0.0f) o += beta * *dst;
+        *dst = o;
+    }
+}
+
+// Vectorised form for N % 4 == 0, 16-byte aligned C rows.
+__global__ void splitk_reduce_kernel_v4(const float *ws, int splits, int64_t slice_stride, float *C, int64_t ldc,
+                                        int64_t M, int64_t N, float alpha, float beta)
+{
+    const int64_t nq = N / 4, total = M * nq;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = e / nq, col = (e - row * nq) * 4;
+        const float *src = ws + row * N + col;
+        floatx4 s = *reinterpret_cast<const floatx4 *>(src);
+        for (int z = 1; z < splits; ++z) s += *reinterpret_cast<const floatx4 *>(src + z * slice_stride);
+        float *dst = C + row * ldc + col;
+        floatx4 o = alpha * s;
+        if (beta != 0.0f) o += beta * *reinterpret_cast<const floatx4 *>(dst);
+        *reinterpret_cast<floatx4 *>(dst) = o;
+    }
+}
+
+struct Plan {
+    int cfg;
+    int splits;
+};
+
+// Shape-based choice (the paper's outlook names choosing the multiply algorithm from the shape as
+// future work; this is its one-GPU form).  Cost model in units of "MFMA time of one K step of a
+// 32x32 block": a compute unit runs its resident workgroups' tiles back to back, small wave tiles
+// pay for their lower operand reuse, split-K pays for writing and re-reading its slices.
+Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split)
+{
+    static const double eff[kNumCfg] = {1.0, 1.0, 1.0, 0.85, 0.55};
+    Plan best = {0, 1};
+    double best_cost = 1e300;
+    for (int c = 0; c < kNumCfg; ++c) {
+        const CfgDesc &d = desc(c);
+        const int64_t tiles = ceil_div(M, d.BM) * ceil_div(N, d.BN);
+        const int64_t ktiles = K / d.BK;
+        const int max_split = allow_split ? 16 : 1;
+        for (int s = 1; s <= max_split; s *= 2) {
+            if (s > 1 && ktiles / s < 8) break;
+            const double per_cu = (double)ceil_div(tiles * s, kNumCU);
+            const double tile_work = (double)d.BM * d.BN * ((double)K / s + 4.0 * d.BK) / eff[c];
+            double cost = per_cu * tile_work;
+            // slices: written once, read once, by all compute units together (~3 bytes/clk/CU effective
+            // against 256 flop/clk/CU of MFMA; expressed in the same unit as tile_work: element-steps)
+            if (s > 1) cost += (double)M * N * (s + 1) * 4.0 / kNumCU * 85.0 / 4.0 + 2.0e5;
+            if (cost < best_cost) {
+                best_cost = cost;
+                best = {c, s};
+            }
+        }
+    }
+    return best;
+}
+
+size_t split_bytes(int64_t M, int64_t N, int splits) { return (size_t)splits * (size_t)M * (size_t)N * sizeof(float); }
+
+Plan resolve_plan(int64_t M, int64_t N, int64_t K, bool measure_only)
+{
+    const ThreadState &st = g_state;
+    Plan p = choose_plan(M, N, K, true);
+    if (st.force_cfg >= 0) p.cfg = st.force_cfg;
+    if (st.force_split >= 1) p.splits = st.force_split;
+    // a forced pair may be impossible: every slice needs at least one whole K tile
+    const int64_t ktiles = K / desc(p.cfg).BK;
+    if (p.splits > 1 && ktiles < p.splits) p.splits = 1;
+    if (!measure_only && p.splits > 1 && (st.ws == nullptr || st.ws_bytes < split_bytes(M, N, p.splits))) {
+        // no room: best plan that needs no scratch
+        Plan q = choose_plan(M, N, K, false);
+        if (st.force_cfg >= 0) q.cfg = st.force_cfg;
+        q.splits = 1;
+        return q;
+    }
+    return p;
+}
+
+}  // namespace
+}  // namespace dmath
+
+using namespace dmath;
+
+extern "C" {
+
+const char *dmath_version(void) { return "dmath-mi355x 0.1 (gfx950, fp32 mfma)"; }
+
+const char *dmath_status_string(dmath_status s)
+{
+    switch (s) {
+        case DMATH_OK: return "ok";
+        case DMATH_ERR_INVALID_ARG: return "invalid argument";
+        case DMATH_ERR_NULL_PTR: return "null pointer";
+        case DMATH_ERR_UNSUPPORTED: return "unsupported";
+        case DMATH_ERR_LAUNCH: return "kernel launch failed";
+        case DMATH_ERR_WORKSPACE: return "bad workspace";
+    }
+    return "unknown status";
+}
+
+int dmath_last_error_arg(void) { return g_state.last_error_arg; }
+
+int dmath_num_configs(void) { return kNumCfg; }
+
+const char *dmath_config_name(int i) { return (i >= 0 && i < kNumCfg) ? desc(i).name : nullptr; }
+
+dmath_status dmath_set_override(int tile_config, int split_k)
+{
+    if (tile_config >= kNumCfg) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (split_k == 0 || split_k > 64) return fail(DMATH_ERR_INVALID_ARG, 2);
+    g_state.force_cfg = tile_config < 0 ? -1 : tile_config;
+    g_state.force_split = split_k < 0 ? -1 : split_k;
+    return DMATH_OK;
+}
+
+dmath_status dmath_set_workspace(void *device_ptr, size_t bytes)
+{
+    if (device_ptr == nullptr && bytes != 0) return fail(DMATH_ERR_WORKSPACE, 1);
+    if (!aligned16(device_ptr)) return fail(DMATH_ERR_WORKSPACE, 1);
+    g_state.ws = device_ptr;
+    g_state.ws_bytes = device_ptr ? bytes : 0;
+    return DMATH_OK;
+}
+
+size_t dmath_gemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K)
+{
+    (void)transA;
+    (void)transB;
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    const Plan p = resolve_plan(M, N, K, true);
+    return p.splits > 1 ? split_bytes(M, N, p.splits) : 0;
+}
+
+dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, float alpha,
+                        const float *A, int64_t lda, const float *B, int64_t ldb, float beta, float *C,
+                        int64_t ldc, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (transA != DMATH_OP_N && transA != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (transB != DMATH_OP_N && transB != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 2);
+    if (M < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
+    if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
+    if (K < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
+    const bool a_k = (transA == DMATH_OP_N);  // A contiguous along k
+    const bool b_k = (transB == DMATH_OP_T);  // B contiguous along k
+    const int64_t a_cols = a_k ? K : M, b_cols = b_k ? K : N;
+    if (lda < (a_cols > 1 ? a_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 8);
+    if (ldb < (b_cols > 1 ? b_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 10);
+    if (ldc < (N > 1 ? N : 1)) return fail(DMATH_ERR_INVALID_ARG, 13);
+    if (M == 0 || N == 0) return DMATH_OK;
+    if (C == nullptr) return fail(DMATH_ERR_NULL_PTR, 12);
+    const bool no_product = (K == 0 || alpha == 0.0f);
+    if (!no_product) {
+        if (A == nullptr) return fail(DMATH_ERR_NULL_PTR, 7);
+        if (B == nullptr) return fail(DMATH_ERR_NULL_PTR, 9);
+    }
+    // tile counts and in-kernel K tile counters are 32-bit
+    if (M > (int64_t)1 << 40 || N > (int64_t)1 << 40 || K > (int64_t)1 << 33) return fail(DMATH_ERR_UNSUPPORTED, 3);
+
+    if (no_product) {
+        if (beta == 1.0f) return DMATH_OK;
+        const int64_t total = M * N;
+        const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
+        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, C, ldc, M, N, beta);
+        return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
+    }
+
+    const Plan plan = resolve_plan(M, N, K, false);
+    const CfgDesc &d = desc(plan.cfg);
+    const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
+    if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
+
+    // 16-byte loads need aligned bases and rows; along the operand's own index also a whole number of quads.
+    bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
+    if (!a_k && M % 4 != 0) vec = false;
+    if (!b_k && N % 4 != 0) vec = false;
+
+    GemmArgs g;
+    g.A = A;
+    g.B = B;
+    g.lda = lda;
+    g.ldb = ldb;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.alpha = alpha;
+    g.beta = beta;
+    g.tiles_m = (int)tiles_m;
+    g.tiles_n = (int)tiles_n;
+    g.splits = plan.splits;
+    g.ktiles_per_split = (int)((K / d.BK) / plan.splits);
+    if (plan.splits > 1) {
+        g.C = static_cast<float *>(g_state.ws);
+        g.ldc = N;
+        g.slice_stride = M * N;
+        g.cvec = (N % 4 == 0) ? 1 : 0;
+    } else {
+        g.C = C;
+        g.ldc = ldc;
+        g.slice_stride = 0;
+        g.ktiles_per_split = (int)(K / d.BK);
+        g.cvec = (aligned16(C) && ldc % 4 == 0) ? 1 : 0;
+    }
+    if (d.gemm(g, a_k, b_k, vec, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+
+    if (plan.splits > 1) {
+        const bool v4 = (N % 4 == 0) && aligned16(C) && ldc % 4 == 0;
+        const int64_t items = v4 ? M * (N / 4) : M * N;
+        const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
+        if (v4)
+            hipLaunchKernelGGL(splitk_reduce_kernel_v4, dim3(blocks), dim3(256), 0, stream,
+                               static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
+        else
+            hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
+                               static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
+        if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    }
+    return DMATH_OK;
+}
+
+dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W, int64_t Kout, int64_t R, int64_t S,
+                              int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, float alpha,
+                              const float *x, const float *w, float beta, float *y, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (C < 0) return fail(DMATH_ERR_INVALID_ARG, 2);
+    if (H < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
+    if (W < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
+    if (Kout < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
+    if (R < 1) return fail(DMATH_ERR_INVALID_ARG, 6);
+    if (S < 1) return fail(DMATH_ERR_INVALID_ARG, 7);
+    if (pad_h < 0) return fail(DMATH_ERR_INVALID_ARG, 8);
+    if (pad_w < 0) return fail(DMATH_ERR_INVALID_ARG, 9);
+    if (stride_h < 1) return fail(DMATH_ERR_INVALID_ARG, 10);
+    if (stride_w < 1) return fail(DMATH_ERR_INVALID_ARG, 11);
+    if (H + 2 * pad_h < R) return fail(DMATH_ERR_INVALID_ARG, 6);
+    if (W + 2 * pad_w < S) return fail(DMATH_ERR_INVALID_ARG, 7);
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1;
+    const int64_t Q = (W + 2 * pad_w - S) / stride_w + 1;
+    const int64_t PQ = P * Q, NPQ = N * PQ, CRS = C * R * S;
+    if (NPQ == 0 || Kout == 0) return DMATH_OK;
+    if (y == nullptr) return fail(DMATH_ERR_NULL_PTR, 16);
+    const bool no_product = (CRS == 0 || alpha == 0.0f);
+    if (!no_product) {
+        if (x == nullptr) return fail(DMATH_ERR_NULL_PTR, 13);
+        if (w == nullptr) return fail(DMATH_ERR_NULL_PTR, 14);
+    }
+    // in-kernel tap offsets, magic divisions and tile counters are 32-bit
+    const int64_t lim = (int64_t)1 << 31;
+    if (C * H * W >= lim || PQ >= lim || (CRS + 64) * R * S >= ((int64_t)1 << 32) || R * S * S >= lim ||
+        Kout * PQ >= ((int64_t)1 << 40) || pad_h >= lim || pad_w >= lim || stride_h >= lim || stride_w >= lim ||
+        N >= lim || Kout >= lim)
+        return fail(DMATH_ERR_UNSUPPORTED, 2);
+
+    if (no_product) {
+        if (beta == 1.0f) return DMATH_OK;
+        const int64_t total = NPQ * Kout;
+        const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
+        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, y, total, (int64_t)1, total, beta);
+        return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
+    }
+
+    int cfg = g_state.force_cfg >= 0 ? g_state.force_cfg : choose_plan(Kout, NPQ, CRS, false).cfg;
+    const CfgDesc &d = desc(cfg);
+    const int64_t tiles_m = ceil_div(Kout, d.BM), tiles_n = ceil_div(NPQ, d.BN);
+    if (tiles_m * tiles_n > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 1);
+
+    ConvArgs a;
+    a.x = x;
+    a.w = w;
+    a.y = y;
+    a.N = (int)N; a.C = (int)C; a.H = (int)H; a.W = (int)W; a.Kout = (int)Kout;
+    a.R = (int)R; a.S = (int)S; a.P = (int)P; a.Q = (int)Q;
+    a.pad_h = (int)pad_h; a.pad_w = (int)pad_w; a.stride_h = (int)stride_h; a.stride_w = (int)stride_w;
+    a.RS = (int)(R * S);
+    a.PQ = (int)PQ;
+    a.CRS = CRS;
+    a.NPQ = NPQ;
+    a.magic_RS = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)a.RS - 1) / (uint64_t)a.RS);
+    a.magic_S = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)S - 1) / (uint64_t)S);
+    a.alpha = alpha;
+    a.beta = beta;
+    a.tiles_m = (int)tiles_m;
+    a.tiles_n = (int)tiles_n;
+    a.yvec = (aligned16(y) && PQ % 4 == 0) ? 1 : 0;
+    const bool vec = aligned16(w) && CRS % 4 == 0;
+    if (d.conv(a, vec, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    return DMATH_OK;
+}
+
+}  // extern "C"

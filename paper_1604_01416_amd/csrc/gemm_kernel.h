@@ -1,0 +1,153 @@
+// GEMM kernel: C = alpha * op(A) * op(B) + beta * C on one BM x BN tile per workgroup, and its
+// host-side launcher template.  Included by one translation unit per tile configuration.
+#pragma once
+#include "tile_core.h"
+
+namespace dmath {
+
+struct GemmArgs {
+    const float *A;
+    const float *B;
+    float *C;         // destination: C itself, or the split-K workspace (then ldc = N, raw partial sums)
+    int64_t lda, ldb, ldc;
+    int64_t M, N, K;
+    float alpha, beta;
+    int tiles_m, tiles_n;
+    int splits;       // number of K slices; slice z covers K tiles [z*tiles_per_split, ...)
+    int ktiles_per_split;
+    int cvec;         // C rows allow aligned NB-wide vector access
+    int64_t slice_stride;  // floats between consecutive workspace slices (M*N), 0 when splits == 1
+};
+
+template <class Cfg, bool ROWS_K, bool VEC>
+struct RowLoaderSel {
+    typedef LoaderK<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, VEC> type;
+};
+template <class Cfg, bool VEC>
+struct RowLoaderSel<Cfg, false, VEC> {
+    typedef LoaderMN<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, VEC> type;
+};
+template <class Cfg, bool COLS_K, bool VEC>
+struct ColLoaderSel {
+    typedef LoaderK<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, VEC> type;
+};
+template <class Cfg, bool VEC>
+struct ColLoaderSel<Cfg, false, VEC> {
+    typedef LoaderMN<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, VEC> type;
+};
+
+// A_KCONTIG: A stored M x K (transA == N).  B_KCONTIG: B stored N x K (transB == T).
+// VEC: every 16-byte global load of A and B is aligned and wholly inside the matrix.
+template <class Cfg, bool A_KCONTIG, bool B_KCONTIG, bool VEC>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(const GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) float smem[Cfg::STAGES * Cfg::STAGE_FLOATS];
+
+    const int tiles = g.tiles_m * g.tiles_n;
+    const int pid = xcd_contiguous_id(blockIdx.x, tiles * g.splits);
+    const int z = pid / tiles;
+    int tm, tn;
+    tile_coords<8>(pid - z * tiles, g.tiles_m, g.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
+
+    // K range of this slice: whole K tiles, the last slice also takes the partial one.
+    const int ktiles_total = (int)(g.K / Cfg::BK);
+    const int kt0 = z * g.ktiles_per_split;
+    int T = ktiles_total - kt0;
+    T = T < g.ktiles_per_split ? T : g.ktiles_per_split;
+    if (z == g.splits - 1) T = ktiles_total - kt0;
+    T = T < 0 ? 0 : T;
+    const int krem = (z == g.splits - 1) ? (int)(g.K - (int64_t)ktiles_total * Cfg::BK) : 0;
+    const int64_t k0 = (int64_t)kt0 * Cfg::BK;
+
+    typename RowLoaderSel<Cfg, A_KCONTIG, VEC>::type rl;
+    typename ColLoaderSel<Cfg, B_KCONTIG, VEC>::type cl;
+    rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x);
+    cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x);
+
+    floatx16 acc[Cfg::MB][Cfg::NB];
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < Cfg::NB; ++bn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
+
+    mainloop<Cfg>(rl, cl, T, krem, acc, smem);
+
+    // Epilogue.  Lane (i, h) owns, for block row bm and accumulator register r, the NB consecutive
+    // columns n0 + wn0 + NB*i .. of row m0 + wm0 + MB*(8*(r/4) + 4*h + r%4) + bm.
+    typedef typename VecOf<Cfg::NB>::type CV;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
+    const int64_t col = n0 + wn0 + Cfg::NB * i;
+    const bool partial = g.splits > 1;
+    float *Cz = g.C + (int64_t)z * g.slice_stride;
+    const float alpha = partial ? 1.0f : g.alpha;
+    const float beta = partial ? 0.0f : g.beta;
+    const bool full_vec = g.cvec && (col + Cfg::NB <= g.N);
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+            if (row >= g.M) continue;
+            float *dst = Cz + row * g.ldc + col;
+            float out[Cfg::NB];
+#pragma unroll
+            for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] = alpha * acc[bm][bn][r];
+            if (full_vec) {
+                CV o;
+                if constexpr (Cfg::NB == 1) {
+                    o = out[0];
+                    if (beta != 0.0f) o += beta * *dst;
+                    *dst = o;
+                } else {
+                    if (beta != 0.0f) {
+                        const CV old = *reinterpret_cast<const CV *>(dst);
+#pragma unroll
+                        for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] += beta * old[bn];
+                    }
+#pragma unroll
+                    for (int bn = 0; bn < Cfg::NB; ++bn) o[bn] = out[bn];
+                    *reinterpret_cast<CV *>(dst) = o;
+                }
+            } else {
+#pragma unroll
+                for (int bn = 0; bn < Cfg::NB; ++bn) {
+                    if (col + bn < g.N) {
+                        float o = out[bn];
+                        if (beta != 0.0f) o += beta * dst[bn];
+                        dst[bn] = o;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Host side: pick the instantiation for the operand orientations and alignment, and launch.
+// Returns the hipError_t of the launch as int.
+template <class Cfg>
+int launch_gemm_cfg(const GemmArgs &g, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t stream)
+{
+    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n * g.splits)), block(Cfg::NT);
+#define DMATH_LAUNCH(AK, BK_, V) \
+    hipLaunchKernelGGL((gemm_tile_kernel<Cfg, AK, BK_, V>), grid, block, 0, stream, g)
+    if (vec) {
+        if (a_kcontig && b_kcontig) DMATH_LAUNCH(true, true, true);
+        else if (a_kcontig) DMATH_LAUNCH(true, false, true);
+        else if (b_kcontig) DMATH_LAUNCH(false, true, true);
+        else DMATH_LAUNCH(false, false, true);
+    } else {
+        if (a_kcontig && b_kcontig) DMATH_LAUNCH(true, true, false);
+        else if (a_kcontig) DMATH_LAUNCH(true, false, false);
+        else if (b_kcontig) DMATH_LAUNCH(false, true, false);
+        else DMATH_LAUNCH(false, false, false);
+    }
+#undef DMATH_LAUNCH
+    return (int)hipGetLastError();
+}
+
+}  // namespace dmath

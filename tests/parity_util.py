@@ -1,0 +1,124 @@
+"""Shared helpers of the GPU parity tests: build stored operands, run the library through its
+C ABI binding, run the FP64 oracle on the same bytes, and compare under the contract bound
+
+    |gpu - ref| <= 4 * K * 2^-24 * mag + 1e-6      (mag = |alpha| |A||B| + |beta| |C0|)
+"""
+import numpy as np
+
+import oracle
+
+GUARD = np.float32(np.nan)
+
+
+def stored(op_matrix, trans, ld_extra=0, lead=0, tail=8):
+    """Flat FP32 buffer holding op_matrix (N) or its transpose (T) with row padding.
+
+    Returns (flat, offset, ld): the matrix starts at flat[offset]; padding, lead and tail are NaN.
+    """
+    m = np.ascontiguousarray(op_matrix.T if trans else op_matrix, dtype=np.float32)
+    rows, cols = m.shape
+    ld = max(1, cols + ld_extra)
+    flat = np.full(lead + rows * ld + tail, GUARD, dtype=np.float32)
+    view = flat[lead:lead + rows * ld].reshape(rows, ld)
+    view[:, :cols] = m
+    return flat, lead, ld
+
+
+def check_bound(gpu, ref, mag, K, what=""):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    err = np.abs(gpu - ref)
+    bnd = oracle.bound(K, mag)
+    bad = ~(err <= bnd)          # also catches NaN
+    if bad.any():
+        idx = np.argwhere(bad)[:5]
+        raise AssertionError("%s: %d of %d elements outside the bound; first at %s, err %s, bound %s, gpu %s, ref %s"
+                             % (what, int(bad.sum()), bad.size, idx.tolist(),
+                                err[bad][:5], bnd[bad][:5], gpu[bad][:5], ref[bad][:5]))
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = np.where(bnd > 0, err / bnd, 0.0)
+    return float(ratio.max()) if ratio.size else 0.0
+
+
+def run_gemm_case(dm, torch, tA, tB, M, N, K, alpha=1.0, beta=0.0, ld_extra=(0, 0, 0), lead=(0, 0, 0),
+                  seed=0, ints=False, c_nan=False, exact=False):
+    """One dmath_gemm call against the oracle, with a NaN guard frame around every operand.
+
+    ints: small-integer entries (every FP32 summation order is exact) -> with exact=True the GPU
+    result must equal the oracle bit for bit.  c_nan: C starts as NaN (only legal with beta == 0).
+    """
+    rng = np.random.default_rng(seed)
+    if ints:
+        A = rng.integers(-4, 5, size=(M, K)).astype(np.float32)
+        B = rng.integers(-4, 5, size=(K, N)).astype(np.float32)
+        C0 = rng.integers(-4, 5, size=(M, N)).astype(np.float32)
+    else:
+        A = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+        B = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+        C0 = rng.standard_normal((M, N)).astype(np.float32)
+    if c_nan:
+        assert beta == 0.0
+        C0[:] = np.nan
+    a_flat, a_off, lda = stored(A, tA, ld_extra[0], lead[0])
+    b_flat, b_off, ldb = stored(B, tB, ld_extra[1], lead[1])
+    c_flat, c_off, ldc = stored(C0, 0, ld_extra[2], lead[2])
+    dA = torch.from_numpy(a_flat).cuda()
+    dB = torch.from_numpy(b_flat).cuda()
+    dC = torch.from_numpy(c_flat).cuda()
+    st = dm.dmath_gemm(tA, tB, M, N, K, alpha, dA[a_off:], lda, dB[b_off:], ldb, beta, dC[c_off:], ldc)
+    assert st == dm.OK, (dm.dmath_status_string(st), dm.dmath_last_error_arg())
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    ref, mag = oracle.gemm(tA, tB, M, N, K, alpha, a_flat[a_off:], lda, b_flat[b_off:], ldb, beta,
+                           c_flat[c_off:] if beta != 0.0 else None, ldc)
+    got = out[c_off:c_off + M * ldc].reshape(M, ldc) if M > 0 else np.zeros((0, ldc), np.float32)
+    # guard frame: everything that is not an element of C must still be NaN
+    if M > 0:
+        assert np.isnan(got[:, N:]).all(), "row padding of C was written"
+    assert np.isnan(out[:c_off]).all() and np.isnan(out[c_off + M * ldc:]).all(), "wrote outside C"
+    if M == 0 or N == 0:
+        return 0.0
+    if exact:
+        assert np.array_equal(got[:, :N].astype(np.float64), ref), "integer case must be bit-exact"
+        return 0.0
+    return check_bound(got[:, :N], ref, mag, max(K, 1), "gemm t%d%d %dx%dx%d" % (tA, tB, M, N, K))
+
+
+def run_conv_case(dm, torch, N, C, H, W, Kout, R, S, pad, stride, alpha=1.0, beta=0.0, seed=0, ints=False,
+                  exact=False, lead=0):
+    rng = np.random.default_rng(seed)
+    P = (H + 2 * pad[0] - R) // stride[0] + 1
+    Q = (W + 2 * pad[1] - S) // stride[1] + 1
+    if ints:
+        x = rng.integers(-3, 4, size=(N, C, H, W)).astype(np.float32)
+        w = rng.integers(-3, 4, size=(Kout, C, R, S)).astype(np.float32)
+        y0 = rng.integers(-3, 4, size=(N, Kout, P, Q)).astype(np.float32)
+    else:
+        x = np.maximum(rng.standard_normal((N, C, H, W)), 0).astype(np.float32)
+        w = (rng.standard_normal((Kout, C, R, S)) * np.sqrt(2.0 / max(1, C * R * S))).astype(np.float32)
+        y0 = rng.standard_normal((N, Kout, P, Q)).astype(np.float32)
+    if beta == 0.0:
+        y0[:] = np.nan
+    tail = 8
+
+    def flat_of(t):
+        f = np.full(lead + t.size + tail, GUARD, dtype=np.float32)
+        f[lead:lead + t.size] = t.reshape(-1)
+        return f
+
+    xf, wf, yf = flat_of(x), flat_of(w), flat_of(y0)
+    dx, dw, dy = (torch.from_numpy(f).cuda() for f in (xf, wf, yf))
+    st = dm.dmath_conv2d_fwd(N, C, H, W, Kout, R, S, pad[0], pad[1], stride[0], stride[1], alpha,
+                             dx[lead:], dw[lead:], beta, dy[lead:])
+    assert st == dm.OK, (dm.dmath_status_string(st), dm.dmath_last_error_arg())
+    torch.cuda.synchronize()
+    out = dy.cpu().numpy()
+    assert np.isnan(out[:lead]).all() and np.isnan(out[lead + y0.size:]).all(), "wrote outside y"
+    got = out[lead:lead + y0.size].reshape(y0.shape)
+    ref, mag = oracle.conv2d_fwd(x, w, pad=pad, stride=stride, alpha=alpha, beta=beta,
+                                 y0=y0 if beta != 0.0 else None)
+    if got.size == 0:
+        return 0.0
+    if exact:
+        assert np.array_equal(got.astype(np.float64), ref), "integer case must be bit-exact"
+        return 0.0
+    return check_bound(got, ref, mag, max(1, C * R * S), "conv %s" % ((N, C, H, W, Kout, R, S, pad, stride),))

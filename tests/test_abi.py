@@ -1,0 +1,112 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol include/dmath.h declares,
+and rejects bad arguments before anything is launched (no GPU needed for any call here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def dm():
+    from paper_1604_01416_amd import build
+    build.build(force=False)
+    from paper_1604_01416_amd import dmath
+    return dmath
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "dmath.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dmath_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(dm):
+    names = _declared_functions()
+    assert "dmath_gemm" in names and "dmath_conv2d_fwd" in names and len(names) >= 10
+    lib = ctypes.CDLL(dm.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(dm.EXPORTS) == names
+
+
+def test_version_and_strings(dm):
+    assert "gfx950" in dm.dmath_version()
+    assert dm.dmath_status_string(dm.OK) == "ok"
+    assert dm.dmath_num_configs() >= 1
+    assert dm.dmath_config_name(0)
+    assert dm.dmath_config_name(dm.dmath_num_configs()) is None
+
+
+def test_gemm_argument_validation(dm):
+    g = dm.dmath_gemm
+    fake = 4096  # never dereferenced: every call below fails validation or returns early
+    assert g(2, 0, 4, 4, 4, 1.0, fake, 4, fake, 4, 0.0, fake, 4, stream=0) == dm.ERR_INVALID_ARG
+    assert dm.dmath_last_error_arg() == 1
+    assert g(0, 7, 4, 4, 4, 1.0, fake, 4, fake, 4, 0.0, fake, 4, stream=0) == dm.ERR_INVALID_ARG
+    assert dm.dmath_last_error_arg() == 2
+    assert g(0, 0, -1, 4, 4, 1.0, fake, 4, fake, 4, 0.0, fake, 4, stream=0) == dm.ERR_INVALID_ARG
+    assert dm.dmath_last_error_arg() == 3
+    assert g(0, 0, 4, -1, 4, 1.0, fake, 4, fake, 4, 0.0, fake, 4, stream=0) == dm.ERR_INVALID_ARG
+    assert g(0, 0, 4, 4, -1, 1.0, fake, 4, fake, 4, 0.0, fake, 4, stream=0) == dm.ERR_INVALID_ARG
+    # leading dimensions: NN needs lda >= K, ldb >= N, ldc >= N
+    assert g(0, 0, 4, 5, 6, 1.0, fake, 5, fake, 5, 0.0, fake, 5, stream=0) == dm.ERR_INVALID_ARG
+    assert dm.dmath_last_error_arg() == 8
+    assert g(0, 0, 4, 5, 6, 1.0, fake, 6, fake, 4, 0.0, fake, 5, stream=0) == dm.ERR_INVALID_ARG
+    assert dm.dmath_last_error_arg() == 10
+    assert g(0, 0, 4, 5, 6, 1.0, fake, 6, fake, 5, 0.0, fake, 4, stream=0) == dm.ERR_INVALID_ARG
+    assert dm.dmath_last_error_arg() == 13
+    # transposed: A stored K x M needs lda >= M, B stored N x K needs ldb >= K
+    assert g(1, 1, 4, 5, 6, 1.0, fake, 3, fake, 6, 0.0, fake, 5, stream=0) == dm.ERR_INVALID_ARG
+    assert dm.dmath_last_error_arg() == 8
+    assert g(1, 1, 4, 5, 6, 1.0, fake, 4, fake, 5, 0.0, fake, 5, stream=0) == dm.ERR_INVALID_ARG
+    assert dm.dmath_last_error_arg() == 10
+    # null pointers
+    assert g(0, 0, 4, 4, 4, 1.0, None, 4, fake, 4, 0.0, fake, 4, stream=0) == dm.ERR_NULL_PTR
+    assert dm.dmath_last_error_arg() == 7
+    assert g(0, 0, 4, 4, 4, 1.0, fake, 4, None, 4, 0.0, fake, 4, stream=0) == dm.ERR_NULL_PTR
+    assert g(0, 0, 4, 4, 4, 1.0, fake, 4, fake, 4, 0.0, None, 4, stream=0) == dm.ERR_NULL_PTR
+    assert dm.dmath_last_error_arg() == 12
+    # empty output: nothing to do, even with null pointers
+    assert g(0, 0, 0, 4, 4, 1.0, None, 4, None, 4, 0.0, None, 4, stream=0) == dm.OK
+    assert g(0, 0, 4, 0, 4, 1.0, None, 4, None, 1, 0.0, None, 1, stream=0) == dm.OK
+    # K == 0 with beta == 1 leaves C alone and needs neither A nor B
+    assert g(0, 0, 4, 4, 0, 1.0, None, 1, None, 4, 1.0, fake, 4, stream=0) == dm.OK
+
+
+def test_conv_argument_validation(dm):
+    c = dm.dmath_conv2d_fwd
+    fake = 4096
+    ok_args = [1, 2, 5, 5, 3, 3, 3, 1, 1, 1, 1]
+    for pos, bad in [(0, -1), (1, -1), (2, -1), (3, -1), (4, -1), (5, 0), (6, 0), (7, -1), (8, -1), (9, 0), (10, 0)]:
+        args = list(ok_args)
+        args[pos] = bad
+        assert c(*args, 1.0, fake, fake, 0.0, fake, stream=0) == dm.ERR_INVALID_ARG, pos
+        assert dm.dmath_last_error_arg() == pos + 1
+    # filter larger than the padded input
+    assert c(1, 2, 2, 5, 3, 5, 3, 1, 1, 1, 1, 1.0, fake, fake, 0.0, fake, stream=0) == dm.ERR_INVALID_ARG
+    assert c(*ok_args, 1.0, None, fake, 0.0, fake, stream=0) == dm.ERR_NULL_PTR
+    assert dm.dmath_last_error_arg() == 13
+    assert c(*ok_args, 1.0, fake, None, 0.0, fake, stream=0) == dm.ERR_NULL_PTR
+    assert c(*ok_args, 1.0, fake, fake, 0.0, None, stream=0) == dm.ERR_NULL_PTR
+    assert dm.dmath_last_error_arg() == 16
+    # empty batch: no-op
+    assert c(0, 2, 5, 5, 3, 3, 3, 1, 1, 1, 1, 1.0, None, None, 0.0, None, stream=0) == dm.OK
+
+
+def test_workspace_and_override_api(dm):
+    assert dm.dmath_set_workspace(None, 16) == dm.ERR_WORKSPACE
+    assert dm.dmath_set_workspace(4100, 64) == dm.ERR_WORKSPACE      # not 16-byte aligned
+    assert dm.dmath_set_workspace(None, 0) == dm.OK
+    assert dm.dmath_gemm_workspace_bytes(0, 0, 0, 4, 4) == 0
+    big = dm.dmath_gemm_workspace_bytes(0, 0, 4096, 4096, 4096)
+    assert big == 0                                                  # enough tiles: no split-K
+    skinny = dm.dmath_gemm_workspace_bytes(0, 0, 256, 4096, 4096)
+    assert skinny % (256 * 4096 * 4) == 0
+    assert dm.dmath_set_override(dm.dmath_num_configs(), 1) == dm.ERR_INVALID_ARG
+    assert dm.dmath_set_override(0, 0) == dm.ERR_INVALID_ARG
+    assert dm.dmath_set_override(0, 4) == dm.OK
+    assert dm.dmath_gemm_workspace_bytes(0, 0, 256, 4096, 4096) == 4 * 256 * 4096 * 4
+    assert dm.dmath_set_override(-1, -1) == dm.OK

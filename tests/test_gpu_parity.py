@@ -1,0 +1,336 @@
+"""GPU parity: the HIP library, called through its C ABI, against the FP64 CPU oracle.
+
+Small cases are compared element by element (sizes span several tiles and a ragged tail, every
+transpose form, every tile configuration, aligned and unaligned operands, a NaN guard frame around
+C); the five benchmark configurations run at full size in the launch configuration bench.py times,
+and are compared on every element where the oracle finishes in seconds and on sampled rows /
+columns / outputs otherwise.  Bound: |gpu - ref| <= 4*K*2^-24*mag + 1e-6; bit-exact where the
+inputs are small integers (every FP32 summation order is then exact).
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1604_01416_amd import workloads
+from parity_util import check_bound, run_conv_case, run_gemm_case
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    return t
+
+
+@pytest.fixture(scope="module")
+def dm(torch):
+    from paper_1604_01416_amd import dmath
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")      # 64 MiB split-K scratch
+    dmath.check(dmath.dmath_set_workspace(ws, ws.numel()))
+    dmath._test_workspace = ws                                       # keep it alive
+    yield dmath
+    dmath.dmath_set_override(-1, -1)
+    dmath.dmath_set_workspace(None, 0)
+
+
+@pytest.fixture(autouse=True)
+def _auto_plan(dm):
+    dm.dmath_set_override(-1, -1)
+    yield
+    dm.dmath_set_override(-1, -1)
+
+
+TRANS = list(itertools.product((0, 1), (0, 1)))
+
+
+# ------------------------------------------------------------------ first: does the MFMA layout hold
+
+def test_identity_and_index_matrices_pin_the_tile_layout(dm, torch):
+    """A = I gives C = B exactly, B = I gives C = A exactly: any wrong lane/register mapping of the
+    MFMA operands or accumulators moves an element and fails this."""
+    for cfg in range(dm.dmath_num_configs()):
+        dm.dmath_set_override(cfg, 1)
+        n = 320
+        idx = (np.arange(n * n, dtype=np.float32).reshape(n, n) % 4093) - 2000.0
+        eye = np.eye(n, dtype=np.float32)
+        for A, B, want in ((eye, idx, idx), (idx, eye, idx)):
+            dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+            dC = torch.full((n, n), float("nan"), device="cuda")
+            dm.check(dm.dmath_gemm(0, 0, n, n, n, 1.0, dA, n, dB, n, 0.0, dC, n))
+            torch.cuda.synchronize()
+            assert np.array_equal(dC.cpu().numpy(), want), dm.dmath_config_name(cfg)
+
+
+# ------------------------------------------------------------------ small cases, element by element
+
+SHAPES = [(1, 1, 1), (3, 5, 7), (17, 33, 19), (64, 64, 64), (127, 129, 65), (255, 257, 130),
+          (300, 200, 100), (513, 260, 48)]
+
+
+@pytest.mark.parametrize("tA,tB", TRANS)
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_gemm_small_auto(dm, torch, tA, tB, M, N, K):
+    run_gemm_case(dm, torch, tA, tB, M, N, K, alpha=1.0, beta=0.0, seed=M + N + K, c_nan=True)
+    run_gemm_case(dm, torch, tA, tB, M, N, K, alpha=-0.75, beta=1.5, ld_extra=(3, 5, 2), lead=(1, 3, 1),
+                  seed=M * 3 + K)
+
+
+@pytest.mark.parametrize("cfg", range(5))
+@pytest.mark.parametrize("tA,tB", TRANS)
+def test_gemm_every_config_aligned_and_unaligned(dm, torch, cfg, tA, tB):
+    if cfg >= dm.dmath_num_configs():
+        pytest.skip("no such configuration")
+    dm.dmath_set_override(cfg, 1)
+    # multiples of 4 and 16-byte aligned: vector path, ragged tiles in M, N and K
+    run_gemm_case(dm, torch, tA, tB, 388, 516, 200, alpha=1.0, beta=0.0, ld_extra=(4, 8, 12), lead=(4, 8, 4),
+                  seed=cfg, c_nan=True)
+    run_gemm_case(dm, torch, tA, tB, 388, 516, 203, alpha=0.5, beta=-2.0, ld_extra=(5, 0, 4), lead=(0, 4, 0),
+                  seed=cfg + 10)
+    # odd sizes, odd leading dimensions, misaligned bases: scalar path
+    run_gemm_case(dm, torch, tA, tB, 259, 131, 77, alpha=2.0, beta=1.0, ld_extra=(1, 2, 3), lead=(1, 2, 3),
+                  seed=cfg + 20)
+    # integer entries: bit-exact
+    run_gemm_case(dm, torch, tA, tB, 260, 136, 96, alpha=1.0, beta=1.0, seed=cfg + 30, ints=True, exact=True)
+
+
+@pytest.mark.parametrize("cfg,split", [(0, 2), (3, 4), (4, 8), (4, 3)])
+@pytest.mark.parametrize("tA,tB", TRANS)
+def test_gemm_split_k(dm, torch, cfg, split, tA, tB):
+    dm.dmath_set_override(cfg, split)
+    run_gemm_case(dm, torch, tA, tB, 130, 264, 1000, alpha=1.25, beta=0.5, ld_extra=(0, 0, 4), seed=split)
+    run_gemm_case(dm, torch, tA, tB, 67, 93, 515, alpha=1.0, beta=0.0, ld_extra=(1, 1, 1), lead=(1, 1, 1),
+                  seed=split + 1, c_nan=True)
+    run_gemm_case(dm, torch, tA, tB, 64, 128, 512, alpha=1.0, beta=1.0, seed=split + 2, ints=True, exact=True)
+
+
+def test_gemm_quick_returns_and_nan_conventions(dm, torch):
+    rng = np.random.default_rng(5)
+    M, N, K = 70, 50, 40
+    C0 = rng.standard_normal((M, N)).astype(np.float32)
+    nanA = torch.full((M, K), float("nan"), device="cuda")
+    nanB = torch.full((K, N), float("nan"), device="cuda")
+    # alpha == 0: A, B not read, C = beta*C
+    dC = torch.from_numpy(C0).cuda()
+    dm.check(dm.dmath_gemm(0, 0, M, N, K, 0.0, nanA, K, nanB, N, -2.0, dC, N))
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), -2.0 * C0)
+    # K == 0, beta == 0: exact zeros even over NaN
+    dC = torch.full((M, N), float("nan"), device="cuda")
+    dm.check(dm.dmath_gemm(0, 0, M, N, 0, 1.0, None, 1, None, N, 0.0, dC, N))
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), np.zeros((M, N), np.float32))
+    # K == 0, beta == 1: untouched; and with a padded C only the M x N window is scaled
+    dC = torch.from_numpy(C0).cuda()
+    dm.check(dm.dmath_gemm(0, 0, M, N, 0, 1.0, None, 1, None, N, 1.0, dC, N))
+    dm.check(dm.dmath_gemm(0, 0, M, N - 10, 0, 1.0, None, 1, None, N, 3.0, dC, N))
+    torch.cuda.synchronize()
+    want = C0.copy()
+    want[:, :N - 10] *= 3.0
+    assert np.array_equal(dC.cpu().numpy(), want)
+    # empty output
+    assert dm.dmath_gemm(0, 0, 0, N, K, 1.0, nanA, K, nanB, N, 0.0, dC, N) == dm.OK
+
+
+def test_gemm_run_to_run_bits(dm, torch):
+    wl = workloads.gemm_square(512, 77, "determinism")
+    dA, dB = torch.from_numpy(wl.arrays["A"]).cuda(), torch.from_numpy(wl.arrays["B"]).cuda()
+    outs = []
+    for cfg, split in [(-1, -1), (-1, -1), (4, 4), (4, 4)]:
+        dm.dmath_set_override(cfg, split)
+        dC = torch.empty((512, 512), device="cuda")
+        dm.check(dm.dmath_gemm(0, 0, 512, 512, 512, 1.0, dA, 512, dB, 512, 0.0, dC, 512))
+        torch.cuda.synchronize()
+        outs.append(dC.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])
+    assert np.array_equal(outs[2], outs[3])
+
+
+def test_gemm_on_a_side_stream(dm, torch):
+    s = torch.cuda.Stream()
+    wl = workloads.gemm_square(256, 3, "stream")
+    dA, dB = torch.from_numpy(wl.arrays["A"]).cuda(), torch.from_numpy(wl.arrays["B"]).cuda()
+    dC = torch.empty((256, 256), device="cuda")
+    torch.cuda.synchronize()
+    dm.check(dm.dmath_gemm(0, 0, 256, 256, 256, 1.0, dA, 256, dB, 256, 0.0, dC, 256, stream=s))
+    s.synchronize()
+    ref, mag = oracle.gemm(0, 0, 256, 256, 256, 1.0, wl.arrays["A"], 256, wl.arrays["B"], 256)
+    check_bound(dC.cpu().numpy(), ref, mag, 256, "side stream")
+
+
+# ------------------------------------------------------------------ the five configurations
+
+def _run_workload(dm, torch, wl):
+    dev = {k: torch.from_numpy(v).cuda() for k, v in wl.arrays.items()}
+    for c in wl.calls:
+        dm.check(dm.dmath_gemm(c.transA, c.transB, c.M, c.N, c.K, c.alpha, dev[c.A], c.lda, dev[c.B], c.ldb,
+                               c.beta, dev[c.C], c.ldc))
+    torch.cuda.synchronize()
+    return {k: dev[k].cpu().numpy() for k in wl.outputs}
+
+
+def test_config1_gemm_256(dm, torch):
+    wl = workloads.config1()
+    out = _run_workload(dm, torch, wl)
+    c = wl.calls[0]
+    ref, mag = oracle.gemm(0, 0, c.M, c.N, c.K, 1.0, wl.arrays["A"], c.lda, wl.arrays["B"], c.ldb)
+    r = check_bound(out["C"], ref, mag, c.K, "config 1")
+    print("config 1 max err/bound %.3g" % r)
+
+
+def _sample_rows_cols(rng, M, N, nrows, ncols):
+    rows = np.sort(rng.choice(M, size=min(nrows, M), replace=False))
+    cols = np.sort(rng.choice(N, size=min(ncols, N), replace=False))
+    # always include the corners of the matrix and of the first / last tiles
+    rows = np.unique(np.concatenate([rows, [0, 1, M // 2, M - 2, M - 1]]))
+    cols = np.unique(np.concatenate([cols, [0, 1, N // 2, N - 2, N - 1]]))
+    pi = np.concatenate([np.repeat(rows, N), np.tile(np.arange(M), len(cols))])
+    pj = np.concatenate([np.tile(np.arange(N), len(rows)), np.repeat(cols, M)])
+    return pi, pj
+
+
+def test_config2_gemm_4096(dm, torch):
+    wl = workloads.config2()
+    out = _run_workload(dm, torch, wl)
+    c = wl.calls[0]
+    pi, pj = _sample_rows_cols(np.random.default_rng(0), c.M, c.N, 24, 24)
+    ref, mag = oracle.gemm_points(0, 0, c.M, c.N, c.K, 1.0, wl.arrays["A"], c.lda, wl.arrays["B"], c.ldb,
+                                  0.0, None, c.ldc, pi, pj)
+    r = check_bound(out["C"][pi, pj], ref, mag, c.K, "config 2 (24+ full rows and columns)")
+    print("config 2 max err/bound %.3g" % r)
+
+
+def test_config2_shape_integer_entries_bit_exact(dm, torch):
+    """Same 4096^3 launch, entries in {-4..4}: |sums| <= 65536, so the GPU must match bit for bit."""
+    n = 4096
+    rng = np.random.default_rng(11)
+    A, B = workloads.small_ints(rng, (n, n)), workloads.small_ints(rng, (n, n))
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dC = torch.empty((n, n), device="cuda")
+    dm.check(dm.dmath_gemm(0, 0, n, n, n, 1.0, dA, n, dB, n, 0.0, dC, n))
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    pi, pj = _sample_rows_cols(np.random.default_rng(1), n, n, 16, 16)
+    ref, _ = oracle.gemm_points(0, 0, n, n, n, 1.0, A, n, B, n, 0.0, None, n, pi, pj)
+    assert np.array_equal(got[pi, pj].astype(np.float64), ref)
+
+
+def test_config3_summa_chain(dm, torch):
+    """16 accumulate steps; the end state is checked against C0 + [A_0..A_15]*[B_0;..;B_15] (K = 8192)."""
+    wl = workloads.config3()
+    out = _run_workload(dm, torch, wl)
+    m, kp, steps = 8192, 512, 16
+    Acat = np.ascontiguousarray(np.concatenate([wl.arrays["A%d" % k] for k in range(steps)], axis=1))
+    Bcat = np.ascontiguousarray(np.concatenate([wl.arrays["B%d" % k] for k in range(steps)], axis=0))
+    pi, pj = _sample_rows_cols(np.random.default_rng(2), m, m, 6, 6)
+    ref, mag = oracle.gemm_points(0, 0, m, m, kp * steps, 1.0, Acat, kp * steps, Bcat, m, 1.0, wl.arrays["C"], m,
+                                  pi, pj)
+    r = check_bound(out["C"][pi, pj], ref, mag, kp * steps, "config 3 chain")
+    # tighter, informative form: per-step rounding of a K=512 product plus 16 roundings of C
+    err = np.abs(out["C"][pi, pj].astype(np.float64) - ref)
+    print("config 3 max err/bound %.3g, max abs err %.3g" % (r, err.max()))
+
+
+def test_config4_fc_layer(dm, torch):
+    wl = workloads.config4()
+    out = _run_workload(dm, torch, wl)
+    for c in wl.calls:
+        ref, mag = oracle.gemm(c.transA, c.transB, c.M, c.N, c.K, 1.0, wl.arrays[c.A], c.lda, wl.arrays[c.B], c.ldb)
+        r = check_bound(out[c.C], ref, mag, c.K, "config 4 %s" % c.C)
+        print("config 4 %s max err/bound %.3g" % (c.C, r))
+
+
+def test_config4_without_workspace(dm, torch):
+    """With no scratch registered the skinny products take a path that needs none."""
+    ws = dm._test_workspace
+    dm.check(dm.dmath_set_workspace(None, 0))
+    try:
+        wl = workloads.config4(batch=256, width=1024)
+        out = _run_workload(dm, torch, wl)
+        for c in wl.calls:
+            ref, mag = oracle.gemm(c.transA, c.transB, c.M, c.N, c.K, 1.0, wl.arrays[c.A], c.lda, wl.arrays[c.B],
+                                   c.ldb)
+            check_bound(out[c.C], ref, mag, c.K, "config 4 (no workspace) %s" % c.C)
+    finally:
+        dm.check(dm.dmath_set_workspace(ws, ws.numel()))
+
+
+# ------------------------------------------------------------------ convolution
+
+CONV_SMALL = [
+    dict(N=2, C=3, H=7, W=5, Kout=4, R=3, S=3, pad=(1, 1), stride=(1, 1)),
+    dict(N=1, C=2, H=9, W=6, Kout=3, R=3, S=2, pad=(0, 0), stride=(2, 2)),
+    dict(N=2, C=1, H=8, W=11, Kout=2, R=5, S=3, pad=(2, 1), stride=(2, 3)),
+    dict(N=3, C=20, H=14, W=14, Kout=70, R=3, S=3, pad=(1, 1), stride=(1, 1)),
+    dict(N=5, C=16, H=12, W=12, Kout=33, R=1, S=1, pad=(0, 0), stride=(1, 1)),
+    dict(N=2, C=7, H=13, W=9, Kout=130, R=3, S=3, pad=(1, 1), stride=(1, 1)),
+    dict(N=1, C=4, H=5, W=5, Kout=6, R=5, S=5, pad=(0, 0), stride=(1, 1)),
+]
+
+
+@pytest.mark.parametrize("shape", CONV_SMALL)
+def test_conv_small(dm, torch, shape):
+    run_conv_case(dm, torch, seed=shape["H"], **shape)
+    run_conv_case(dm, torch, seed=shape["W"], alpha=0.5, beta=-1.5, lead=1, **shape)
+    run_conv_case(dm, torch, seed=shape["C"], ints=True, exact=True, beta=1.0, **shape)
+
+
+@pytest.mark.parametrize("cfg", range(5))
+def test_conv_every_config(dm, torch, cfg):
+    if cfg >= dm.dmath_num_configs():
+        pytest.skip("no such configuration")
+    dm.dmath_set_override(cfg, 1)
+    run_conv_case(dm, torch, N=3, C=12, H=28, W=28, Kout=72, R=3, S=3, pad=(1, 1), stride=(1, 1), seed=cfg)
+    run_conv_case(dm, torch, N=2, C=5, H=11, W=13, Kout=260, R=3, S=3, pad=(1, 1), stride=(2, 1), seed=cfg + 5,
+                  alpha=2.0, beta=1.0, lead=3)
+
+
+def test_conv_quick_returns(dm, torch):
+    y0 = np.arange(2 * 3 * 4 * 4, dtype=np.float32).reshape(2, 3, 4, 4)
+    dy = torch.from_numpy(y0).cuda()
+    nanx = torch.full((2, 2, 4, 4), float("nan"), device="cuda")
+    nanw = torch.full((3, 2, 3, 3), float("nan"), device="cuda")
+    dm.check(dm.dmath_conv2d_fwd(2, 2, 4, 4, 3, 3, 3, 1, 1, 1, 1, 0.0, nanx, nanw, 2.0, dy))
+    torch.cuda.synchronize()
+    assert np.array_equal(dy.cpu().numpy(), 2.0 * y0)
+    dm.check(dm.dmath_conv2d_fwd(2, 0, 4, 4, 3, 3, 3, 1, 1, 1, 1, 1.0, None, None, 0.0, dy))
+    torch.cuda.synchronize()
+    assert np.array_equal(dy.cpu().numpy(), np.zeros_like(y0))
+
+
+def test_config5_conv_full_size_sampled(dm, torch):
+    wl = workloads.config5()
+    N, Kout, P, Q = wl.out_shape
+    dx, dw = torch.from_numpy(wl.x).cuda(), torch.from_numpy(wl.w).cuda()
+    dy = torch.full((N, Kout, P, Q), float("nan"), device="cuda")
+    _, C, H, W = wl.x.shape
+    dm.check(dm.dmath_conv2d_fwd(N, C, H, W, Kout, 3, 3, 1, 1, 1, 1, 1.0, dx, dw, 0.0, dy))
+    torch.cuda.synchronize()
+    got = dy.cpu().numpy()
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(3)
+    total = got.size
+    idx = rng.choice(total, size=300000, replace=False)
+    # add whole output planes: first and last image / channel, with their borders
+    plane = P * Q
+    for n, j in [(0, 0), (N - 1, Kout - 1), (N // 2, 129), (1, 255)]:
+        base = (n * Kout + j) * plane
+        idx = np.concatenate([idx, np.arange(base, base + plane)])
+    ref, mag = oracle.conv2d_fwd_points(wl.x, wl.w, idx, pad=wl.pad, stride=wl.stride)
+    M, Ng, K = wl.gemm_view
+    r = check_bound(got.reshape(-1)[idx], ref, mag, K, "config 5 sampled")
+    print("config 5 max err/bound %.3g" % r)
+
+
+def test_config5_shape_small_batch_every_element(dm, torch):
+    wl = workloads.config5(batch=2)
+    N, Kout, P, Q = wl.out_shape
+    dx, dw = torch.from_numpy(wl.x).cuda(), torch.from_numpy(wl.w).cuda()
+    dy = torch.full((N, Kout, P, Q), float("nan"), device="cuda")
+    dm.check(dm.dmath_conv2d_fwd(N, 256, 28, 28, Kout, 3, 3, 1, 1, 1, 1, 1.0, dx, dw, 0.0, dy))
+    torch.cuda.synchronize()
+    ref, mag = oracle.conv2d_fwd(wl.x, wl.w, pad=wl.pad, stride=wl.stride)
+    check_bound(dy.cpu().numpy(), ref, mag, 2304, "config 5 shape, batch 2")
