@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X-native local GEMM / forward convolution library.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+Prints ONE JSON line.  The default workload is the headline one: the FP32 NN GEMM with
+M = N = K = 4096 (one GPU's local block of a block-distributed matrix), seeded synthetic inputs
+already resident in HBM, one dmath_gemm call per step.  Metric: TFLOP/s (2*M*N*K per call over
+the mean time per call), with the fraction of the MI355X FP32 MFMA peak in "roofline" and the
+FP64 CPU oracle timed on this machine's host cores on a bounded sample of the same problem in
+"cpu_baseline".  Other workloads (--workload) are the remaining benchmark configurations; they
+print the same kind of line for their own shape.
+
+Everything runs on one GPU; --gpus above 1 is refused.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Published MI355X peaks used as roofline denominators.
+PEAK_FP32_MFMA_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 64 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by
+# what the same counter reads for a device copy of known size); figures and commands are in
+# profiles/gemm_nn_4096_hbm_traffic.md.  Keyed by workload; None where no counter run is committed.
+MEASURED_HBM_TRAFFIC_BYTES = {
+}
+
+WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv")
+
+
+def _device_arrays(torch, arrays):
+    return {k: torch.from_numpy(v).cuda() for k, v in arrays.items()}
+
+
+def _time_steps(torch, step, steps, warmup):
+    """warmup untimed steps, then exactly `steps` timed ones between synchronisations.
+
+    Returns (ms per step by HIP events on the launch stream, ms per step by the host clock)."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return e0.elapsed_time(e1) / steps, (t1 - t0) * 1e3 / steps
+
+
+def _cpu_baseline_gemm(oracle, call, arrays, budget_s=15.0):
+    """The oracle as it stands on a bounded sample: the first R rows of C (all N columns, full K)."""
+    A, B = arrays[call.A], arrays[call.B]
+    C0 = arrays[call.C] if call.beta != 0.0 else None
+
+    def run(rows):
+        t0 = time.perf_counter()
+        oracle.gemm(call.transA, call.transB, rows, call.N, call.K, call.alpha, A, call.lda, B, call.ldb,
+                    call.beta, C0, call.ldc)
+        return time.perf_counter() - t0
+
+    threads = oracle.num_threads()
+    probe_rows = min(call.M, 2 * threads)
+    t_probe = max(run(probe_rows), 1e-4)
+    rows = int(min(call.M, max(probe_rows, probe_rows * budget_s / t_probe)))
+    rows = max(threads, rows - rows % threads)
+    rows = min(rows, call.M)
+    t = run(rows)
+    flop = 2.0 * rows * call.N * call.K
+    return {
+        "value": flop / t / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "sample": "first %d of %d rows of C (all %d columns, full K=%d), FP64 sums plus the magnitude sums, %.1f s"
+                  % (rows, call.M, call.N, call.K, t),
+    }
+
+
+def _cpu_baseline_conv(oracle, wl, budget_s=15.0):
+    import numpy as np
+    threads = oracle.num_threads()
+    N, Kout, P, Q = wl.out_shape
+    _, _, K = wl.gemm_view
+    total = N * Kout * P * Q
+    rng = np.random.default_rng(0)
+
+    def run(npts):
+        idx = rng.choice(total, size=npts, replace=False)
+        t0 = time.perf_counter()
+        oracle.conv2d_fwd_points(wl.x, wl.w, idx, pad=wl.pad, stride=wl.stride)
+        return time.perf_counter() - t0
+
+    probe = 20000
+    t_probe = max(run(probe), 1e-4)
+    npts = int(min(total, max(probe, probe * budget_s / t_probe)))
+    t = run(npts)
+    return {
+        "value": 2.0 * npts * K / t / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "sample": "%d random output elements of %d (all %d taps each), FP64 sums plus the magnitude sums, %.1f s"
+                  % (npts, total, K, t),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", choices=WORKLOADS, default="gemm4096")
+    ap.add_argument("--tile-config", type=int, default=-1, help="force a tile configuration (tuning only)")
+    ap.add_argument("--split-k", type=int, default=-1, help="force a split-K factor (tuning only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the workload, run `steps` device copies of 256 MiB (for scaling HBM counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this library runs on one GPU; --gpus %d is not supported "
+                         "(no multi-GPU path exists in this build)\n" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1604_01416_amd import dmath as dm      # fails loudly if libdmath.so is missing
+    from paper_1604_01416_amd import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        nbytes = 256 << 20
+        src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        ms, _ = _time_steps(torch, lambda: dst.copy_(src), args.steps, args.warmup)
+        print(json.dumps({"copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "steps": args.steps,
+                          "ms_per_copy": ms, "GBps": 2 * nbytes / ms / 1e6}))
+        return
+
+    ws_bytes = 128 << 20
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    dm.check(dm.dmath_set_workspace(ws, ws_bytes))
+    if args.tile_config >= 0 or args.split_k >= 1:
+        dm.check(dm.dmath_set_override(args.tile_config, args.split_k))
+
+    cpu_baseline = None
+    conv = None
+    if args.workload == "conv":
+        conv = workloads.config5()
+        N, Kout, P, Q = conv.out_shape
+        _, C, H, W = conv.x.shape
+        dx, dw = torch.from_numpy(conv.x).cuda(), torch.from_numpy(conv.w).cuda()
+        dy = torch.empty((N, Kout, P, Q), device="cuda")
+
+        def step():
+            dm.check(dm.dmath_conv2d_fwd(N, C, H, W, Kout, 3, 3, 1, 1, 1, 1, 1.0, dx, dw, 0.0, dy))
+
+        flop, alg_bytes, launches = conv.flop, conv.algorithmic_bytes, 1
+        wl_name = conv.name
+    else:
+        wl = {"gemm4096": workloads.config2, "gemm256": workloads.config1, "summa": workloads.config3,
+              "fc": workloads.config4}[args.workload]()
+        dev = _device_arrays(torch, wl.arrays)
+        calls = [(c, dev[c.A], dev[c.B], dev[c.C]) for c in wl.calls]
+
+        def step():
+            for c, a, b, cc in calls:
+                dm.check(dm.dmath_gemm(c.transA, c.transB, c.M, c.N, c.K, c.alpha, a, c.lda, b, c.ldb, c.beta, cc,
+                                       c.ldc))
+
+        flop = wl.flop
+        alg_bytes = sum(c.algorithmic_bytes for c in wl.calls)
+        launches = len(wl.calls)
+        wl_name = wl.name
+
+    ms_ev, ms_wall = _time_steps(torch, step, args.steps, args.warmup)
+    tflops = flop / ms_ev / 1e9
+
+    # Clock the tile kernel really ran at (GEMM workloads): one more step with the in-kernel stamps on.
+    measured_clock_ghz = None
+    if conv is None:
+        probe = torch.zeros(32, dtype=torch.int64, device="cuda")
+        dm.check(dm.dmath_set_clock_probe(probe))
+        step()
+        torch.cuda.synchronize()
+        dm.check(dm.dmath_set_clock_probe(None))
+        p = [int(v) for v in probe.cpu().tolist()]
+        per_die = [(p[4 * d + 2] - p[4 * d]) / (p[4 * d + 3] - p[4 * d + 1]) * 0.1
+                   for d in range(8) if p[4 * d + 3] > p[4 * d + 1]]
+        if per_die:
+            measured_clock_ghz = {"mean": sum(per_die) / len(per_die), "min": min(per_die), "max": max(per_die)}
+
+    if not args.no_cpu_baseline:
+        import oracle
+        if conv is not None:
+            cpu_baseline = _cpu_baseline_conv(oracle, conv)
+        else:
+            cpu_baseline = _cpu_baseline_gemm(oracle, wl.calls[0], wl.arrays)
+
+    # Dominant kernel: the MFMA tile kernel.  The headline workload is one launch of it per step, so its
+    # mean duration is the event time per step; for multi-call workloads this is the aggregate rate.
+    achieved = tflops
+    roofline = {
+        "bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+        "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+        "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(args.workload),
+        "algorithmic_bytes_per_step": alg_bytes,
+        "algorithmic_GBps": alg_bytes / ms_ev / 1e6,
+        "hbm_frac": alg_bytes / ms_ev / 1e6 / PEAK_HBM_GBS,
+    }
+    line = {
+        "metric": "FP32 GEMM TFLOP/s at 4096^3 on 1 MI355X; % of FP32 MFMA peak" if args.workload == "gemm4096"
+                  else "FP32 TFLOP/s on workload %s on 1 MI355X" % wl_name,
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_ev, "ms_per_step_host_clock": ms_wall, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl_name, "launches_per_step": launches, "flop_per_step": flop,
+                   "tile_config": dm.dmath_config_name(args.tile_config) if args.tile_config >= 0 else "auto",
+                   "library": dm.dmath_version()},
+        "pct_of_fp32_mfma_peak": 100.0 * tflops / PEAK_FP32_MFMA_TFLOPS,
+        "measured_shader_clock_ghz": measured_clock_ghz,
+        "pct_of_fp32_mfma_peak_at_measured_clock":
+            None if not measured_clock_ghz
+            else 100.0 * tflops / (PEAK_FP32_MFMA_TFLOPS * measured_clock_ghz["mean"] / 2.4),
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "paper_context": "dMath paper, table 'Matrix Multiplication Performance': N=4096 on one K80 GPU with "
+                         "cuBLAS 7.5 took 0.052 s (about 2.64 TFLOP/s, precision not stated); other hardware, "
+                         "context only",
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -134,8 +134,28 @@ dmath_status dmath_set_workspace(void *device_ptr, size_t bytes);
  * INVALID_ARG for an index outside the table.
  */
 dmath_status dmath_set_override(int tile_config, int split_k);
+
+/*
+ * Which tile configuration and split-K factor dmath_gemm would use for this shape right now (given
+ * this thread's workspace and override).  Host-side only, launches nothing.  tile_config receives -1
+ * when the call would not run a tile kernel (empty output or K == 0).  Either pointer may be NULL.
+ */
+dmath_status dmath_gemm_plan(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K,
+                             int *tile_config, int *split_k);
 int dmath_num_configs(void);
 const char *dmath_config_name(int tile_config); /* NULL outside the table */
+
+/*
+ * Measurement hook: when device_ptr is not NULL it must point to 32 uint64 values (256 bytes) of
+ * device memory; workgroups 0..7 of every later dmath_gemm tile kernel launched by this thread (the
+ * first workgroup placed on each of the 8 dies, which clock independently) each write four of them:
+ * the shader-clock counter and the fixed 100 MHz counter when the workgroup starts, and both again
+ * when it ends.  (shader clocks elapsed) / (100 MHz ticks elapsed) * 100 MHz is the clock that die
+ * ran at while the workgroup lived; the benchmark reports it next to the nominal 2.4 GHz.  Entries of
+ * workgroups the launch does not have stay untouched.  NULL switches the hook off.  INVALID_ARG
+ * unless 8-byte aligned.
+ */
+dmath_status dmath_set_clock_probe(void *device_ptr);
 
 /* 1-based index of the argument rejected by this thread's last failed call, 0 if none. */
 int dmath_last_error_arg(void);

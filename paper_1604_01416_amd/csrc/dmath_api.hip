@@ -21,6 +21,7 @@ struct ThreadState {
     int force_cfg = -1;
     int force_split = -1;
     int last_error_arg = 0;
+    unsigned long long *clock_probe = nullptr;
 };
 thread_local ThreadState g_state;
 
@@ -94,27 +95,43 @@ struct Plan {
 };
 
 // Shape-based choice (the paper's outlook names choosing the multiply algorithm from the shape as
-// future work; this is its one-GPU form).  Cost model in units of "MFMA time of one K step of a
-// 32x32 block": a compute unit runs its resident workgroups' tiles back to back, small wave tiles
-// pay for their lower operand reuse, split-K pays for writing and re-reading its slices.
+// future work; this is its one-GPU form).  A small time model in microseconds, fitted to measurements
+// on MI355X: a compute unit works through ceil(workgroups / 256) tiles at the MFMA rate it sustains
+// under load (about 2.2 GHz), scaled by how well the configuration keeps the MFMA pipe fed, and pays a
+// fixed fill/drain time per batch of co-resident workgroups (first loads, last stores; hidden behind
+// the other resident workgroup when there is one).  Split-K adds writing and re-reading its slices.
+struct CfgModel {
+    double eff;        // fraction of the MFMA rate sustained in the K loop with a full compute unit
+    double eff_alone;  // the same with a single workgroup on the compute unit (less latency hiding)
+    double fill_us;    // fill + drain per batch of resident workgroups
+    int wg_per_cu;     // workgroups resident on a compute unit
+};
+const CfgModel kModel[kNumCfg] = {
+    {0.958, 0.95, 23.0, 2},  // 256x128
+    {0.948, 0.94, 15.0, 2},  // 128x256
+    {1.000, 1.00, 33.0, 1},  // 256x256
+    {0.930, 0.85, 12.0, 3},  // 128x128
+    {0.800, 0.55, 8.0, 6},   // 64x64
+};
+
 Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split)
 {
-    static const double eff[kNumCfg] = {1.0, 1.0, 1.0, 0.85, 0.55};
+    const double flop_per_us_cu = 256.0 * 2200.0;  // flop per microsecond per compute unit
     Plan best = {0, 1};
     double best_cost = 1e300;
     for (int c = 0; c < kNumCfg; ++c) {
         const CfgDesc &d = desc(c);
+        const CfgModel &m = kModel[c];
         const int64_t tiles = ceil_div(M, d.BM) * ceil_div(N, d.BN);
         const int64_t ktiles = K / d.BK;
         const int max_split = allow_split ? 16 : 1;
         for (int s = 1; s <= max_split; s *= 2) {
             if (s > 1 && ktiles / s < 8) break;
-            const double per_cu = (double)ceil_div(tiles * s, kNumCU);
-            const double tile_work = (double)d.BM * d.BN * ((double)K / s + 4.0 * d.BK) / eff[c];
-            double cost = per_cu * tile_work;
-            // slices: written once, read once, by all compute units together (~3 bytes/clk/CU effective
-            // against 256 flop/clk/CU of MFMA; expressed in the same unit as tile_work: element-steps)
-            if (s > 1) cost += (double)M * N * (s + 1) * 4.0 / kNumCU * 85.0 / 4.0 + 2.0e5;
+            const int64_t per_cu = ceil_div(tiles * s, kNumCU);
+            const double eff = per_cu >= 2 || m.wg_per_cu == 1 ? m.eff : m.eff_alone;
+            const double tile_us = 2.0 * d.BM * d.BN * ((double)K / s) / flop_per_us_cu / eff;
+            double cost = per_cu * tile_us + (double)ceil_div(per_cu, m.wg_per_cu) * m.fill_us;
+            if (s > 1) cost += (double)M * N * (s + 1) * 4.0 / 4.0e6 + 6.0;  // slices at ~4 TB/s + a launch
             if (cost < best_cost) {
                 best_cost = cost;
                 best = {c, s};
@@ -182,6 +199,13 @@ dmath_status dmath_set_override(int tile_config, int split_k)
     return DMATH_OK;
 }
 
+dmath_status dmath_set_clock_probe(void *device_ptr)
+{
+    if ((reinterpret_cast<uintptr_t>(device_ptr) & 7u) != 0) return fail(DMATH_ERR_INVALID_ARG, 1);
+    g_state.clock_probe = static_cast<unsigned long long *>(device_ptr);
+    return DMATH_OK;
+}
+
 dmath_status dmath_set_workspace(void *device_ptr, size_t bytes)
 {
     if (device_ptr == nullptr && bytes != 0) return fail(DMATH_ERR_WORKSPACE, 1);
@@ -198,6 +222,20 @@ size_t dmath_gemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, i
     if (M <= 0 || N <= 0 || K <= 0) return 0;
     const Plan p = resolve_plan(M, N, K, true);
     return p.splits > 1 ? split_bytes(M, N, p.splits) : 0;
+}
+
+dmath_status dmath_gemm_plan(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, int *tile_config,
+                             int *split_k)
+{
+    (void)transA;
+    (void)transB;
+    if (M < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
+    if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
+    if (K < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
+    const Plan p = (M == 0 || N == 0 || K == 0) ? Plan{-1, 1} : resolve_plan(M, N, K, false);
+    if (tile_config) *tile_config = p.cfg;
+    if (split_k) *split_k = p.splits;
+    return DMATH_OK;
 }
 
 dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, float alpha,
@@ -256,6 +294,7 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     g.beta = beta;
     g.tiles_m = (int)tiles_m;
     g.tiles_n = (int)tiles_n;
+    g.clock_probe = g_state.clock_probe;
     g.splits = plan.splits;
     g.ktiles_per_split = (int)((K / d.BK) / plan.splits);
     if (plan.splits > 1) {

@@ -17,6 +17,7 @@ struct GemmArgs {
     int ktiles_per_split;
     int cvec;         // C rows allow aligned NB-wide vector access
     int64_t slice_stride;  // floats between consecutive workspace slices (M*N), 0 when splits == 1
+    unsigned long long *clock_probe;  // optional: 4 stamps from each of workgroups 0..7 (see dmath_set_clock_probe)
 };
 
 template <class Cfg, bool ROWS_K, bool VEC>
@@ -43,6 +44,11 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
 {
     __shared__ __attribute__((aligned(16))) float smem[Cfg::STAGES * Cfg::STAGE_FLOATS];
 
+    // Workgroups 0..7 are the first ones handed to each of the 8 dies, which clock independently.
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();      // shader-clock counter
+        g.clock_probe[blockIdx.x * 4 + 1] = __builtin_amdgcn_s_memrealtime();  // fixed 100 MHz counter
+    }
     const int tiles = g.tiles_m * g.tiles_n;
     const int pid = xcd_contiguous_id(blockIdx.x, tiles * g.splits);
     const int z = pid / tiles;
@@ -124,6 +130,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
                 }
             }
         }
+    }
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
+        g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
     }
 }
 

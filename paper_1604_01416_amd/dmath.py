@@ -16,7 +16,7 @@ OP_N, OP_T = 0, 1
 
 EXPORTS = (
     "dmath_gemm", "dmath_conv2d_fwd", "dmath_gemm_workspace_bytes", "dmath_set_workspace",
-    "dmath_set_override", "dmath_num_configs", "dmath_config_name", "dmath_last_error_arg",
+    "dmath_set_override", "dmath_set_clock_probe", "dmath_gemm_plan", "dmath_num_configs", "dmath_config_name", "dmath_last_error_arg",
     "dmath_status_string", "dmath_version",
 )
 
@@ -38,6 +38,10 @@ _lib.dmath_set_workspace.restype = _int
 _lib.dmath_set_workspace.argtypes = [_vp, ctypes.c_size_t]
 _lib.dmath_set_override.restype = _int
 _lib.dmath_set_override.argtypes = [_int, _int]
+_lib.dmath_set_clock_probe.restype = _int
+_lib.dmath_set_clock_probe.argtypes = [_vp]
+_lib.dmath_gemm_plan.restype = _int
+_lib.dmath_gemm_plan.argtypes = [_int, _int, _i64, _i64, _i64, ctypes.POINTER(_int), ctypes.POINTER(_int)]
 _lib.dmath_num_configs.restype = _int
 _lib.dmath_config_name.restype = ctypes.c_char_p
 _lib.dmath_config_name.argtypes = [_int]
@@ -85,6 +89,17 @@ def dmath_set_workspace(device_ptr, nbytes):
 
 def dmath_set_override(tile_config, split_k):
     return _lib.dmath_set_override(tile_config, split_k)
+
+
+def dmath_set_clock_probe(device_ptr):
+    return _lib.dmath_set_clock_probe(_addr(device_ptr))
+
+
+def dmath_gemm_plan(transA, transB, M, N, K):
+    """Returns (status, tile_config, split_k)."""
+    cfg, split = _int(0), _int(0)
+    st = _lib.dmath_gemm_plan(transA, transB, M, N, K, ctypes.byref(cfg), ctypes.byref(split))
+    return st, cfg.value, split.value
 
 
 def dmath_num_configs():
