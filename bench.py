@@ -29,8 +29,10 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by
 # what the same counter reads for a device copy of known size); figures and commands are in
-# profiles/gemm_nn_4096_hbm_traffic.md.  Keyed by workload; None where no counter run is committed.
+# profiles/*.md.  Keyed by workload; None where no counter run is committed.
 MEASURED_HBM_TRAFFIC_BYTES = {
+    # profiles/gemm_nn_4096_tile_kernel.md: FETCH_SIZE 196744 KiB x 2.0 (copy factor) + WRITE_SIZE 65536 KiB x 1.0
+    "gemm4096": int((196743.6 * 2.0 + 65536.0) * 1024),
 }
 
 WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv")
