@@ -13,7 +13,10 @@ template <> struct CfgAt<1> { typedef TileCfg<128, 256, 16, 2, 2, 3, 2> type; };
 template <> struct CfgAt<2> { typedef TileCfg<256, 256, 16, 4, 2, 3, 2> type; };  // 512 threads, one workgroup per CU
 template <> struct CfgAt<3> { typedef TileCfg<128, 128, 16, 2, 2, 3, 2> type; };  // wave tile 64 x 64
 template <> struct CfgAt<4> { typedef TileCfg<64, 64, 16, 2, 2, 2, 2> type; };    // wave tile 32 x 32, small problems
-constexpr int kNumCfg = 5;
+template <> struct CfgAt<5> { typedef TileCfg<256, 256, 16, 4, 2, 3, 2, 0> type; };  // experiment: loader variant 0
+template <> struct CfgAt<6> { typedef TileCfg<256, 128, 16, 4, 1, 3, 2, 0> type; };  // experiment: loader variant 0
+template <> struct CfgAt<7> { typedef TileCfg<256, 256, 16, 2, 2, 3, 1> type; };     // experiment: 4 waves of 128x128, one wave per SIMD
+constexpr int kNumCfg = 8;
 
 struct CfgDesc {
     const char *name;
@@ -29,5 +32,8 @@ template <> const CfgDesc &cfg_desc<1>();
 template <> const CfgDesc &cfg_desc<2>();
 template <> const CfgDesc &cfg_desc<3>();
 template <> const CfgDesc &cfg_desc<4>();
+template <> const CfgDesc &cfg_desc<5>();
+template <> const CfgDesc &cfg_desc<6>();
+template <> const CfgDesc &cfg_desc<7>();
 
 }  // namespace dmath

@@ -37,10 +37,11 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t magic, int d)
 // Loader of the generated operand.  Lanes run along the output pixels (contiguous q in x), each
 // thread keeps one column and walks k; k is uniform over a wave, so (c, r, s) and the offset of the
 // tap are scalar work, and only the halo test and the load itself are per lane.
-template <int BN, int BK, int NT, int LD>
+template <int BN, int BK, int NT, int LD, int ROT>
 struct LoaderConvX {
     static constexpr int KG = NT / BN;  // k rows loaded side by side
     static constexpr int NQ = BK / KG;  // k rows per thread and tile
+    static constexpr int NLOAD = NQ, NSTORE = NQ;
     static_assert(NT % BN == 0 && BK % KG == 0 && BN % 64 == 0 && NQ >= 1, "one column per thread");
     const float *xcol;  // x + n*C*H*W + ih0*W + iw0 (the tap (c=0, r=0, s=0); may lie in the halo)
     int ih0, iw0;
@@ -69,31 +70,30 @@ struct LoaderConvX {
         iw0 = q * a.stride_w - a.pad_w;
         xcol = a.x + (int64_t)n * a.C * HW + (int64_t)ih0 * W + iw0;
     }
-    __device__ __forceinline__ void load_rows(int kbase)
+    template <int I>
+    __device__ __forceinline__ void load_piece()
     {
-#pragma unroll
-        for (int it = 0; it < NQ; ++it) {
-            const uint32_t k = (uint32_t)(kbase + kg + it * KG);
-            const uint32_t c = fast_div(k, magic_RS, RS);
-            const uint32_t rs = k - c * (uint32_t)RS;
-            const uint32_t r = fast_div(rs, magic_S, S);
-            const uint32_t s = rs - r * (uint32_t)S;
-            const int off = (int)c * HW + (int)r * W + (int)s;
-            const bool ok = col_ok && (int64_t)k < CRS && (unsigned)(ih0 + (int)r) < (unsigned)H &&
-                            (unsigned)(iw0 + (int)s) < (unsigned)W;
-            v[it] = ok ? xcol[off] : 0.0f;
-        }
+        const uint32_t k = (uint32_t)(knext + kg + I * KG);
+        const uint32_t c = fast_div(k, magic_RS, RS);
+        const uint32_t rs = k - c * (uint32_t)RS;
+        const uint32_t r = fast_div(rs, magic_S, S);
+        const uint32_t s = rs - r * (uint32_t)S;
+        const int off = (int)c * HW + (int)r * W + (int)s;
+        const bool ok = col_ok && (int64_t)k < CRS && (unsigned)(ih0 + (int)r) < (unsigned)H &&
+                        (unsigned)(iw0 + (int)s) < (unsigned)W;
+        v[I] = ok ? xcol[off] : 0.0f;
     }
-    __device__ __forceinline__ void load()
+    __device__ __forceinline__ void advance() { knext += BK; }
+    // the partial last tile needs nothing special: k >= C*R*S is already generated as zero
+    __device__ __forceinline__ void load_tail(int)
     {
-        load_rows(knext);
-        knext += BK;
+        static_for<NQ>([&](auto ic) { load_piece<decltype(ic)::value>(); });
     }
-    __device__ __forceinline__ void load_tail(int) { load_rows(knext); }
-    __device__ __forceinline__ void store(float *Sm) const
+    template <int I>
+    __device__ __forceinline__ void store_piece(float *Sm) const
     {
-#pragma unroll
-        for (int it = 0; it < NQ; ++it) Sm[(kg + it * KG) * LD + col] = v[it];
+        const int k = kg + I * KG;
+        Sm[k * LD + rot_col<BN, ROT>(col, k)] = v[I];
     }
 };
 
@@ -111,8 +111,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
     const int T = (int)(a.CRS / Cfg::BK);
     const int krem = (int)(a.CRS - (int64_t)T * Cfg::BK);
 
-    LoaderK<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, VEC> rl;
-    LoaderConvX<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB> cl;
+    typename LoaderKSel<Cfg::LKV, Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC>::type rl;
+    LoaderConvX<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT> cl;
     rl.init(a.w, a.CRS, m0, a.Kout, 0, threadIdx.x);
     cl.init(a, n0, threadIdx.x);
 

@@ -32,7 +32,10 @@ const CfgDesc &desc(int i)
         case 1: return cfg_desc<1>();
         case 2: return cfg_desc<2>();
         case 3: return cfg_desc<3>();
-        default: return cfg_desc<4>();
+        case 4: return cfg_desc<4>();
+        case 5: return cfg_desc<5>();
+        case 6: return cfg_desc<6>();
+        default: return cfg_desc<7>();
     }
 }
 
@@ -112,6 +115,9 @@ const CfgModel kModel[kNumCfg] = {
     {1.000, 1.00, 33.0, 1},  // 256x256
     {0.930, 0.85, 12.0, 3},  // 128x128
     {0.800, 0.55, 8.0, 6},   // 64x64
+    {0.900, 0.90, 33.0, 1},  // experiments (never preferred)
+    {0.900, 0.90, 23.0, 2},
+    {0.900, 0.90, 33.0, 1},
 };
 
 Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split)

@@ -22,19 +22,19 @@ struct GemmArgs {
 
 template <class Cfg, bool ROWS_K, bool VEC>
 struct RowLoaderSel {
-    typedef LoaderK<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, VEC> type;
+    typedef typename LoaderKSel<Cfg::LKV, Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC>::type type;
 };
 template <class Cfg, bool VEC>
 struct RowLoaderSel<Cfg, false, VEC> {
-    typedef LoaderMN<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, VEC> type;
+    typedef LoaderMN<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC> type;
 };
 template <class Cfg, bool COLS_K, bool VEC>
 struct ColLoaderSel {
-    typedef LoaderK<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, VEC> type;
+    typedef typename LoaderKSel<Cfg::LKV, Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC>::type type;
 };
 template <class Cfg, bool VEC>
 struct ColLoaderSel<Cfg, false, VEC> {
-    typedef LoaderMN<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, VEC> type;
+    typedef LoaderMN<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC> type;
 };
 
 // A_KCONTIG: A stored M x K (transA == N).  B_KCONTIG: B stored N x K (transB == T).

@@ -6,13 +6,17 @@
 // times cols-operand (K x BN).  Both operands are staged in LDS in the same
 // image, whatever their orientation in memory:
 //
-//     As[stage][k][LDA]   element (k, r) = rows-operand(r, k),  r in [0, BM)
-//     Bs[stage][k][LDB]   element (k, c) = cols-operand(k, c),  c in [0, BN)
+//     As[stage][k][LDA]   element (k, rot(r, k)) = rows-operand(r, k),  r in [0, BM)
+//     Bs[stage][k][LDB]   element (k, rot(c, k)) = cols-operand(k, c),  c in [0, BN)
+//     rot(x, k) = (x + ROT * (k / 4)) mod extent        (ROT = 8 floats, LDA = BM, LDB = BN)
 //
 // so the MFMA loop and the epilogue are the same for every transpose form
 // (the local multiply of section "Matrix Multiplication" of the dMath paper and
 // its transposed variants) and for the convolution, which only brings its own
-// loader for the operand generated from x.
+// loader for the operand generated from x.  The rotation of each group of four
+// k rows by 8 floats is what lets an operand that is contiguous along k in
+// memory be stored transposed without LDS bank conflicts (see LoaderK); it
+// costs nothing on the read side, where it is a per-lane constant.
 //
 // MFMA used: v_mfma_f32_32x32x2_f32.  For lane l (i = l % 32, h = l / 32):
 //   A operand register holds A[i][k = h], B operand holds B[k = h][j = i],
@@ -26,6 +30,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <utility>
 
 namespace dmath {
 
@@ -41,247 +47,512 @@ template <> struct VecOf<4> { typedef floatx4 type; };
 constexpr int kNumXcd = 8;  // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 
 // Tile configuration.  WM = BM / WAVES_M and WN = BN / WAVES_N are the wave tile.
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int MIN_WAVES_PER_SIMD_>
+// LKV selects the LDS image: 2 = rotated rows, no padding (the product layout); 0 = plain rows padded
+// by 4 floats with 4-byte transposing stores (kept as a comparison point for the counters).
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int MIN_WAVES_PER_SIMD_, int LKV_ = 2>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_;
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
     static constexpr int MIN_WAVES = MIN_WAVES_PER_SIMD_;
+    static constexpr int LKV = LKV_;
+    static constexpr int ROT = (LKV_ == 2) ? 8 : 0;
     static constexpr int NT = WAVES_M * WAVES_N * 64;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int MB = WM / 32, NB = WN / 32;
-    // +4 floats of padding: rows stay 16-byte aligned and the transposing
-    // 4-byte stores of a K-contiguous operand (4 lanes per row, 16 rows per
-    // wave) land in 64 different banks.
-    static constexpr int LDA = BM + 4, LDB = BN + 4;
+    static constexpr int LDA = BM + (LKV_ == 2 ? 0 : 4), LDB = BN + (LKV_ == 2 ? 0 : 4);
     static constexpr int A_FLOATS = BK * LDA, B_FLOATS = BK * LDB;
     static constexpr int STAGE_FLOATS = A_FLOATS + B_FLOATS;
     static constexpr int LDS_BYTES = STAGES * STAGE_FLOATS * 4;
+    static constexpr int KGROUPS = BK / 4;
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
     static_assert(MB == 1 || MB == 2 || MB == 4, "operand reads are 4, 8 or 16 bytes");
     static_assert(NB == 1 || NB == 2 || NB == 4, "operand reads are 4, 8 or 16 bytes");
     static_assert(BK % 4 == 0 && BK >= 4, "K tile is a multiple of one 16-byte load");
+    static_assert((BM & (BM - 1)) == 0 && (BN & (BN - 1)) == 0 && BM >= 32 && BN >= 32, "rotation wraps with a mask");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
 };
 
+// Column of the LDS image that holds element x of k row `k` (extent BR, a power of two).
+template <int BR, int ROT>
+__device__ __forceinline__ int rot_col(int x, int k)
+{
+    return ROT == 0 ? x : ((x + ROT * (k >> 2)) & (BR - 1));
+}
+
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}).
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+template <int U>
+__device__ __forceinline__ typename VecOf<U>::type gather_column(const floatx4 (&rows)[U], int j)
+{
+    typename VecOf<U>::type o;
+    if constexpr (U == 1) {
+        o = rows[0][j];
+    } else {
+#pragma unroll
+        for (int it = 0; it < U; ++it) o[it] = rows[it][j];
+    }
+    return o;
+}
+
+// All loaders share one interface.  A tile is loaded in NLOAD pieces (load_piece<I>, one 16-byte
+// global load each on the fast path) and stored to LDS in NSTORE pieces (store_piece<I>), so that the
+// main loop can issue them one at a time between MFMAs; advance() moves to the next K tile.  Global
+// addresses are a workgroup-uniform tile pointer (kept in scalar registers, advanced once per tile)
+// plus per-thread 32-bit byte offsets that never change, so the K loop spends no vector ALU work on
+// addressing.  The host guarantees leading dimensions small enough for those offsets (ld <= 2^22).
+//
 // ---------------------------------------------------------------------------------------------
 // Loader for an operand stored contiguously along k: element (r, k) at base[r*ld + k].
 // Used for A when transA == N, for B when transB == T, and for the filters of the convolution.
-// Thread t owns 16-byte quads q = t + it*NT of the BR x BK tile, quad q = (row q / (BK/4), k quad
-// q % (BK/4)); it keeps them in registers between the global load and the transposing LDS store.
-template <int BR, int BK, int NT, int LD, bool VEC>
+// The BR x BK tile is cut into units of U rows x one 16-byte k quad (U = 4, 2 or 1, as many as the
+// tile gives each thread).  Consecutive lanes take the k quads of one row group, so a wave reads
+// whole 64-byte row segments.  A thread loads the U quads of a unit, which gives it a U x 4 block of
+// the tile in registers, and stores that block transposed: four LDS stores of U consecutive floats,
+// one per k.  The lanes the LDS serves together in one cycle (8 lanes of a 16-byte store, 16 of an
+// 8-byte one, 32 of a 4-byte one) hold all BK/4 k quads of a few row groups; with the image rows of
+// k quad kq rotated by 8*kq floats their addresses fall into distinct banks
+// (bank = 8*kq + U*rg + 0..U-1 mod 32), measured as zero SQ_LDS_BANK_CONFLICT cycles.
+template <int BR, int BK, int NT, int LD, int ROT, bool VEC>
 struct LoaderK {
-    static constexpr int QPR = BK / 4;
-    static constexpr int NQ = (BR * QPR) / NT;
-    static_assert((BR * QPR) % NT == 0 && NQ >= 1, "tile must split evenly over the threads");
-    const float *p[NQ];
-    floatx4 v[NQ];
-    int row0, kq;
+    static constexpr int QPR = BK / 4;          // k quads per row
+    static constexpr int NQ = (BR * QPR) / NT;  // quads per thread
+    static constexpr int U = NQ >= 4 ? 4 : NQ;  // rows per unit
+    static constexpr int UNITS = NQ / U;        // units per thread
+    static constexpr int RG_STEP = NT / QPR;    // row groups between a thread's units
+    static constexpr int NLOAD = UNITS * U, NSTORE = UNITS * 4;
+    static_assert((BR * QPR) % NT == 0 && NQ >= 1 && NQ % U == 0, "tile must split evenly over the threads");
+    static_assert((U == 1 || U == 2 || U == 4) && LD % 4 == 0 && ROT > 0 && ROT % 4 == 0, "layout assumptions");
+    typedef typename VecOf<U>::type UV;
+    const char *tile;         // &base[r0*ld + k], uniform over the workgroup
+    uint32_t off[UNITS][U];   // byte offset of each quad from `tile`
+    floatx4 v[UNITS][U];
+    int lds[UNITS];           // float offset of the unit's (rotated) column in row kq*4 of the image
+    int kq;
 
     // r0: first row of this tile, R: number of rows of the operand (rows past the end re-read
     // row R-1; their products land in rows/columns of C that are never stored).
     __device__ __forceinline__ void init(const float *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
     {
-        row0 = tid / QPR;
         kq = tid % QPR;
+        const int rg0 = tid / QPR;
+        tile = reinterpret_cast<const char *>(base + r0 * ld + k0);
 #pragma unroll
-        for (int it = 0; it < NQ; ++it) {
-            int64_t gr = r0 + row0 + it * (NT / QPR);
-            gr = gr < R ? gr : R - 1;
-            p[it] = base + gr * ld + k0 + kq * 4;
+        for (int u = 0; u < UNITS; ++u) {
+            const int row = (rg0 + u * RG_STEP) * U;
+            lds[u] = kq * 4 * LD + rot_col<BR, ROT>(row, kq * 4);
+#pragma unroll
+            for (int it = 0; it < U; ++it) {
+                int64_t lr = row + it;
+                lr = r0 + lr < R ? lr : R - 1 - r0;
+                off[u][it] = (uint32_t)((lr * ld + kq * 4) * 4);
+            }
         }
     }
-    __device__ __forceinline__ void load()
+    template <int I>
+    __device__ __forceinline__ void load_piece()
     {
-#pragma unroll
-        for (int it = 0; it < NQ; ++it) {
-            if (VEC) {
-                v[it] = *reinterpret_cast<const floatx4 *>(p[it]);
-            } else {
-                v[it][0] = p[it][0];
-                v[it][1] = p[it][1];
-                v[it][2] = p[it][2];
-                v[it][3] = p[it][3];
-            }
-            p[it] += BK;
+        constexpr int u = I / U, it = I % U;
+        const char *q = tile + off[u][it];
+        if (VEC) {
+            v[u][it] = *reinterpret_cast<const floatx4 *>(q);
+        } else {
+            const float *f = reinterpret_cast<const float *>(q);
+            v[u][it][0] = f[0];
+            v[u][it][1] = f[1];
+            v[u][it][2] = f[2];
+            v[u][it][3] = f[3];
         }
+    }
+    __device__ __forceinline__ void advance() { tile += BK * 4; }
+    template <int I>
+    __device__ __forceinline__ void store_piece(float *S) const
+    {
+        constexpr int u = I / 4, j = I % 4;
+        *reinterpret_cast<UV *>(&S[lds[u] + j * LD]) = gather_column<U>(v[u], j);
     }
     // Last, partial K tile: only k < krem exists; the rest of the tile is zero on both operands.
     __device__ __forceinline__ void load_tail(int krem)
     {
 #pragma unroll
-        for (int it = 0; it < NQ; ++it) {
+        for (int u = 0; u < UNITS; ++u)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[it][j] = (kq * 4 + j < krem) ? p[it][j] : 0.0f;
-        }
-    }
-    __device__ __forceinline__ void store(float *S) const
-    {
+            for (int it = 0; it < U; ++it) {
+                const float *f = reinterpret_cast<const float *>(tile + off[u][it]);
 #pragma unroll
-        for (int it = 0; it < NQ; ++it) {
-            const int row = row0 + it * (NT / QPR);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) S[(kq * 4 + j) * LD + row] = v[it][j];
-        }
+                for (int j = 0; j < 4; ++j) v[u][it][j] = (kq * 4 + j < krem) ? f[j] : 0.0f;
+            }
     }
 };
 
-// Loader for an operand stored contiguously along its own index: element (r, k) at base[k*ld + r].
-// Used for A when transA == T and for B when transB == N.  Quads run along r; NT is a multiple of
-// the quads per k row, so a thread keeps one r quad and walks k.
+// Comparison variant for the unrotated, padded image (LD = BR + 4): 4 consecutive lanes per row,
+// 4-byte transposing stores (two-way bank conflicts on every store).
 template <int BR, int BK, int NT, int LD, bool VEC>
-struct LoaderMN {
-    static constexpr int QPR = BR / 4;
-    static constexpr int NQ = (BK * QPR) / NT;
-    static constexpr int KSTEP = NT / QPR;
-    static_assert((BK * QPR) % NT == 0 && NQ >= 1 && NT % QPR == 0, "tile must split evenly over the threads");
-    const float *p;   // row k0 + krow of the operand
-    int64_t kstride;  // KSTEP * ld
-    int64_t tstride;  // BK * ld
-    int c[4];         // column offsets of the four elements (clamped to the last valid one)
+struct LoaderK0 {
+    static constexpr int QPR = BK / 4;
+    static constexpr int NQ = (BR * QPR) / NT;
+    static constexpr int NLOAD = NQ, NSTORE = NQ * 4;
+    static_assert((BR * QPR) % NT == 0 && NQ >= 1, "tile must split evenly over the threads");
+    const char *tile;
+    uint32_t off[NQ];
     floatx4 v[NQ];
-    int krow, rq;
+    int row0, kq;
 
     __device__ __forceinline__ void init(const float *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
     {
-        krow = tid / QPR;
-        rq = tid % QPR;
-        p = base + (k0 + krow) * ld;
-        kstride = (int64_t)KSTEP * ld;
-        tstride = (int64_t)BK * ld;
-        if (VEC) {
-            // R is a multiple of 4 on this path: a quad is wholly inside or wholly outside.
-            int64_t gr = r0 + rq * 4;
-            gr = gr + 4 <= R ? gr : R - 4;
-            p += gr;
-            c[0] = 0; c[1] = 1; c[2] = 2; c[3] = 3;
-        } else {
-            p += r0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                int64_t lr = rq * 4 + j;
-                c[j] = (int)(r0 + lr < R ? lr : R - 1 - r0);
-            }
-        }
-    }
-    __device__ __forceinline__ void load()
-    {
+        row0 = tid / QPR;
+        kq = tid % QPR;
+        tile = reinterpret_cast<const char *>(base + r0 * ld + k0);
 #pragma unroll
         for (int it = 0; it < NQ; ++it) {
-            const float *q = p + it * kstride;
-            if (VEC) {
-                v[it] = *reinterpret_cast<const floatx4 *>(q);
-            } else {
-                v[it][0] = q[c[0]];
-                v[it][1] = q[c[1]];
-                v[it][2] = q[c[2]];
-                v[it][3] = q[c[3]];
-            }
+            int64_t lr = row0 + it * (NT / QPR);
+            lr = r0 + lr < R ? lr : R - 1 - r0;
+            off[it] = (uint32_t)((lr * ld + kq * 4) * 4);
         }
-        p += tstride;
+    }
+    template <int I>
+    __device__ __forceinline__ void load_piece()
+    {
+        const char *q = tile + off[I];
+        if (VEC) {
+            v[I] = *reinterpret_cast<const floatx4 *>(q);
+        } else {
+            const float *f = reinterpret_cast<const float *>(q);
+            v[I][0] = f[0];
+            v[I][1] = f[1];
+            v[I][2] = f[2];
+            v[I][3] = f[3];
+        }
+    }
+    __device__ __forceinline__ void advance() { tile += BK * 4; }
+    template <int I>
+    __device__ __forceinline__ void store_piece(float *S) const
+    {
+        constexpr int it = I / 4, j = I % 4;
+        S[(kq * 4 + j) * LD + row0 + it * (NT / QPR)] = v[it][j];
     }
     __device__ __forceinline__ void load_tail(int krem)
     {
 #pragma unroll
         for (int it = 0; it < NQ; ++it) {
-            const float *q = p + it * kstride;
-            const bool ok = krow + it * KSTEP < krem;
+            const float *f = reinterpret_cast<const float *>(tile + off[it]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[it][j] = ok ? q[c[j]] : 0.0f;
+            for (int j = 0; j < 4; ++j) v[it][j] = (kq * 4 + j < krem) ? f[j] : 0.0f;
         }
-    }
-    __device__ __forceinline__ void store(float *S) const
-    {
-#pragma unroll
-        for (int it = 0; it < NQ; ++it)
-            *reinterpret_cast<floatx4 *>(&S[(krow + it * KSTEP) * LD + rq * 4]) = v[it];
     }
 };
 
+template <int LKV, int BR, int BK, int NT, int LD, int ROT, bool VEC>
+struct LoaderKSel {
+    typedef LoaderK<BR, BK, NT, LD, ROT, VEC> type;
+};
+template <int BR, int BK, int NT, int LD, int ROT, bool VEC>
+struct LoaderKSel<0, BR, BK, NT, LD, ROT, VEC> {
+    typedef LoaderK0<BR, BK, NT, LD, VEC> type;
+};
+
+// Loader for an operand stored contiguously along its own index: element (r, k) at base[k*ld + r].
+// Used for A when transA == T and for B when transB == N.  Quads run along r; NT is a multiple of
+// the quads per k row, so a thread keeps one r quad and walks k.  16-byte global loads, 16-byte LDS
+// stores; the lanes served together write one contiguous (rotated) run of an image row.
+template <int BR, int BK, int NT, int LD, int ROT, bool VEC>
+struct LoaderMN {
+    static constexpr int QPR = BR / 4;
+    static constexpr int NQ = (BK * QPR) / NT;
+    static constexpr int KSTEP = NT / QPR;
+    static constexpr int NLOAD = NQ, NSTORE = NQ;
+    static_assert((BK * QPR) % NT == 0 && NQ >= 1 && NT % QPR == 0, "tile must split evenly over the threads");
+    const char *tile;   // &base[k*ld + r0], uniform over the workgroup
+    int64_t tstride;    // bytes per K tile: BK * ld * 4
+    uint32_t off[NQ];   // byte offset of k row krow + it*KSTEP, column of the quad (VEC) or 0 (scalar path)
+    uint32_t c[4];      // scalar path: byte offsets of the four elements (clamped to the last valid one)
+    floatx4 v[NQ];
+    int lds[NQ];
+    int krow;
+
+    __device__ __forceinline__ void init(const float *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
+    {
+        krow = tid / QPR;
+        const int rq = tid % QPR;
+        tile = reinterpret_cast<const char *>(base + k0 * ld + r0);
+        tstride = (int64_t)BK * ld * 4;
+        int64_t quad = rq * 4;  // VEC: R is a multiple of 4, a quad is wholly inside or wholly outside
+        if (VEC) quad = r0 + quad + 4 <= R ? quad : R - 4 - r0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t lr = rq * 4 + j;
+            c[j] = (uint32_t)((r0 + lr < R ? lr : R - 1 - r0) * 4);
+        }
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) {
+            const int k = krow + it * KSTEP;
+            off[it] = (uint32_t)((k * ld + (VEC ? quad : 0)) * 4);
+            lds[it] = k * LD + rot_col<BR, ROT>(rq * 4, k);
+        }
+    }
+    template <int I>
+    __device__ __forceinline__ void load_piece()
+    {
+        const char *q = tile + off[I];
+        if (VEC) {
+            v[I] = *reinterpret_cast<const floatx4 *>(q);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[I][j] = *reinterpret_cast<const float *>(q + c[j]);
+        }
+    }
+    __device__ __forceinline__ void advance() { tile += tstride; }
+    template <int I>
+    __device__ __forceinline__ void store_piece(float *S) const
+    {
+        *reinterpret_cast<floatx4 *>(&S[lds[I]]) = v[I];
+    }
+    __device__ __forceinline__ void load_tail(int krem)
+    {
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) {
+            const char *q = tile + off[it];
+            const bool ok = krow + it * KSTEP < krem;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[it][j] = ok ? *reinterpret_cast<const float *>(q + (VEC ? 4 * j : c[j])) : 0.0f;
+        }
+    }
+};
+
+template <class L>
+__device__ __forceinline__ void load_tile(L &l)
+{
+    static_for<L::NLOAD>([&](auto ic) { l.template load_piece<decltype(ic)::value>(); });
+    l.advance();
+}
+template <class L>
+__device__ __forceinline__ void store_tile(const L &l, float *S)
+{
+    static_for<L::NSTORE>([&](auto ic) { l.template store_piece<decltype(ic)::value>(S); });
+}
+
 // ---------------------------------------------------------------------------------------------
-// MFMA macro-tile: one K tile (BK deep) from LDS into the accumulators.
+// MFMA macro-tile.  A K tile is consumed in groups of 4 k (two MFMA k steps).  The operand fragments
+// of a group are one LDS read per operand and k step, fetched one group ahead of the MFMAs that use
+// them (and the first group of the next K tile during the last group of this one).
 template <class Cfg>
-__device__ __forceinline__ void mma_stage(const float *As, const float *Bs,
-                                          floatx16 (&acc)[Cfg::MB][Cfg::NB], int a_off, int b_off)
+struct Frag {
+    typename VecOf<Cfg::MB>::type a[2];
+    typename VecOf<Cfg::NB>::type b[2];
+};
+
+template <int N>
+__device__ __forceinline__ float vec_elem(const typename VecOf<N>::type &v, int x)
+{
+    if constexpr (N == 1) return v; else return v[x];
+}
+
+// Fragment read piece R of k group G: R = 2*s2 + (0: rows operand, 1: cols operand).
+// a_off[g] / b_off[g]: the lane's float offsets into a k row of k group g (rotation and its k = h row applied).
+template <class Cfg, int G, int R>
+__device__ __forceinline__ void load_frag_piece(Frag<Cfg> &f, const float *As, const float *Bs,
+                                                const int (&a_off)[Cfg::KGROUPS], const int (&b_off)[Cfg::KGROUPS])
 {
     typedef typename VecOf<Cfg::MB>::type AV;
     typedef typename VecOf<Cfg::NB>::type BV;
-#pragma unroll
-    for (int s = 0; s < Cfg::BK / 2; ++s) {
-        const AV av = *reinterpret_cast<const AV *>(As + a_off + 2 * s * Cfg::LDA);
-        const BV bv = *reinterpret_cast<const BV *>(Bs + b_off + 2 * s * Cfg::LDB);
-        float a[Cfg::MB], b[Cfg::NB];
-        if constexpr (Cfg::MB == 1) { a[0] = av; } else {
-#pragma unroll
-            for (int x = 0; x < Cfg::MB; ++x) a[x] = av[x];
-        }
-        if constexpr (Cfg::NB == 1) { b[0] = bv; } else {
-#pragma unroll
-            for (int x = 0; x < Cfg::NB; ++x) b[x] = bv[x];
-        }
-#pragma unroll
-        for (int bm = 0; bm < Cfg::MB; ++bm)
-#pragma unroll
-            for (int bn = 0; bn < Cfg::NB; ++bn)
-                acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bm], b[bn], acc[bm][bn], 0, 0, 0);
+    constexpr int s2 = R / 2;
+    if constexpr (R % 2 == 0)
+        f.a[s2] = *reinterpret_cast<const AV *>(As + a_off[G] + (4 * G + 2 * s2) * Cfg::LDA);
+    else
+        f.b[s2] = *reinterpret_cast<const BV *>(Bs + b_off[G] + (4 * G + 2 * s2) * Cfg::LDB);
+}
+template <class Cfg, int G>
+__device__ __forceinline__ void load_frag(Frag<Cfg> &f, const float *As, const float *Bs,
+                                          const int (&a_off)[Cfg::KGROUPS], const int (&b_off)[Cfg::KGROUPS])
+{
+    static_for<4>([&](auto rc) { load_frag_piece<Cfg, G, decltype(rc)::value>(f, As, Bs, a_off, b_off); });
+}
+
+// MFMA number M (0 .. 2*MB*NB-1) of a k group.
+template <class Cfg, int M>
+__device__ __forceinline__ void mma_one(const Frag<Cfg> &f, floatx16 (&acc)[Cfg::MB][Cfg::NB])
+{
+    constexpr int s2 = M / (Cfg::MB * Cfg::NB), bm = (M / Cfg::NB) % Cfg::MB, bn = M % Cfg::NB;
+    acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x2f32(vec_elem<Cfg::MB>(f.a[s2], bm), vec_elem<Cfg::NB>(f.b[s2], bn),
+                                                       acc[bm][bn], 0, 0, 0);
+}
+
+// One K tile, generic form: `cur` holds group 0 on entry.  When next_A is not null, group 0 of that
+// stage is left in `cur` on exit (it must already be visible in LDS).
+template <class Cfg, int G>
+__device__ __forceinline__ void mma_groups_from(Frag<Cfg> &cur, const float *As, const float *Bs, const float *next_A,
+                                                const float *next_B, floatx16 (&acc)[Cfg::MB][Cfg::NB],
+                                                const int (&a_off)[Cfg::KGROUPS], const int (&b_off)[Cfg::KGROUPS])
+{
+    Frag<Cfg> nxt;
+    if constexpr (G + 1 < Cfg::KGROUPS) {
+        load_frag<Cfg, G + 1>(nxt, As, Bs, a_off, b_off);
+    } else {
+        if (next_A != nullptr) load_frag<Cfg, 0>(nxt, next_A, next_B, a_off, b_off);
     }
+    static_for<2 * Cfg::MB * Cfg::NB>([&](auto mc) { mma_one<Cfg, decltype(mc)::value>(cur, acc); });
+    if constexpr (G + 1 < Cfg::KGROUPS) {
+        cur = nxt;
+        mma_groups_from<Cfg, G + 1>(cur, As, Bs, next_A, next_B, acc, a_off, b_off);
+    } else {
+        if (next_A != nullptr) cur = nxt;
+    }
+}
+
+// One K tile in the steady state of the pipeline (no conditions: tile t+STAGES-1 is in registers and
+// is stored, tile t+STAGES exists and is loaded, tile t+1 is visible in LDS).  CS is the stage of tile
+// t, a compile-time constant, so every LDS address is a per-lane base plus an immediate.  A wave's
+// MFMA stream only stays dense if the other instructions are issued in the shadow of MFMAs that are
+// already running: each MFMA is followed by at most a few of them, in a fixed order pinned with
+// scheduling barriers: first the fragment reads of the next k group, then the LDS stores of the
+// staged tile, then the global loads of the tile after it.
+template <class Cfg, int CS, class RL, class CL>
+__device__ __forceinline__ void steady_iter(RL &rl, CL &cl, Frag<Cfg> &cur, floatx16 (&acc)[Cfg::MB][Cfg::NB],
+                                            float *smem, const int (&a_off)[Cfg::KGROUPS],
+                                            const int (&b_off)[Cfg::KGROUPS])
+{
+    constexpr int S = Cfg::STAGES, KG = Cfg::KGROUPS, NM = 2 * Cfg::MB * Cfg::NB;
+    constexpr int FILL = (CS + S - 1) % S, NS = (CS + 1) % S;
+    float *fill_a = smem + FILL * Cfg::STAGE_FLOATS, *fill_b = fill_a + Cfg::A_FLOATS;
+    const float *As = smem + CS * Cfg::STAGE_FLOATS, *Bs = As + Cfg::A_FLOATS;
+    const float *An = smem + NS * Cfg::STAGE_FLOATS, *Bn = An + Cfg::A_FLOATS;
+    constexpr int NWA = RL::NSTORE, NWB = CL::NSTORE, NVA = RL::NLOAD, NVB = CL::NLOAD;
+    constexpr int NSIDE = NWA + NWB + NVA + NVB;
+    constexpr int SLOTS = KG * NM - (NM >= 4 ? 4 * KG : 0);  // slots not used by fragment reads
+    constexpr int PER = (NSIDE + SLOTS - 1) / SLOTS;
+    static_for<KG>([&](auto gc) {
+        constexpr int g = decltype(gc)::value;
+        Frag<Cfg> nxt;
+        static_for<NM>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mma_one<Cfg, m>(cur, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            // fragment reads of the next group (of the next tile after the last group)
+            static_for<4>([&](auto rc) {
+                constexpr int r = decltype(rc)::value;
+                constexpr int slot = NM >= 4 ? r : (r * NM) / 4;
+                if constexpr (slot == m) {
+                    if constexpr (g + 1 < KG)
+                        load_frag_piece<Cfg, g + 1, r>(nxt, As, Bs, a_off, b_off);
+                    else
+                        load_frag_piece<Cfg, 0, r>(nxt, An, Bn, a_off, b_off);
+                }
+            });
+            // staged tile -> LDS, then next tile -> registers
+            if constexpr (NM < 4 || m >= 4) {
+                constexpr int sl = g * (NM >= 4 ? NM - 4 : NM) + (NM >= 4 ? m - 4 : m);
+                static_for<PER>([&](auto pc) {
+                    constexpr int j = sl * PER + decltype(pc)::value;
+                    if constexpr (j < NWA) {
+                        rl.template store_piece<j>(fill_a);
+                    } else if constexpr (j < NWA + NWB) {
+                        cl.template store_piece<j - NWA>(fill_b);
+                    } else if constexpr (j < NWA + NWB + NVA) {
+                        rl.template load_piece<j - NWA - NWB>();
+                        if constexpr (j == NWA + NWB + NVA - 1) rl.advance();
+                    } else if constexpr (j < NSIDE) {
+                        cl.template load_piece<j - NWA - NWB - NVA>();
+                        if constexpr (j == NSIDE - 1) cl.advance();
+                    }
+                });
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        cur = nxt;
+    });
+    __syncthreads();
 }
 
 // Software pipeline over the K range of one tile.  T full K tiles, then an optional partial one of
 // krem (< BK) columns.  LDS holds STAGES tiles; registers hold one more in flight, so a global load
 // has a whole K tile of MFMA work to land.  One barrier per K tile: the store of tile t+STAGES-1
-// goes to the stage whose readers finished before the previous barrier.
+// goes to the stage whose readers finished before the previous barrier.  With 3 or more stages tile
+// t+1 is already visible while tile t is computed, which is what allows the fragment prefetch across
+// the barrier and the branch-free steady state (steady_iter, unrolled over the stage ring); the first
+// and last tiles, and 2-stage configurations, go through the generic loop with its conditions.
 template <class Cfg, class RowLoader, class ColLoader>
 __device__ __forceinline__ void mainloop(RowLoader &rl, ColLoader &cl, int T, int krem,
                                          floatx16 (&acc)[Cfg::MB][Cfg::NB], float *smem)
 {
     constexpr int S = Cfg::STAGES;
+    constexpr bool kAhead = S >= 3;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM;
     const int wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
     const int i = lane & 31, h = lane >> 5;
-    const int a_off = h * Cfg::LDA + wm0 + Cfg::MB * i;
-    const int b_off = h * Cfg::LDB + wn0 + Cfg::NB * i;
+    int a_off[Cfg::KGROUPS], b_off[Cfg::KGROUPS];
+#pragma unroll
+    for (int g = 0; g < Cfg::KGROUPS; ++g) {
+        a_off[g] = h * Cfg::LDA + rot_col<Cfg::BM, Cfg::ROT>(wm0 + Cfg::MB * i, 4 * g);
+        b_off[g] = h * Cfg::LDB + rot_col<Cfg::BN, Cfg::ROT>(wn0 + Cfg::NB * i, 4 * g);
+    }
 
 #pragma unroll
     for (int s = 0; s < S - 1; ++s) {
         if (s < T) {
-            rl.load();
-            cl.load();
-            rl.store(smem + s * Cfg::STAGE_FLOATS);
-            cl.store(smem + s * Cfg::STAGE_FLOATS + Cfg::A_FLOATS);
+            load_tile(rl);
+            load_tile(cl);
+            store_tile(rl, smem + s * Cfg::STAGE_FLOATS);
+            store_tile(cl, smem + s * Cfg::STAGE_FLOATS + Cfg::A_FLOATS);
         }
     }
     if (S - 1 < T) {
-        rl.load();
-        cl.load();
+        load_tile(rl);
+        load_tile(cl);
     }
     __syncthreads();
 
-    int cur = 0;       // stage holding tile t
+    Frag<Cfg> cur;
+    if (T > 0) load_frag<Cfg, 0>(cur, smem, smem + Cfg::A_FLOATS, a_off, b_off);
+    int t = 0;
+    if constexpr (kAhead) {
+        // S iterations at a time keep the stage of tile t equal to 0 at the top of the loop
+        while (t + 2 * S - 1 < T) {
+            static_for<S>([&](auto sc) { steady_iter<Cfg, decltype(sc)::value>(rl, cl, cur, acc, smem, a_off, b_off); });
+            t += S;
+        }
+    }
+    int cs = 0;        // stage holding tile t (t is a multiple of S here)
     int fill = S - 1;  // stage that receives tile t + S - 1
-    for (int t = 0; t < T; ++t) {
+    for (; t < T; ++t) {
         if (t + S - 1 < T) {
-            rl.store(smem + fill * Cfg::STAGE_FLOATS);
-            cl.store(smem + fill * Cfg::STAGE_FLOATS + Cfg::A_FLOATS);
+            store_tile(rl, smem + fill * Cfg::STAGE_FLOATS);
+            store_tile(cl, smem + fill * Cfg::STAGE_FLOATS + Cfg::A_FLOATS);
         }
         if (t + S < T) {
-            rl.load();
-            cl.load();
+            load_tile(rl);
+            load_tile(cl);
         }
-        mma_stage<Cfg>(smem + cur * Cfg::STAGE_FLOATS, smem + cur * Cfg::STAGE_FLOATS + Cfg::A_FLOATS, acc,
-                       a_off, b_off);
-        cur = (cur + 1 == S) ? 0 : cur + 1;
+        const int ns = (cs + 1 == S) ? 0 : cs + 1;
+        const float *As = smem + cs * Cfg::STAGE_FLOATS;
+        const float *An = smem + ns * Cfg::STAGE_FLOATS;
+        const bool more = t + 1 < T;
+        mma_groups_from<Cfg, 0>(cur, As, As + Cfg::A_FLOATS, (kAhead && more) ? An : nullptr, An + Cfg::A_FLOATS, acc,
+                                a_off, b_off);
+        cs = ns;
         fill = (fill + 1 == S) ? 0 : fill + 1;
         __syncthreads();
+        if (!kAhead && more) load_frag<Cfg, 0>(cur, An, An + Cfg::A_FLOATS, a_off, b_off);
     }
     if (krem > 0) {
         rl.load_tail(krem);
         cl.load_tail(krem);
-        rl.store(smem);
-        cl.store(smem + Cfg::A_FLOATS);
+        store_tile(rl, smem);
+        store_tile(cl, smem + Cfg::A_FLOATS);
         __syncthreads();
-        mma_stage<Cfg>(smem, smem + Cfg::A_FLOATS, acc, a_off, b_off);
+        load_frag<Cfg, 0>(cur, smem, smem + Cfg::A_FLOATS, a_off, b_off);
+        mma_groups_from<Cfg, 0>(cur, smem, smem + Cfg::A_FLOATS, nullptr, nullptr, acc, a_off, b_off);
     }
 }
 

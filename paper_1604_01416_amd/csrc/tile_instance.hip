@@ -16,8 +16,8 @@ template <>
 const CfgDesc &cfg_desc<DMATH_CFG_INDEX>()
 {
     static char name[64];
-    std::snprintf(name, sizeof(name), "%dx%dx%d_w%dx%d_s%d", ThisCfg::BM, ThisCfg::BN, ThisCfg::BK,
-                  ThisCfg::WAVES_M, ThisCfg::WAVES_N, ThisCfg::STAGES);
+    std::snprintf(name, sizeof(name), "%dx%dx%d_w%dx%d_s%d_l%d", ThisCfg::BM, ThisCfg::BN, ThisCfg::BK,
+                  ThisCfg::WAVES_M, ThisCfg::WAVES_N, ThisCfg::STAGES, ThisCfg::LKV);
     static const CfgDesc d = {
         name,
         ThisCfg::BM, ThisCfg::BN, ThisCfg::BK, ThisCfg::NT, ThisCfg::LDS_BYTES,
