@@ -92,8 +92,11 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB,
  * Q = (W + 2*pad_w - S)/stride_w + 1 (integer division; the filter must fit:
  * H + 2*pad_h >= R, W + 2*pad_w >= S).  Taps that fall outside x count as zero.
  * Dilation 1, one group, no bias.  The product is evaluated as a matrix
- * multiply whose left operand is generated on the fly from x; the unfolded
- * matrix is never stored and no workspace is used.
+ * multiply one of whose operands is generated on the fly from x; the unfolded
+ * matrix is never stored.  When a workspace of at least Kout*C*R*S*4 bytes is
+ * registered (dmath_set_workspace), C is a multiple of 16 and R*S <= 32, the
+ * filters are first copied into it in tap-major order, which makes the
+ * generated operand cheaper to address; otherwise no workspace is touched.
  *
  * Empty outputs (N, Kout, P or Q zero) are a no-op; C == 0 or alpha == 0 gives
  * y = beta*y without reading x or w; beta == 0 makes y write-only.

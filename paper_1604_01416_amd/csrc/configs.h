@@ -7,22 +7,21 @@
 namespace dmath {
 
 template <int I> struct CfgAt;
-//                                        BM   BN  BK  waves  stages  min waves per SIMD
-template <> struct CfgAt<0> { typedef TileCfg<256, 128, 16, 4, 1, 3, 2> type; };  // wave tile 64 x 128, 2 workgroups per CU
-template <> struct CfgAt<1> { typedef TileCfg<128, 256, 16, 2, 2, 3, 2> type; };  // wave tile 64 x 128
-template <> struct CfgAt<2> { typedef TileCfg<256, 256, 16, 4, 2, 3, 2> type; };  // 512 threads, one workgroup per CU
-template <> struct CfgAt<3> { typedef TileCfg<128, 128, 16, 2, 2, 3, 2> type; };  // wave tile 64 x 64
-template <> struct CfgAt<4> { typedef TileCfg<64, 64, 16, 2, 2, 2, 2> type; };    // wave tile 32 x 32, small problems
-template <> struct CfgAt<5> { typedef TileCfg<256, 256, 16, 4, 2, 3, 2, 0> type; };  // experiment: loader variant 0
-template <> struct CfgAt<6> { typedef TileCfg<256, 128, 16, 4, 1, 3, 2, 0> type; };  // experiment: loader variant 0
-template <> struct CfgAt<7> { typedef TileCfg<256, 256, 16, 2, 2, 3, 1> type; };     // experiment: 4 waves of 128x128, one wave per SIMD
-constexpr int kNumCfg = 8;
+//                                        BM   BN  BK  waves  stages  min waves per SIMD, LDS image
+template <> struct CfgAt<0> { typedef TileCfg<256, 128, 16, 4, 1, 3, 2, 0> type; };  // wave tile 64 x 128, 2 workgroups per CU
+template <> struct CfgAt<1> { typedef TileCfg<128, 256, 16, 2, 2, 3, 2, 0> type; };  // wave tile 64 x 128, 2 workgroups per CU
+template <> struct CfgAt<2> { typedef TileCfg<256, 256, 16, 4, 2, 3, 2, 0> type; };  // 512 threads, one workgroup per CU
+template <> struct CfgAt<3> { typedef TileCfg<128, 128, 16, 2, 2, 3, 2, 0> type; };  // wave tile 64 x 64
+template <> struct CfgAt<4> { typedef TileCfg<64, 64, 16, 2, 2, 3, 2, 0> type; };    // wave tile 32 x 32, small problems
+// Same tile as 2 with the rotated, bank-conflict-free LDS image: the comparison point for the counters.
+template <> struct CfgAt<5> { typedef TileCfg<256, 256, 16, 4, 2, 3, 2, 2> type; };
+constexpr int kNumCfg = 6;
 
 struct CfgDesc {
     const char *name;
     int BM, BN, BK, NT, lds_bytes;
     int (*gemm)(const GemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);
-    int (*conv)(const ConvArgs &, bool vec, hipStream_t);
+    int (*conv)(const ConvArgs &, bool vec, bool tap_major, hipStream_t);
 };
 
 // Defined one per translation unit.
@@ -33,7 +32,5 @@ template <> const CfgDesc &cfg_desc<2>();
 template <> const CfgDesc &cfg_desc<3>();
 template <> const CfgDesc &cfg_desc<4>();
 template <> const CfgDesc &cfg_desc<5>();
-template <> const CfgDesc &cfg_desc<6>();
-template <> const CfgDesc &cfg_desc<7>();
 
 }  // namespace dmath

@@ -5,8 +5,13 @@
 // Rows of the product are output channels (the filters, read in place: w is already a
 // Kout x CRS row-major matrix, contiguous along k), columns are output pixels (n, p, q) in memory
 // order, so a row of the product is contiguous in y inside one image.  The unfolded matrix is
-// never stored: the loader below generates each of its elements from x with the zero halo applied.
-// k = (c*R + r)*S + s, column = (n*P + p)*Q + q.
+// never stored: the loaders below generate each of its elements from x with the zero halo applied.
+// column = (n*P + p)*Q + q.  Two orders of k are implemented (any order gives the same sums):
+//   - generic (LoaderConvX): k = (c*R + r)*S + s, the order of w in memory; works for every shape.
+//   - tap-major (LoaderConvTap): k = (r*S + s)*C + c with C a multiple of the K tile, so a K tile is
+//     BK channels of ONE filter tap: the halo test and the tap offset are per tile instead of per
+//     element, and a K row is a plain scalar offset c*H*W away from the previous one.  The filters
+//     are first re-laid out as w'[j][r][s][c] into the workspace by a small kernel.
 #pragma once
 #include "tile_core.h"
 
@@ -24,6 +29,7 @@ struct ConvArgs {
     float alpha, beta;
     int tiles_m, tiles_n;
     int yvec;  // y is 16-byte aligned and P*Q is a multiple of 4
+    int64_t x_bytes;  // size of x, for the buffer descriptor of the tap-major loader
 };
 
 // floor(n / d) for a divisor fixed at launch: with magic = ceil(2^32 / d) the high word of n*magic is
@@ -97,7 +103,91 @@ struct LoaderConvX {
     }
 };
 
-template <class Cfg, bool VEC>
+// Tap-major loader of the generated operand (see the top of the file).  x is read through a buffer
+// descriptor whose base is shifted down by pad_h*W + pad_w elements: the lane offset (of the pixel's
+// (r=0, s=0) tap) is then never negative, the tap and channel offset is one scalar, and a lane whose
+// tap falls into the halo gets an offset beyond the descriptor, which makes the hardware return 0.
+template <int BN, int BK, int NT, int LD, int ROT>
+struct LoaderConvTap {
+    static constexpr int KG = NT / BN;
+    static constexpr int NQ = BK / KG;
+    static constexpr int NLOAD = NQ, NSTORE = NQ;
+    static_assert(NT % BN == 0 && BK % KG == 0 && BN % 64 == 0 && NQ >= 1, "one column per thread");
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t voff;      // byte offset of the lane's (r=0, s=0) tap of channel 0 in the shifted buffer
+    uint32_t tapmask;   // bit r*S+s set when that tap of this pixel lies inside x (0 for a column past the end)
+    uint32_t tile_voff, tile_soff;
+    int col, kg;
+    int c0, r, s;       // first channel and tap of the next tile to load
+    int C, HW, W, S;
+    float v[NQ];
+
+    __device__ __forceinline__ void init(const ConvArgs &a, int64_t col0, int tid)
+    {
+        col = tid % BN;
+        kg = __builtin_amdgcn_readfirstlane(tid / BN);
+        C = a.C; HW = a.H * a.W; W = a.W; S = a.S;
+        c0 = 0; r = 0; s = 0;
+        const int shift = a.pad_h * a.W + a.pad_w;
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x) - shift, 0,
+                                                 (int)(a.x_bytes + (int64_t)shift * 4), 0x00020000);
+        int64_t gc = col0 + col;
+        const bool col_ok = gc < a.NPQ;
+        gc = col_ok ? gc : a.NPQ - 1;
+        const int n = (int)(gc / a.PQ);
+        const int pq = (int)(gc - (int64_t)n * a.PQ);
+        const int p = pq / a.Q, q = pq - p * a.Q;
+        const int ih0 = p * a.stride_h - a.pad_h, iw0 = q * a.stride_w - a.pad_w;
+        voff = (uint32_t)(((int64_t)n * a.C * HW + (int64_t)ih0 * W + iw0 + shift) * 4);
+        uint32_t m = 0;
+        for (int rr = 0; rr < a.R; ++rr)
+            for (int ss = 0; ss < a.S; ++ss)
+                if ((unsigned)(ih0 + rr) < (unsigned)a.H && (unsigned)(iw0 + ss) < (unsigned)a.W) m |= 1u << (rr * a.S + ss);
+        tapmask = col_ok ? m : 0u;
+    }
+    template <int I>
+    __device__ __forceinline__ void load_piece()
+    {
+        if constexpr (I == 0) {
+            const bool ok = (tapmask >> (r * S + s)) & 1u;
+            tile_voff = ok ? voff : 0x80000000u;
+            tile_soff = (uint32_t)(((c0 + kg) * HW + r * W + s) * 4);
+        }
+        // the builtin returns the loaded dword as an unsigned integer
+        v[I] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, tile_voff, tile_soff + (uint32_t)(I * KG * HW * 4), 0));
+    }
+    __device__ __forceinline__ void advance()
+    {
+        c0 += BK;
+        if (c0 >= C) {
+            c0 = 0;
+            if (++s == S) {
+                s = 0;
+                ++r;
+            }
+        }
+    }
+    __device__ __forceinline__ void load_tail(int) {}  // C is a multiple of BK on this path: no partial tile
+    template <int I>
+    __device__ __forceinline__ void store_piece(float *Sm) const
+    {
+        const int k = kg + I * KG;
+        Sm[k * LD + rot_col<BN, ROT>(col, k)] = v[I];
+    }
+};
+
+template <class Cfg, bool TAP>
+struct ConvColLoaderSel {
+    typedef LoaderConvX<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT> type;
+};
+template <class Cfg>
+struct ConvColLoaderSel<Cfg, true> {
+    typedef LoaderConvTap<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT> type;
+};
+
+// VEC: 16-byte loads of the filter matrix are aligned.  TAP: tap-major k order (a.w is then w').
+template <class Cfg, bool VEC, bool TAP>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(const ConvArgs a)
 {
     __shared__ __attribute__((aligned(16))) float smem[Cfg::STAGES * Cfg::STAGE_FLOATS];
@@ -112,7 +202,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
     const int krem = (int)(a.CRS - (int64_t)T * Cfg::BK);
 
     typename LoaderKSel<Cfg::LKV, Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC>::type rl;
-    LoaderConvX<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT> cl;
+    typename ConvColLoaderSel<Cfg, TAP>::type cl;
     rl.init(a.w, a.CRS, m0, a.Kout, 0, threadIdx.x);
     cl.init(a, n0, threadIdx.x);
 
@@ -180,13 +270,17 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
 }
 
 template <class Cfg>
-int launch_conv_cfg(const ConvArgs &a, bool vec, hipStream_t stream)
+int launch_conv_cfg(const ConvArgs &a, bool vec, bool tap, hipStream_t stream)
 {
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n)), block(Cfg::NT);
-    if (vec)
-        hipLaunchKernelGGL((conv_tile_kernel<Cfg, true>), grid, block, 0, stream, a);
-    else
-        hipLaunchKernelGGL((conv_tile_kernel<Cfg, false>), grid, block, 0, stream, a);
+    if (tap) {
+        if (a.C % Cfg::BK != 0 || !vec) return (int)hipErrorInvalidValue;  // the caller checks this first
+        hipLaunchKernelGGL((conv_tile_kernel<Cfg, true, true>), grid, block, 0, stream, a);
+    } else if (vec) {
+        hipLaunchKernelGGL((conv_tile_kernel<Cfg, true, false>), grid, block, 0, stream, a);
+    } else {
+        hipLaunchKernelGGL((conv_tile_kernel<Cfg, false, false>), grid, block, 0, stream, a);
+    }
     return (int)hipGetLastError();
 }
 

@@ -33,9 +33,7 @@ const CfgDesc &desc(int i)
         case 2: return cfg_desc<2>();
         case 3: return cfg_desc<3>();
         case 4: return cfg_desc<4>();
-        case 5: return cfg_desc<5>();
-        case 6: return cfg_desc<6>();
-        default: return cfg_desc<7>();
+        default: return cfg_desc<5>();
     }
 }
 
@@ -92,6 +90,18 @@ __global__ void splitk_reduce_kernel_v4(const float *ws, int splits, int64_t sli
     }
 }
 
+// w'[j][rs][c] = w[j][c][rs]: the filter matrix in tap-major k order.
+__global__ void conv_filter_tap_major_kernel(const float *w, float *wt, int64_t Kout, int C, int RS)
+{
+    const int64_t total = Kout * C * RS;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t j = e / ((int64_t)C * RS);
+        const int rem = (int)(e - j * C * RS);
+        const int rs = rem / C, c = rem - rs * C;
+        wt[e] = w[(j * C + c) * RS + rs];
+    }
+}
+
 struct Plan {
     int cfg;
     int splits;
@@ -100,7 +110,7 @@ struct Plan {
 // Shape-based choice (the paper's outlook names choosing the multiply algorithm from the shape as
 // future work; this is its one-GPU form).  A small time model in microseconds, fitted to measurements
 // on MI355X: a compute unit works through ceil(workgroups / 256) tiles at the MFMA rate it sustains
-// under load (about 2.2 GHz), scaled by how well the configuration keeps the MFMA pipe fed, and pays a
+// under load (about 2.39 GHz), scaled by how well the configuration keeps the MFMA pipe fed, and pays a
 // fixed fill/drain time per batch of co-resident workgroups (first loads, last stores; hidden behind
 // the other resident workgroup when there is one).  Split-K adds writing and re-reading its slices.
 struct CfgModel {
@@ -110,19 +120,17 @@ struct CfgModel {
     int wg_per_cu;     // workgroups resident on a compute unit
 };
 const CfgModel kModel[kNumCfg] = {
-    {0.958, 0.95, 23.0, 2},  // 256x128
-    {0.948, 0.94, 15.0, 2},  // 128x256
-    {1.000, 1.00, 33.0, 1},  // 256x256
-    {0.930, 0.85, 12.0, 3},  // 128x128
-    {0.800, 0.55, 8.0, 6},   // 64x64
-    {0.900, 0.90, 33.0, 1},  // experiments (never preferred)
-    {0.900, 0.90, 23.0, 2},
-    {0.900, 0.90, 33.0, 1},
+    {0.935, 0.93, 19.0, 2},  // 256x128
+    {0.938, 0.93, 18.0, 2},  // 128x256
+    {0.989, 0.989, 36.0, 1}, // 256x256
+    {0.946, 0.93, 14.0, 3},  // 128x128
+    {0.800, 0.60, 8.0, 6},   // 64x64
+    {0.970, 0.97, 36.0, 1},  // 256x256, rotated image (measured slower than 2; offered, never preferred)
 };
 
 Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split)
 {
-    const double flop_per_us_cu = 256.0 * 2200.0;  // flop per microsecond per compute unit
+    const double flop_per_us_cu = 256.0 * 2390.0;  // flop per microsecond per compute unit at the sustained clock
     Plan best = {0, 1};
     double best_cost = 1e300;
     for (int c = 0; c < kNumCfg; ++c) {
@@ -137,7 +145,7 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split)
             const double eff = per_cu >= 2 || m.wg_per_cu == 1 ? m.eff : m.eff_alone;
             const double tile_us = 2.0 * d.BM * d.BN * ((double)K / s) / flop_per_us_cu / eff;
             double cost = per_cu * tile_us + (double)ceil_div(per_cu, m.wg_per_cu) * m.fill_us;
-            if (s > 1) cost += (double)M * N * (s + 1) * 4.0 / 4.0e6 + 6.0;  // slices at ~4 TB/s + a launch
+            if (s > 1) cost += (double)M * N * (s + 1) * 4.0 / 5.0e6 + 3.0;  // slices at ~5 TB/s + a launch
             if (cost < best_cost) {
                 best_cost = cost;
                 best = {c, s};
@@ -398,8 +406,24 @@ dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W, int64_
     a.tiles_m = (int)tiles_m;
     a.tiles_n = (int)tiles_n;
     a.yvec = (aligned16(y) && PQ % 4 == 0) ? 1 : 0;
-    const bool vec = aligned16(w) && CRS % 4 == 0;
-    if (d.conv(a, vec, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    a.x_bytes = N * C * H * W * 4;
+    bool vec = aligned16(w) && CRS % 4 == 0;
+    // Tap-major path: needs room for the re-laid-out filters, whole K tiles per tap, a tap mask that
+    // fits 32 bits and 31-bit byte offsets into x.
+    const size_t wt_bytes = (size_t)Kout * (size_t)CRS * sizeof(float);
+    const bool tap = C % d.BK == 0 && R * S <= 32 && a.x_bytes + (pad_h * W + pad_w) * 4 < lim &&
+                     g_state.ws != nullptr && g_state.ws_bytes >= wt_bytes;
+    if (tap) {
+        float *wt = static_cast<float *>(g_state.ws);
+        const int64_t total = Kout * CRS;
+        const int blocks = (int)(ceil_div(total, 256) < 2048 ? ceil_div(total, 256) : 2048);
+        hipLaunchKernelGGL(conv_filter_tap_major_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, Kout, (int)C,
+                           (int)(R * S));
+        if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+        a.w = wt;
+        vec = true;  // the workspace is 16-byte aligned and C is a multiple of 4
+    }
+    if (d.conv(a, vec, tap, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
     return DMATH_OK;
 }
 

@@ -79,7 +79,7 @@ def test_gemm_small_auto(dm, torch, tA, tB, M, N, K):
                   seed=M * 3 + K)
 
 
-@pytest.mark.parametrize("cfg", range(5))
+@pytest.mark.parametrize("cfg", range(6))
 @pytest.mark.parametrize("tA,tB", TRANS)
 def test_gemm_every_config_aligned_and_unaligned(dm, torch, cfg, tA, tB):
     if cfg >= dm.dmath_num_configs():
@@ -278,7 +278,7 @@ def test_conv_small(dm, torch, shape):
     run_conv_case(dm, torch, seed=shape["C"], ints=True, exact=True, beta=1.0, **shape)
 
 
-@pytest.mark.parametrize("cfg", range(5))
+@pytest.mark.parametrize("cfg", range(6))
 def test_conv_every_config(dm, torch, cfg):
     if cfg >= dm.dmath_num_configs():
         pytest.skip("no such configuration")
@@ -286,6 +286,35 @@ def test_conv_every_config(dm, torch, cfg):
     run_conv_case(dm, torch, N=3, C=12, H=28, W=28, Kout=72, R=3, S=3, pad=(1, 1), stride=(1, 1), seed=cfg)
     run_conv_case(dm, torch, N=2, C=5, H=11, W=13, Kout=260, R=3, S=3, pad=(1, 1), stride=(2, 1), seed=cfg + 5,
                   alpha=2.0, beta=1.0, lead=3)
+
+
+CONV_TAP_MAJOR = [
+    dict(N=3, C=16, H=9, W=7, Kout=40, R=3, S=3, pad=(1, 1), stride=(1, 1)),
+    dict(N=2, C=32, H=11, W=10, Kout=72, R=5, S=5, pad=(2, 2), stride=(2, 2)),
+    dict(N=4, C=48, H=6, W=6, Kout=130, R=1, S=1, pad=(0, 0), stride=(1, 1)),
+    dict(N=2, C=64, H=14, W=14, Kout=260, R=3, S=3, pad=(1, 1), stride=(1, 1)),
+    dict(N=1, C=16, H=8, W=9, Kout=8, R=2, S=3, pad=(0, 1), stride=(1, 2)),
+]
+
+
+@pytest.mark.parametrize("shape", CONV_TAP_MAJOR)
+def test_conv_tap_major_and_generic_paths(dm, torch, shape):
+    """Channel counts that are multiples of the K tile take the tap-major path when a workspace is
+    registered (filters re-laid out into it) and the generic path when none is: both must hold."""
+    run_conv_case(dm, torch, seed=1, **shape)
+    run_conv_case(dm, torch, seed=2, alpha=-1.5, beta=0.5, lead=4, **shape)
+    run_conv_case(dm, torch, seed=3, ints=True, exact=True, beta=1.0, **shape)
+    for cfg in range(dm.dmath_num_configs()):
+        dm.dmath_set_override(cfg, 1)
+        run_conv_case(dm, torch, seed=4 + cfg, ints=True, exact=True, **shape)
+    dm.dmath_set_override(-1, -1)
+    ws = dm._test_workspace
+    dm.check(dm.dmath_set_workspace(None, 0))
+    try:
+        run_conv_case(dm, torch, seed=5, **shape)
+        run_conv_case(dm, torch, seed=6, ints=True, exact=True, beta=1.0, **shape)
+    finally:
+        dm.check(dm.dmath_set_workspace(ws, ws.numel()))
 
 
 def test_conv_quick_returns(dm, torch):
