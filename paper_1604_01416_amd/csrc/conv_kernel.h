@@ -30,6 +30,7 @@ struct ConvArgs {
     int tiles_m, tiles_n;
     int yvec;  // y is 16-byte aligned and P*Q is a multiple of 4
     int64_t x_bytes;  // size of x, for the buffer descriptor of the tap-major loader
+    SplitPlan split;
 };
 
 // floor(n / d) for a divisor fixed at launch: with magic = ceil(2^32 / d) the high word of n*magic is
@@ -59,11 +60,11 @@ struct LoaderConvX {
     uint32_t magic_RS, magic_S;
     float v[NQ];
 
-    __device__ __forceinline__ void init(const ConvArgs &a, int64_t c0, int tid)
+    __device__ __forceinline__ void init(const ConvArgs &a, int64_t c0, int kstart, int tid)
     {
         col = tid % BN;
         kg = __builtin_amdgcn_readfirstlane(tid / BN);
-        knext = 0;
+        knext = kstart;
         H = a.H; W = a.W; S = a.S; RS = a.RS; HW = a.H * a.W; CRS = a.CRS;
         magic_RS = a.magic_RS; magic_S = a.magic_S;
         int64_t gc = c0 + col;
@@ -122,12 +123,15 @@ struct LoaderConvTap {
     int C, HW, W, S;
     float v[NQ];
 
-    __device__ __forceinline__ void init(const ConvArgs &a, int64_t col0, int tid)
+    __device__ __forceinline__ void init(const ConvArgs &a, int64_t col0, int kstart, int tid)
     {
         col = tid % BN;
         kg = __builtin_amdgcn_readfirstlane(tid / BN);
         C = a.C; HW = a.H * a.W; W = a.W; S = a.S;
-        c0 = 0; r = 0; s = 0;
+        const int tap0 = kstart / a.C;  // kstart is a multiple of the K tile, which divides C
+        c0 = kstart - tap0 * a.C;
+        r = tap0 / a.S;
+        s = tap0 - r * a.S;
         const int shift = a.pad_h * a.W + a.pad_w;
         rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x) - shift, 0,
                                                  (int)(a.x_bytes + (int64_t)shift * 4), 0x00020000);
@@ -193,18 +197,19 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
     __shared__ __attribute__((aligned(16))) float smem[Cfg::STAGES * Cfg::STAGE_FLOATS];
 
     const int tiles = a.tiles_m * a.tiles_n;
-    const int pid = xcd_contiguous_id(blockIdx.x, tiles);
+    const WorkItem wi = work_item(blockIdx.x, tiles, a.split);
     int tm, tn;
-    tile_coords<8>(pid, a.tiles_m, a.tiles_n, tm, tn);
+    tile_coords<8>(wi.tile, a.tiles_m, a.tiles_n, tm, tn);
     const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
 
-    const int T = (int)(a.CRS / Cfg::BK);
-    const int krem = (int)(a.CRS - (int64_t)T * Cfg::BK);
+    const int ktiles_total = (int)(a.CRS / Cfg::BK);
+    int kt0, T, krem;
+    slice_range(ktiles_total, (int)(a.CRS - (int64_t)ktiles_total * Cfg::BK), wi.slice, wi.nslice, kt0, T, krem);
 
     typename LoaderKSel<Cfg::LKV, Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC>::type rl;
     typename ConvColLoaderSel<Cfg, TAP>::type cl;
-    rl.init(a.w, a.CRS, m0, a.Kout, 0, threadIdx.x);
-    cl.init(a, n0, threadIdx.x);
+    rl.init(a.w, a.CRS, m0, a.Kout, (int64_t)kt0 * Cfg::BK, threadIdx.x);
+    cl.init(a, n0, kt0 * Cfg::BK, threadIdx.x);
 
     floatx16 acc[Cfg::MB][Cfg::NB];
 #pragma unroll
@@ -215,6 +220,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
             for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
 
     mainloop<Cfg>(rl, cl, T, krem, acc, smem);
+    if (!combine_slices<Cfg>(acc, a.split, wi)) return;
 
     // Epilogue: the lane's NB columns are NB consecutive output pixels; when P*Q is a multiple of 4
     // they lie in one image, 16-byte aligned.  Row j of the product is output channel j.
@@ -272,7 +278,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
 template <class Cfg>
 int launch_conv_cfg(const ConvArgs &a, bool vec, bool tap, hipStream_t stream)
 {
-    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n)), block(Cfg::NT);
+    const int tiles = a.tiles_m * a.tiles_n;
+    const dim3 grid((unsigned)(a.split.dp_tiles + (tiles - a.split.dp_tiles) * a.split.splits)), block(Cfg::NT);
     if (tap) {
         if (a.C % Cfg::BK != 0 || !vec) return (int)hipErrorInvalidValue;  // the caller checks this first
         hipLaunchKernelGGL((conv_tile_kernel<Cfg, true, true>), grid, block, 0, stream, a);

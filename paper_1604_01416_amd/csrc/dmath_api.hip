@@ -90,6 +90,12 @@ __global__ void splitk_reduce_kernel_v4(const float *ws, int splits, int64_t sli
     }
 }
 
+__global__ void zero_u32_kernel(unsigned *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 // w'[j][rs][c] = w[j][c][rs]: the filter matrix in tap-major k order.
 __global__ void conv_filter_tap_major_kernel(const float *w, float *wt, int64_t Kout, int C, int RS)
 {
@@ -104,15 +110,22 @@ __global__ void conv_filter_tap_major_kernel(const float *w, float *wt, int64_t 
 
 struct Plan {
     int cfg;
-    int splits;
+    int dp_tiles;  // tiles computed whole; the remaining tiles - dp_tiles are cut into `splits` slices
+    int splits;    // 1: nothing is split (dp_tiles == tiles)
 };
+// dp_tiles == 0 with splits > 1 (every tile split: skinny products) is run as plain split-K: each slice
+// writes an M x N array of raw sums to the workspace and a second kernel adds the slices in order;
+// measured faster than combining in the tile kernel when every workgroup has to publish its slice.
+// A split tail (dp_tiles > 0) is combined in the tile kernel by the last slice to arrive.
 
 // Shape-based choice (the paper's outlook names choosing the multiply algorithm from the shape as
 // future work; this is its one-GPU form).  A small time model in microseconds, fitted to measurements
-// on MI355X: a compute unit works through ceil(workgroups / 256) tiles at the MFMA rate it sustains
-// under load (about 2.39 GHz), scaled by how well the configuration keeps the MFMA pipe fed, and pays a
+// on MI355X: a compute unit works through its share of the tiles at the MFMA rate it sustains under
+// load (about 2.39 GHz), scaled by how well the configuration keeps the MFMA pipe fed, and pays a
 // fixed fill/drain time per batch of co-resident workgroups (first loads, last stores; hidden behind
-// the other resident workgroup when there is one).  Split-K adds writing and re-reading its slices.
+// the other resident workgroup when there is one).  Tiles past the last full round over the 256
+// compute units, or all tiles of a product with few of them, can be cut into K slices (see
+// combine_slices); slices pay for writing and re-reading their accumulators.
 struct CfgModel {
     double eff;        // fraction of the MFMA rate sustained in the K loop with a full compute unit
     double eff_alone;  // the same with a single workgroup on the compute unit (less latency hiding)
@@ -128,52 +141,115 @@ const CfgModel kModel[kNumCfg] = {
     {0.970, 0.97, 36.0, 1},  // 256x256, rotated image (measured slower than 2; offered, never preferred)
 };
 
-Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split)
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// Workspace a plan needs: slice accumulators, then one counter per split tile.
+size_t plan_bytes(const Plan &p, int64_t tiles, int64_t M, int64_t N)
+{
+    if (p.splits <= 1) return 0;
+    const CfgDesc &d = desc(p.cfg);
+    if (p.dp_tiles == 0) return (size_t)p.splits * (size_t)M * (size_t)N * sizeof(float);  // plain split-K
+    const size_t split_tiles = (size_t)(tiles - p.dp_tiles);
+    return align256(split_tiles * p.splits * (size_t)d.BM * d.BN * sizeof(float)) + align256(split_tiles * sizeof(unsigned));
+}
+
+double plan_cost(int c, int64_t tiles, int64_t dp, int s, int64_t K)
 {
     const double flop_per_us_cu = 256.0 * 2390.0;  // flop per microsecond per compute unit at the sustained clock
-    Plan best = {0, 1};
+    const CfgDesc &d = desc(c);
+    const CfgModel &m = kModel[c];
+    const int64_t items = (tiles - dp) * s;
+    const int64_t per_cu_whole = ceil_div(dp, kNumCU), per_cu_items = ceil_div(items, kNumCU);
+    const bool alone = per_cu_whole + per_cu_items < 2 && m.wg_per_cu > 1;
+    const double tile_us = 2.0 * d.BM * d.BN * (double)K / flop_per_us_cu / (alone ? m.eff_alone : m.eff);
+    double cost = per_cu_whole * tile_us + (double)ceil_div(per_cu_whole, m.wg_per_cu) * m.fill_us;
+    if (items > 0) {
+        cost += per_cu_items * (tile_us / s) + (double)ceil_div(per_cu_items, m.wg_per_cu) * m.fill_us;
+        // slices out and back at ~5 TB/s; a second launch (plain split-K) or the publication fences (split tail)
+        cost += (double)items * d.BM * d.BN * 8.0 / 5.0e6 + (dp == 0 ? 5.0 : 8.0);
+    }
+    return cost;
+}
+
+// only_cfg >= 0 restricts the search to that configuration; forced_split >= 1 fixes the split factor
+// (then every tile is split); allow_split == false forbids splitting.
+Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split, int only_cfg = -1, int forced_split = -1)
+{
+    Plan best = {only_cfg >= 0 ? only_cfg : 0, 0, 1};
     double best_cost = 1e300;
     for (int c = 0; c < kNumCfg; ++c) {
+        if (only_cfg >= 0 && c != only_cfg) continue;
         const CfgDesc &d = desc(c);
-        const CfgModel &m = kModel[c];
         const int64_t tiles = ceil_div(M, d.BM) * ceil_div(N, d.BN);
+        if (tiles > 0x7fffffff / 64) continue;
         const int64_t ktiles = K / d.BK;
-        const int max_split = allow_split ? 16 : 1;
-        for (int s = 1; s <= max_split; s *= 2) {
-            if (s > 1 && ktiles / s < 8) break;
-            const int64_t per_cu = ceil_div(tiles * s, kNumCU);
-            const double eff = per_cu >= 2 || m.wg_per_cu == 1 ? m.eff : m.eff_alone;
-            const double tile_us = 2.0 * d.BM * d.BN * ((double)K / s) / flop_per_us_cu / eff;
-            double cost = per_cu * tile_us + (double)ceil_div(per_cu, m.wg_per_cu) * m.fill_us;
-            if (s > 1) cost += (double)M * N * (s + 1) * 4.0 / 5.0e6 + 3.0;  // slices at ~5 TB/s + a launch
+        const int64_t full = (tiles / kNumCU) * kNumCU;
+        if (forced_split >= 1) {
+            const int s = (allow_split && ktiles >= forced_split) ? forced_split : 1;
+            const double cost = plan_cost(c, tiles, s > 1 ? 0 : tiles, s, K);
             if (cost < best_cost) {
                 best_cost = cost;
-                best = {c, s};
+                best = {c, (int)(s > 1 ? 0 : tiles), s};
+            }
+            continue;
+        }
+        for (int s = 1; s <= (allow_split ? 16 : 1); s *= 2) {
+            if (s > 1 && ktiles / s < 8) break;
+            // s == 1: no split.  s > 1: all tiles split, and (if there is a full round) only the tail split.
+            const int64_t dps[2] = {s == 1 ? tiles : 0, full};
+            for (int v = 0; v < (s > 1 && full > 0 && full < tiles ? 2 : 1); ++v) {
+                const double cost = plan_cost(c, tiles, dps[v], s, K);
+                if (cost < best_cost) {
+                    best_cost = cost;
+                    best = {c, (int)dps[v], s};
+                }
             }
         }
     }
     return best;
 }
 
-size_t split_bytes(int64_t M, int64_t N, int splits) { return (size_t)splits * (size_t)M * (size_t)N * sizeof(float); }
-
-Plan resolve_plan(int64_t M, int64_t N, int64_t K, bool measure_only)
+// The plan a call will really use: the automatic one, or the forced configuration / split factor, and
+// always one whose scratch fits into `avail` bytes (measure_only: as if the workspace were unlimited).
+Plan resolve_plan(int64_t M, int64_t N, int64_t K, size_t avail, bool measure_only)
 {
     const ThreadState &st = g_state;
-    Plan p = choose_plan(M, N, K, true);
-    if (st.force_cfg >= 0) p.cfg = st.force_cfg;
-    if (st.force_split >= 1) p.splits = st.force_split;
-    // a forced pair may be impossible: every slice needs at least one whole K tile
-    const int64_t ktiles = K / desc(p.cfg).BK;
-    if (p.splits > 1 && ktiles < p.splits) p.splits = 1;
-    if (!measure_only && p.splits > 1 && (st.ws == nullptr || st.ws_bytes < split_bytes(M, N, p.splits))) {
-        // no room: best plan that needs no scratch
-        Plan q = choose_plan(M, N, K, false);
-        if (st.force_cfg >= 0) q.cfg = st.force_cfg;
-        q.splits = 1;
-        return q;
-    }
+    Plan p = choose_plan(M, N, K, true, st.force_cfg, st.force_split);
+    const CfgDesc &d = desc(p.cfg);
+    if (!measure_only && plan_bytes(p, ceil_div(M, d.BM) * ceil_div(N, d.BN), M, N) > avail)
+        p = choose_plan(M, N, K, false, st.force_cfg, -1);  // no room: best plan that needs no scratch
     return p;
+}
+
+// Fills the SplitPlan of a launch from a plan and the scratch area [ws, ws + plan_bytes), and resets
+// the counters on the stream.  Returns false if the reset could not be launched.
+bool prepare_split(const Plan &p, int64_t tiles, int64_t M, int64_t N, void *ws, hipStream_t stream, SplitPlan &out)
+{
+    out.dp_tiles = p.dp_tiles;
+    out.splits = p.splits;
+    out.partials = nullptr;
+    out.counters = nullptr;
+    out.plain = 0;
+    out.slice_stride = 0;
+    if (p.splits > 1 && p.dp_tiles == 0) {
+        out.plain = 1;
+        out.partials = static_cast<float *>(ws);
+        out.slice_stride = M * N;
+        return true;
+    }
+    if (p.splits <= 1) {
+        out.dp_tiles = (int)tiles;
+        out.splits = 1;
+        return true;
+    }
+    const CfgDesc &d = desc(p.cfg);
+    const size_t split_tiles = (size_t)(tiles - p.dp_tiles);
+    out.partials = static_cast<float *>(ws);
+    out.counters = reinterpret_cast<unsigned *>(static_cast<char *>(ws) +
+                                                align256(split_tiles * p.splits * (size_t)d.BM * d.BN * sizeof(float)));
+    hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)ceil_div((int64_t)split_tiles, 256)), dim3(256), 0, stream,
+                       out.counters, (int)split_tiles);
+    return hipGetLastError() == hipSuccess;
 }
 
 }  // namespace
@@ -234,8 +310,9 @@ size_t dmath_gemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, i
     (void)transA;
     (void)transB;
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    const Plan p = resolve_plan(M, N, K, true);
-    return p.splits > 1 ? split_bytes(M, N, p.splits) : 0;
+    const Plan p = resolve_plan(M, N, K, 0, true);
+    const CfgDesc &d = desc(p.cfg);
+    return plan_bytes(p, ceil_div(M, d.BM) * ceil_div(N, d.BN), M, N);
 }
 
 dmath_status dmath_gemm_plan(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, int *tile_config,
@@ -246,7 +323,7 @@ dmath_status dmath_gemm_plan(dmath_op transA, dmath_op transB, int64_t M, int64_
     if (M < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
     if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
     if (K < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
-    const Plan p = (M == 0 || N == 0 || K == 0) ? Plan{-1, 1} : resolve_plan(M, N, K, false);
+    const Plan p = (M == 0 || N == 0 || K == 0) ? Plan{-1, 0, 1} : resolve_plan(M, N, K, g_state.ws ? g_state.ws_bytes : 0, false);
     if (tile_config) *tile_config = p.cfg;
     if (split_k) *split_k = p.splits;
     return DMATH_OK;
@@ -286,10 +363,11 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
 
-    const Plan plan = resolve_plan(M, N, K, false);
+    const Plan plan = resolve_plan(M, N, K, g_state.ws ? g_state.ws_bytes : 0, false);
     const CfgDesc &d = desc(plan.cfg);
     const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
     if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
+    if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, lda > ((int64_t)1 << 22) ? 8 : 10);
 
     // 16-byte loads need aligned bases and rows; along the operand's own index also a whole number of quads.
     bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
@@ -299,8 +377,10 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     GemmArgs g;
     g.A = A;
     g.B = B;
+    g.C = C;
     g.lda = lda;
     g.ldb = ldb;
+    g.ldc = ldc;
     g.M = M;
     g.N = N;
     g.K = K;
@@ -309,23 +389,10 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     g.tiles_m = (int)tiles_m;
     g.tiles_n = (int)tiles_n;
     g.clock_probe = g_state.clock_probe;
-    g.splits = plan.splits;
-    g.ktiles_per_split = (int)((K / d.BK) / plan.splits);
-    if (plan.splits > 1) {
-        g.C = static_cast<float *>(g_state.ws);
-        g.ldc = N;
-        g.slice_stride = M * N;
-        g.cvec = (N % 4 == 0) ? 1 : 0;
-    } else {
-        g.C = C;
-        g.ldc = ldc;
-        g.slice_stride = 0;
-        g.ktiles_per_split = (int)(K / d.BK);
-        g.cvec = (aligned16(C) && ldc % 4 == 0) ? 1 : 0;
-    }
+    g.cvec = (aligned16(C) && ldc % 4 == 0) ? 1 : 0;
+    if (!prepare_split(plan, tiles_m * tiles_n, M, N, g_state.ws, stream, g.split)) return fail(DMATH_ERR_LAUNCH, 0);
     if (d.gemm(g, a_k, b_k, vec, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
-
-    if (plan.splits > 1) {
+    if (g.split.plain) {
         const bool v4 = (N % 4 == 0) && aligned16(C) && ldc % 4 == 0;
         const int64_t items = v4 ? M * (N / 4) : M * N;
         const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
@@ -383,10 +450,19 @@ dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W, int64_
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
 
-    int cfg = g_state.force_cfg >= 0 ? g_state.force_cfg : choose_plan(Kout, NPQ, CRS, false).cfg;
-    const CfgDesc &d = desc(cfg);
+    // The filter copy of the tap-major path sits at the start of the workspace; slices come after it.
+    const size_t wt_bytes = align256((size_t)Kout * (size_t)CRS * sizeof(float));
+    const size_t ws_total = g_state.ws ? g_state.ws_bytes : 0;
+    const bool tap_shape = R * S <= 32 && C % 16 == 0 && N * C * H * W * 4 + (pad_h * W + pad_w) * 4 < lim &&
+                           ws_total >= wt_bytes;
+    const size_t split_off = tap_shape ? wt_bytes : 0;
+    Plan plan = resolve_plan(Kout, NPQ, CRS, ws_total - split_off, false);
+    if (plan.splits > 1 && plan.dp_tiles == 0)  // the convolution has no plain split-K path: tail splits only
+        plan = choose_plan(Kout, NPQ, CRS, false, g_state.force_cfg, -1);
+    const CfgDesc &d = desc(plan.cfg);
     const int64_t tiles_m = ceil_div(Kout, d.BM), tiles_n = ceil_div(NPQ, d.BN);
-    if (tiles_m * tiles_n > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 1);
+    if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 1);
+    if (CRS > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, 2);
 
     ConvArgs a;
     a.x = x;
@@ -410,9 +486,7 @@ dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W, int64_
     bool vec = aligned16(w) && CRS % 4 == 0;
     // Tap-major path: needs room for the re-laid-out filters, whole K tiles per tap, a tap mask that
     // fits 32 bits and 31-bit byte offsets into x.
-    const size_t wt_bytes = (size_t)Kout * (size_t)CRS * sizeof(float);
-    const bool tap = C % d.BK == 0 && R * S <= 32 && a.x_bytes + (pad_h * W + pad_w) * 4 < lim &&
-                     g_state.ws != nullptr && g_state.ws_bytes >= wt_bytes;
+    const bool tap = tap_shape && C % d.BK == 0;
     if (tap) {
         float *wt = static_cast<float *>(g_state.ws);
         const int64_t total = Kout * CRS;
@@ -423,6 +497,10 @@ dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W, int64_
         a.w = wt;
         vec = true;  // the workspace is 16-byte aligned and C is a multiple of 4
     }
+    // K slices of the tap-major order must start on a tap's channel block: they do, a slice starts at
+    // a multiple of the K tile and C is a multiple of it.
+    if (!prepare_split(plan, tiles_m * tiles_n, Kout, NPQ, static_cast<char *>(g_state.ws) + split_off, stream, a.split))
+        return fail(DMATH_ERR_LAUNCH, 0);
     if (d.conv(a, vec, tap, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
     return DMATH_OK;
 }

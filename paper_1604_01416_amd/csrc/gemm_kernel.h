@@ -8,15 +8,13 @@ namespace dmath {
 struct GemmArgs {
     const float *A;
     const float *B;
-    float *C;         // destination: C itself, or the split-K workspace (then ldc = N, raw partial sums)
+    float *C;
     int64_t lda, ldb, ldc;
     int64_t M, N, K;
     float alpha, beta;
     int tiles_m, tiles_n;
-    int splits;       // number of K slices; slice z covers K tiles [z*tiles_per_split, ...)
-    int ktiles_per_split;
     int cvec;         // C rows allow aligned NB-wide vector access
-    int64_t slice_stride;  // floats between consecutive workspace slices (M*N), 0 when splits == 1
+    SplitPlan split;
     unsigned long long *clock_probe;  // optional: 4 stamps from each of workgroups 0..7 (see dmath_set_clock_probe)
 };
 
@@ -50,20 +48,15 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
         g.clock_probe[blockIdx.x * 4 + 1] = __builtin_amdgcn_s_memrealtime();  // fixed 100 MHz counter
     }
     const int tiles = g.tiles_m * g.tiles_n;
-    const int pid = xcd_contiguous_id(blockIdx.x, tiles * g.splits);
-    const int z = pid / tiles;
+    const WorkItem w = work_item(blockIdx.x, tiles, g.split);
     int tm, tn;
-    tile_coords<8>(pid - z * tiles, g.tiles_m, g.tiles_n, tm, tn);
+    tile_coords<8>(w.tile, g.tiles_m, g.tiles_n, tm, tn);
     const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
 
-    // K range of this slice: whole K tiles, the last slice also takes the partial one.
+    // K range of this workgroup: the whole K, or one slice of it
     const int ktiles_total = (int)(g.K / Cfg::BK);
-    const int kt0 = z * g.ktiles_per_split;
-    int T = ktiles_total - kt0;
-    T = T < g.ktiles_per_split ? T : g.ktiles_per_split;
-    if (z == g.splits - 1) T = ktiles_total - kt0;
-    T = T < 0 ? 0 : T;
-    const int krem = (z == g.splits - 1) ? (int)(g.K - (int64_t)ktiles_total * Cfg::BK) : 0;
+    int kt0, T, krem;
+    slice_range(ktiles_total, (int)(g.K - (int64_t)ktiles_total * Cfg::BK), w.slice, w.nslice, kt0, T, krem);
     const int64_t k0 = (int64_t)kt0 * Cfg::BK;
 
     typename RowLoaderSel<Cfg, A_KCONTIG, VEC>::type rl;
@@ -80,6 +73,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
             for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
 
     mainloop<Cfg>(rl, cl, T, krem, acc, smem);
+    if (!combine_slices<Cfg>(acc, g.split, w)) return;
 
     // Epilogue.  Lane (i, h) owns, for block row bm and accumulator register r, the NB consecutive
     // columns n0 + wn0 + NB*i .. of row m0 + wm0 + MB*(8*(r/4) + 4*h + r%4) + bm.
@@ -88,18 +82,18 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
     const int i = lane & 31, h = lane >> 5;
     const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
     const int64_t col = n0 + wn0 + Cfg::NB * i;
-    const bool partial = g.splits > 1;
-    float *Cz = g.C + (int64_t)z * g.slice_stride;
-    const float alpha = partial ? 1.0f : g.alpha;
-    const float beta = partial ? 0.0f : g.beta;
-    const bool full_vec = g.cvec && (col + Cfg::NB <= g.N);
+    const bool raw_slice = g.split.plain && w.nslice > 1;  // plain split-K: raw sums to the workspace
+    float *Cz = raw_slice ? g.split.partials + (int64_t)w.slice * g.split.slice_stride : g.C;
+    const int64_t ldc = raw_slice ? g.N : g.ldc;
+    const float alpha = raw_slice ? 1.0f : g.alpha, beta = raw_slice ? 0.0f : g.beta;
+    const bool full_vec = (raw_slice ? (g.N % 4 == 0) : (g.cvec != 0)) && (col + Cfg::NB <= g.N);
 #pragma unroll
     for (int bm = 0; bm < Cfg::MB; ++bm) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
             if (row >= g.M) continue;
-            float *dst = Cz + row * g.ldc + col;
+            float *dst = Cz + row * ldc + col;
             float out[Cfg::NB];
 #pragma unroll
             for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] = alpha * acc[bm][bn][r];
@@ -142,7 +136,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
 template <class Cfg>
 int launch_gemm_cfg(const GemmArgs &g, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t stream)
 {
-    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n * g.splits)), block(Cfg::NT);
+    const int tiles = g.tiles_m * g.tiles_n;
+    const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
 #define DMATH_LAUNCH(AK, BK_, V) \
     hipLaunchKernelGGL((gemm_tile_kernel<Cfg, AK, BK_, V>), grid, block, 0, stream, g)
     if (vec) {

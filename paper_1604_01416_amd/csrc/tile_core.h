@@ -556,6 +556,119 @@ __device__ __forceinline__ void mainloop(RowLoader &rl, ColLoader &cl, int T, in
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Split tiles.  When the tile grid does not fill the device evenly, the tiles past the last full
+// round (or all tiles of a skinny product) are cut into `splits` slices along K, one workgroup each.
+// A slice leaves its raw accumulators in the workspace and bumps the tile's counter; whichever slice
+// arrives last adds the others to its own registers and runs the epilogue.  Nobody waits (a counter
+// is only ever incremented and read by its incrementer), and the slices are always added in slice
+// order, block by block, so the result does not depend on which slice finishes last: same bits every
+// run, as the paper's remarks on reproducibility ask of a library wherever it is affordable.
+struct SplitPlan {
+    int dp_tiles;        // tiles [0, dp_tiles) are computed whole by one workgroup each
+    int splits;          // every later tile is cut into this many K slices (1: no tile is split)
+    float *partials;     // [(tile - dp_tiles) * splits + slice][MB*NB blocks][4][NT][4] floats
+    unsigned *counters;  // one per split tile, zero at launch
+    // Plain split-K (every tile split, combined by a second kernel): slice z of the whole product is
+    // written as a dense M x N array at partials + z * slice_stride; no counters.
+    int plain;
+    int64_t slice_stride;
+};
+
+// Which tile (index in raster order) and which K slice a workgroup owns.
+struct WorkItem {
+    int tile;    // raster index of the tile
+    int slice;   // K slice, 0 when the tile is not split
+    int nslice;  // number of slices of this tile (1 or splits)
+    int sq;      // index among the split tiles (for partials / counters)
+};
+
+__device__ __forceinline__ int xcd_contiguous_id(int bid, int total);
+
+__device__ __forceinline__ WorkItem work_item(int bid, int tiles, const SplitPlan &sp)
+{
+    WorkItem w;
+    if (bid < sp.dp_tiles) {
+        w.tile = xcd_contiguous_id(bid, sp.dp_tiles);
+        w.slice = 0;
+        w.nslice = 1;
+        w.sq = 0;
+    } else {
+        const int q = bid - sp.dp_tiles;
+        w.sq = q / sp.splits;
+        w.slice = q - w.sq * sp.splits;
+        w.nslice = sp.splits;
+        w.tile = sp.dp_tiles + w.sq;
+    }
+    (void)tiles;
+    return w;
+}
+
+// K tiles [first, first + count) and the partial tile (krem columns) of slice `slice` of `nslice`.
+__device__ __forceinline__ void slice_range(int ktiles_total, int krem_total, int slice, int nslice, int &first,
+                                            int &count, int &krem)
+{
+    const int per = ktiles_total / nslice;
+    first = slice * per;
+    const bool last = slice == nslice - 1;
+    count = last ? ktiles_total - first : per;
+    krem = last ? krem_total : 0;
+}
+
+// Returns true when this workgroup has to run the epilogue (its tile is whole, or it is the last
+// slice of its tile to arrive, in which case acc holds the sum over all slices on return).
+template <class Cfg>
+__device__ __forceinline__ bool combine_slices(floatx16 (&acc)[Cfg::MB][Cfg::NB], const SplitPlan &sp, const WorkItem &w)
+{
+    if (w.nslice == 1 || sp.plain) return true;
+    constexpr int NBLK = Cfg::MB * Cfg::NB;
+    const size_t slot_floats = (size_t)NBLK * 16 * Cfg::NT;
+    float *mine = sp.partials + ((size_t)w.sq * w.nslice + w.slice) * slot_floats;
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < Cfg::NB; ++bn)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                floatx4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = acc[bm][bn][4 * r4 + e];
+                *reinterpret_cast<floatx4 *>(mine + ((size_t)((bm * Cfg::NB + bn) * 4 + r4) * Cfg::NT + threadIdx.x) * 4) = o;
+            }
+    __shared__ unsigned arrived;
+    __threadfence();   // the slice is visible device-wide before the counter moves
+    __syncthreads();
+    if (threadIdx.x == 0) arrived = atomicAdd(sp.counters + w.sq, 1u);
+    __syncthreads();
+    if (arrived != (unsigned)(w.nslice - 1)) return false;
+    __threadfence();   // the other slices' data is read after their counter increments
+    const float *base = sp.partials + (size_t)w.sq * w.nslice * slot_floats;
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < Cfg::NB; ++bn) {
+            floatx16 tot;
+            for (int z = 0; z < w.nslice; ++z) {
+                floatx16 part;
+                if (z == w.slice) {
+                    part = acc[bm][bn];
+                } else {
+                    const float *src = base + (size_t)z * slot_floats;
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const floatx4 q = *reinterpret_cast<const floatx4 *>(
+                            src + ((size_t)((bm * Cfg::NB + bn) * 4 + r4) * Cfg::NT + threadIdx.x) * 4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) part[4 * r4 + e] = q[e];
+                    }
+                }
+                if (z == 0) tot = part; else tot += part;
+            }
+            acc[bm][bn] = tot;
+        }
+    return true;
+}
+
 // Workgroup id -> tile id.  Workgroups are handed to the 8 dies in turn, each die has its own L2:
 // give every die one contiguous run of tile ids, and order tile ids so that a run covers a compact
 // block of the tile grid (GROUP tile rows at a time, walking down the rows first), so that the

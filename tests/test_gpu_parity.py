@@ -107,6 +107,31 @@ def test_gemm_split_k(dm, torch, cfg, split, tA, tB):
     run_gemm_case(dm, torch, tA, tB, 64, 128, 512, alpha=1.0, beta=1.0, seed=split + 2, ints=True, exact=True)
 
 
+@pytest.mark.parametrize("tA,tB", [(0, 0), (1, 1)])
+def test_gemm_tail_tiles_split(dm, torch, tA, tB):
+    """17 x 16 tiles of 128 x 128 on 256 compute units: one full round plus 16 tiles, which the planner
+    cuts into K slices combined in-kernel; also the same with ragged edges."""
+    st, cfg, split = dm.dmath_gemm_plan(tA, tB, 2176, 2048, 768)
+    assert st == dm.OK
+    run_gemm_case(dm, torch, tA, tB, 2176, 2048, 768, alpha=1.0, beta=0.0, seed=41, c_nan=True)
+    run_gemm_case(dm, torch, tA, tB, 2170, 2044, 771, alpha=0.5, beta=1.0, ld_extra=(2, 4, 4), seed=42)
+    dm.dmath_set_override(3, -1)       # fixed 128 x 128 tiles, automatic split: the tail-split plan
+    st, cfg, split = dm.dmath_gemm_plan(tA, tB, 2176, 2048, 768)
+    assert cfg == 3 and split > 1, (cfg, split)
+    run_gemm_case(dm, torch, tA, tB, 2176, 2048, 768, alpha=1.0, beta=1.0, seed=43, ints=True, exact=True)
+    outs = []
+    for _ in range(2):                 # which slice arrives last may differ between runs; the bits may not
+        rng = np.random.default_rng(44)
+        A = rng.uniform(-1, 1, (2176, 768)).astype(np.float32)
+        B = rng.uniform(-1, 1, (768, 2048)).astype(np.float32)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        dC = torch.empty((2176, 2048), device="cuda")
+        dm.check(dm.dmath_gemm(0, 0, 2176, 2048, 768, 1.0, dA, 768, dB, 2048, 0.0, dC, 2048))
+        torch.cuda.synchronize()
+        outs.append(dC.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])
+
+
 def test_gemm_quick_returns_and_nan_conventions(dm, torch):
     rng = np.random.default_rng(5)
     M, N, K = 70, 50, 40
