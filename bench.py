@@ -31,8 +31,13 @@ PEAK_HBM_GBS = 8000.0
 # what the same counter reads for a device copy of known size); figures and commands are in
 # profiles/*.md.  Keyed by workload; None where no counter run is committed.
 MEASURED_HBM_TRAFFIC_BYTES = {
-    # profiles/gemm_nn_4096_tile_kernel.md: FETCH_SIZE 196744 KiB x 2.0 (copy factor) + WRITE_SIZE 65536 KiB x 1.0
-    "gemm4096": int((196743.6 * 2.0 + 65536.0) * 1024),
+    # per step: sum over the kernels of a step of FETCH_SIZE KiB x 2.0 (copy factor) + WRITE_SIZE KiB x 1.0
+    "gemm4096": int((196777.7 * 2.0 + 65536.5) * 1024),                         # profiles/gemm_nn_4096_tile_kernel.md
+    "gemm256": int((840.6 * 2.0 + 256.2) * 1024),                               # profiles/gemm_nn_256_tile_kernel.md
+    "summa": int(16 * (247992.5 * 2.0 + 262144.5) * 1024),                      # profiles/summa_update_8192x8192x512_tile_kernel.md
+    "fc": int(((67704.2 + 70375.3 + 12475.0 + 2 * 8210.6) * 2.0
+               + 2 * 16384.5 + 65536.5 + 2 * 4096.0) * 1024),                   # profiles/fc_4096_batch256_kernels.md
+    "conv": int(((94305.9 + 1812.2) * 2.0 + 119682.4 + 2304.0) * 1024),         # profiles/conv3x3_n128_c256_k256_28x28_kernels.md
 }
 
 WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv")

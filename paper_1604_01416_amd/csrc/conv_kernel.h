@@ -8,10 +8,12 @@
 // never stored: the loaders below generate each of its elements from x with the zero halo applied.
 // column = (n*P + p)*Q + q.  Two orders of k are implemented (any order gives the same sums):
 //   - generic (LoaderConvX): k = (c*R + r)*S + s, the order of w in memory; works for every shape.
-//   - tap-major (LoaderConvTap): k = (r*S + s)*C + c with C a multiple of the K tile, so a K tile is
-//     BK channels of ONE filter tap: the halo test and the tap offset are per tile instead of per
-//     element, and a K row is a plain scalar offset c*H*W away from the previous one.  The filters
-//     are first re-laid out as w'[j][r][s][c] into the workspace by a small kernel.
+//   - tap-major (LoaderConvTap): k = ((cb*R + r)*S + s)*BK + cc for channel c = cb*BK + cc, with C a
+//     multiple of the K tile BK, so a K tile is BK channels of ONE filter tap: the halo test and the
+//     tap offset are per tile instead of per element, and a K row is a plain scalar offset H*W away
+//     from the previous one.  The R*S taps of a channel block are consecutive K tiles, so the pixels
+//     of those channels are re-read while still in cache.  The filters are first re-laid out as
+//     w'[j][cb][r][s][cc] into the workspace by a small kernel.
 #pragma once
 #include "tile_core.h"
 
@@ -120,16 +122,17 @@ struct LoaderConvTap {
     uint32_t tile_voff, tile_soff;
     int col, kg;
     int c0, r, s;       // first channel and tap of the next tile to load
-    int C, HW, W, S;
+    int HW, W, R, S;
     float v[NQ];
 
     __device__ __forceinline__ void init(const ConvArgs &a, int64_t col0, int kstart, int tid)
     {
         col = tid % BN;
         kg = __builtin_amdgcn_readfirstlane(tid / BN);
-        C = a.C; HW = a.H * a.W; W = a.W; S = a.S;
-        const int tap0 = kstart / a.C;  // kstart is a multiple of the K tile, which divides C
-        c0 = kstart - tap0 * a.C;
+        HW = a.H * a.W; W = a.W; R = a.R; S = a.S;
+        const int t0 = kstart / BK;     // kstart is a multiple of the K tile
+        const int cb = t0 / a.RS, tap0 = t0 - cb * a.RS;
+        c0 = cb * BK;
         r = tap0 / a.S;
         s = tap0 - r * a.S;
         const int shift = a.pad_h * a.W + a.pad_w;
@@ -163,12 +166,11 @@ struct LoaderConvTap {
     }
     __device__ __forceinline__ void advance()
     {
-        c0 += BK;
-        if (c0 >= C) {
-            c0 = 0;
-            if (++s == S) {
-                s = 0;
-                ++r;
+        if (++s == S) {
+            s = 0;
+            if (++r == R) {
+                r = 0;
+                c0 += BK;
             }
         }
     }

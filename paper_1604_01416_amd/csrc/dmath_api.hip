@@ -96,15 +96,16 @@ __global__ void zero_u32_kernel(unsigned *p, int n)
     if (i < n) p[i] = 0u;
 }
 
-// w'[j][rs][c] = w[j][c][rs]: the filter matrix in tap-major k order.
-__global__ void conv_filter_tap_major_kernel(const float *w, float *wt, int64_t Kout, int C, int RS)
+// w'[j][cb][rs][cc] = w[j][cb*BK + cc][rs]: the filter matrix in the tap-major k order of LoaderConvTap.
+__global__ void conv_filter_tap_major_kernel(const float *w, float *wt, int64_t Kout, int C, int RS, int BK)
 {
-    const int64_t total = Kout * C * RS;
+    const int64_t CRS = (int64_t)C * RS, total = Kout * CRS;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t j = e / ((int64_t)C * RS);
-        const int rem = (int)(e - j * C * RS);
-        const int rs = rem / C, c = rem - rs * C;
-        wt[e] = w[(j * C + c) * RS + rs];
+        const int64_t j = e / CRS;
+        const int rem = (int)(e - j * CRS);
+        const int t = rem / BK, cc = rem - t * BK;
+        const int cb = t / RS, rs = t - cb * RS;
+        wt[e] = w[(j * C + cb * BK + cc) * RS + rs];
     }
 }
 
@@ -492,7 +493,7 @@ dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W, int64_
         const int64_t total = Kout * CRS;
         const int blocks = (int)(ceil_div(total, 256) < 2048 ? ceil_div(total, 256) : 2048);
         hipLaunchKernelGGL(conv_filter_tap_major_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, Kout, (int)C,
-                           (int)(R * S));
+                           (int)(R * S), d.BK);
         if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
         a.w = wt;
         vec = true;  // the workspace is 16-byte aligned and C is a multiple of 4
