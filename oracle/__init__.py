@@ -42,6 +42,10 @@ def _load():
         lib.oracle_conv2d_fwd_points.restype = ctypes.c_int
         lib.oracle_conv2d_fwd_points.argtypes = [_i64] * 11 + [_dbl, _fp, _fp, _dbl, _fp, _i64, _ip,
                                                                _dp, _dp]
+        lib.oracle_conv2d_bwd_data.restype = ctypes.c_int
+        lib.oracle_conv2d_bwd_data.argtypes = [_i64] * 11 + [_dbl, _fp, _fp, _dbl, _fp, _i64, _ip, _dp, _dp]
+        lib.oracle_conv2d_bwd_filter.restype = ctypes.c_int
+        lib.oracle_conv2d_bwd_filter.argtypes = [_i64] * 11 + [_dbl, _fp, _fp, _dbl, _fp, _i64, _ip, _dp, _dp]
         _lib = lib
     return _lib
 
@@ -172,6 +176,62 @@ def conv2d_fwd_points(x, w, idx, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=0.0,
                                           ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
     if rc != 0:
         raise RuntimeError("oracle_conv2d_fwd_points rejected its arguments")
+    return ref, mag
+
+
+def conv2d_bwd_data(dy, w, x_shape, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=0.0, dx0=None, idx=None):
+    """ref, mag of the gradient of the forward convolution with respect to x (shape x_shape = N, C, H, W),
+    given dy[N,Kout,P,Q] and w[Kout,C,R,S]; all elements, or the flat offsets idx only."""
+    N, C, H, W = x_shape
+    Kout, C2, R, S = w.shape
+    assert C == C2
+    P, Q = conv_out_shape(H, W, R, S, pad[0], pad[1], stride[0], stride[1])
+    assert dy.shape == (N, Kout, P, Q)
+    dy = _f32(dy, "dy")
+    w = _f32(w, "w")
+    dx0 = _f32(dx0, "dx0")
+    if beta != 0.0:
+        _need(dx0, N * C * H * W, "dx0")
+    if idx is None:
+        shape, n, ip = (N, C, H, W), 0, ctypes.cast(None, _ip)
+    else:
+        idx = np.ascontiguousarray(idx, dtype=np.int64)
+        shape, n, ip = idx.shape, idx.size, idx.ctypes.data_as(_ip)
+    ref = np.empty(shape, dtype=np.float64)
+    mag = np.empty(shape, dtype=np.float64)
+    rc = _load().oracle_conv2d_bwd_data(N, C, H, W, Kout, R, S, pad[0], pad[1], stride[0], stride[1], float(alpha),
+                                        _ptr(dy), _ptr(w), float(beta), _ptr(dx0), n, ip,
+                                        ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
+    if rc != 0:
+        raise RuntimeError("oracle_conv2d_bwd_data rejected its arguments")
+    return ref, mag
+
+
+def conv2d_bwd_filter(x, dy, w_shape, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=0.0, dw0=None, idx=None):
+    """ref, mag of the gradient of the forward convolution with respect to w (shape w_shape = Kout, C, R, S),
+    given x[N,C,H,W] and dy[N,Kout,P,Q]; all elements, or the flat offsets idx only."""
+    N, C, H, W = x.shape
+    Kout, C2, R, S = w_shape
+    assert C == C2
+    P, Q = conv_out_shape(H, W, R, S, pad[0], pad[1], stride[0], stride[1])
+    assert dy.shape == (N, Kout, P, Q)
+    x = _f32(x, "x")
+    dy = _f32(dy, "dy")
+    dw0 = _f32(dw0, "dw0")
+    if beta != 0.0:
+        _need(dw0, Kout * C * R * S, "dw0")
+    if idx is None:
+        shape, n, ip = (Kout, C, R, S), 0, ctypes.cast(None, _ip)
+    else:
+        idx = np.ascontiguousarray(idx, dtype=np.int64)
+        shape, n, ip = idx.shape, idx.size, idx.ctypes.data_as(_ip)
+    ref = np.empty(shape, dtype=np.float64)
+    mag = np.empty(shape, dtype=np.float64)
+    rc = _load().oracle_conv2d_bwd_filter(N, C, H, W, Kout, R, S, pad[0], pad[1], stride[0], stride[1], float(alpha),
+                                          _ptr(x), _ptr(dy), float(beta), _ptr(dw0), n, ip,
+                                          ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
+    if rc != 0:
+        raise RuntimeError("oracle_conv2d_bwd_filter rejected its arguments")
     return ref, mag
 
 

@@ -273,3 +273,137 @@ int oracle_conv2d_fwd_points(int64_t N, int64_t C, int64_t H, int64_t W,
     }
     return 0;
 }
+
+/*
+ * Backward passes of the same convolution (the paper's DNN pipeline is forward and backward; it names
+ * separate data- and filter-gradient work in its discussion of streams).  Both are the adjoints of the
+ * forward definition above with respect to x and to w, written out directly:
+ *
+ *   dx[n][c][h][w]  = alpha * sum_{j,r,s : p*sh + r - ph == h, q*sw + s - pw == w, 0 <= p < P, 0 <= q < Q}
+ *                             dy[n][j][p][q] * w[j][c][r][s]                      + beta * dx0[n][c][h][w]
+ *   dw[j][c][r][s]  = alpha * sum_{n,p,q : 0 <= p*sh + r - ph < H, 0 <= q*sw + s - pw < W}
+ *                             dy[n][j][p][q] * x[n][c][p*sh + r - ph][q*sw + s - pw] + beta * dw0[j][c][r][s]
+ *
+ * FP64 sums in the loop order written (j, r, s for dx; n, p, q for dw), magnitude sums alongside.
+ */
+static inline void bwd_data_point(int64_t Kout, int64_t C, int64_t P, int64_t Q, int64_t R, int64_t S,
+                                  int64_t ph, int64_t pw, int64_t sh, int64_t sw,
+                                  const float *dy_img, const float *w, int64_t c, int64_t h, int64_t wcol,
+                                  double *sum, double *msum)
+{
+    double s_acc = 0.0, t_acc = 0.0;
+    for (int64_t j = 0; j < Kout; ++j)
+        for (int64_t r = 0; r < R; ++r)
+            for (int64_t s = 0; s < S; ++s) {
+                const int64_t th = h + ph - r, tw = wcol + pw - s;
+                if (th < 0 || tw < 0 || th % sh != 0 || tw % sw != 0) continue;
+                const int64_t p = th / sh, q = tw / sw;
+                if (p >= P || q >= Q) continue;
+                const double g = (double)dy_img[(j * P + p) * Q + q];
+                const double wv = (double)w[((j * C + c) * R + r) * S + s];
+                s_acc += g * wv;
+                t_acc += fabs(g) * fabs(wv);
+            }
+    *sum = s_acc;
+    *msum = t_acc;
+}
+
+/* idx == NULL: every element of dx (npts ignored, ref / mag are N*C*H*W); else the flat offsets idx[0..npts). */
+int oracle_conv2d_bwd_data(int64_t N, int64_t C, int64_t H, int64_t W,
+                           int64_t Kout, int64_t R, int64_t S,
+                           int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w,
+                           double alpha, const float *dy, const float *w,
+                           double beta, const float *dx0,
+                           int64_t npts, const int64_t *idx, double *ref, double *mag)
+{
+    if (N < 0 || C < 0 || H < 0 || W < 0 || Kout < 0 || R < 1 || S < 1) return 1;
+    if (pad_h < 0 || pad_w < 0 || stride_h < 1 || stride_w < 1 || !ref) return 1;
+    const int64_t P = conv_out_dim(H, pad_h, R, stride_h);
+    const int64_t Q = conv_out_dim(W, pad_w, S, stride_w);
+    const int64_t total = N * C * H * W;
+    const int64_t count = idx ? npts : total;
+    if (idx)
+        for (int64_t t = 0; t < npts; ++t)
+            if (idx[t] < 0 || idx[t] >= total) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < count; ++t) {
+        int64_t o = idx ? idx[t] : t;
+        const int64_t flat = o;
+        const int64_t wc = o % W;
+        o /= W;
+        const int64_t h = o % H;
+        o /= H;
+        const int64_t c = o % C;
+        const int64_t n = o / C;
+        double s = 0.0, m = 0.0;
+        if (alpha != 0.0)
+            bwd_data_point(Kout, C, P, Q, R, S, pad_h, pad_w, stride_h, stride_w, dy + n * Kout * P * Q, w, c, h, wc,
+                           &s, &m);
+        double r = (alpha != 0.0) ? alpha * s : 0.0;
+        double mm = (alpha != 0.0) ? fabs(alpha) * m : 0.0;
+        if (beta != 0.0) {
+            const double c0 = (double)dx0[flat];
+            r += beta * c0;
+            mm += fabs(beta) * fabs(c0);
+        }
+        ref[t] = r;
+        if (mag) mag[t] = mm;
+    }
+    return 0;
+}
+
+/* idx == NULL: every element of dw (ref / mag are Kout*C*R*S); else the flat offsets idx[0..npts). */
+int oracle_conv2d_bwd_filter(int64_t N, int64_t C, int64_t H, int64_t W,
+                             int64_t Kout, int64_t R, int64_t S,
+                             int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w,
+                             double alpha, const float *x, const float *dy,
+                             double beta, const float *dw0,
+                             int64_t npts, const int64_t *idx, double *ref, double *mag)
+{
+    if (N < 0 || C < 0 || H < 0 || W < 0 || Kout < 0 || R < 1 || S < 1) return 1;
+    if (pad_h < 0 || pad_w < 0 || stride_h < 1 || stride_w < 1 || !ref) return 1;
+    const int64_t P = conv_out_dim(H, pad_h, R, stride_h);
+    const int64_t Q = conv_out_dim(W, pad_w, S, stride_w);
+    const int64_t total = Kout * C * R * S;
+    const int64_t count = idx ? npts : total;
+    if (idx)
+        for (int64_t t = 0; t < npts; ++t)
+            if (idx[t] < 0 || idx[t] >= total) return 1;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t t = 0; t < count; ++t) {
+        int64_t o = idx ? idx[t] : t;
+        const int64_t flat = o;
+        const int64_t s = o % S;
+        o /= S;
+        const int64_t r = o % R;
+        o /= R;
+        const int64_t c = o % C;
+        const int64_t j = o / C;
+        double s_acc = 0.0, t_acc = 0.0;
+        if (alpha != 0.0) {
+            for (int64_t n = 0; n < N; ++n)
+                for (int64_t p = 0; p < P; ++p) {
+                    const int64_t ih = p * stride_h + r - pad_h;
+                    if (ih < 0 || ih >= H) continue;
+                    for (int64_t q = 0; q < Q; ++q) {
+                        const int64_t iw = q * stride_w + s - pad_w;
+                        if (iw < 0 || iw >= W) continue;
+                        const double g = (double)dy[((n * Kout + j) * P + p) * Q + q];
+                        const double xv = (double)x[((n * C + c) * H + ih) * W + iw];
+                        s_acc += g * xv;
+                        t_acc += fabs(g) * fabs(xv);
+                    }
+                }
+        }
+        double rr = (alpha != 0.0) ? alpha * s_acc : 0.0;
+        double mm = (alpha != 0.0) ? fabs(alpha) * t_acc : 0.0;
+        if (beta != 0.0) {
+            const double c0 = (double)dw0[flat];
+            rr += beta * c0;
+            mm += fabs(beta) * fabs(c0);
+        }
+        ref[t] = rr;
+        if (mag) mag[t] = mm;
+    }
+    return 0;
+}

@@ -6,17 +6,18 @@
 // times cols-operand (K x BN).  Both operands are staged in LDS in the same
 // image, whatever their orientation in memory:
 //
-//     As[stage][k][LDA]   element (k, rot(r, k)) = rows-operand(r, k),  r in [0, BM)
-//     Bs[stage][k][LDB]   element (k, rot(c, k)) = cols-operand(k, c),  c in [0, BN)
-//     rot(x, k) = (x + ROT * (k / 4)) mod extent        (ROT = 8 floats, LDA = BM, LDB = BN)
+//     As[stage][k][LDA]   element (k, col(r, k)) = rows-operand(r, k),  r in [0, BM)
+//     Bs[stage][k][LDB]   element (k, col(c, k)) = cols-operand(k, c),  c in [0, BN)
 //
 // so the MFMA loop and the epilogue are the same for every transpose form
 // (the local multiply of section "Matrix Multiplication" of the dMath paper and
 // its transposed variants) and for the convolution, which only brings its own
-// loader for the operand generated from x.  The rotation of each group of four
-// k rows by 8 floats is what lets an operand that is contiguous along k in
-// memory be stored transposed without LDS bank conflicts (see LoaderK); it
-// costs nothing on the read side, where it is a per-lane constant.
+// loader for the operand generated from x.  Two images exist (TileCfg::LKV):
+// padded, col(x, k) = x with LDA = BM + 4, and rotated, col(x, k) =
+// (x + 8 * (k / 4)) mod extent with LDA = BM, which is free of LDS bank
+// conflicts also for the transposing stores of operands contiguous along k.
+// The padded image is the faster one on MI355X and is what the product
+// configurations use; see LoaderK / LoaderK0.
 //
 // MFMA used: v_mfma_f32_32x32x2_f32.  For lane l (i = l % 32, h = l / 32):
 //   A operand register holds A[i][k = h], B operand holds B[k = h][j = i],

@@ -366,3 +366,145 @@ def test_bound_formula():
     mag = np.array([0.0, 1.0, 2.5])
     got = oracle.bound(4096, mag)
     assert np.array_equal(got, 4.0 * 4096 * 2.0 ** -24 * mag + 1e-6)
+
+
+# ----------------------------------------------------------------------------- convolution, backward passes
+
+BWD_SHAPES = [
+    dict(N=2, C=3, H=7, W=5, Kout=4, R=3, S=3, pad=(1, 1), stride=(1, 1)),
+    dict(N=1, C=2, H=9, W=6, Kout=3, R=3, S=2, pad=(0, 0), stride=(2, 2)),
+    dict(N=2, C=1, H=8, W=11, Kout=2, R=5, S=3, pad=(2, 1), stride=(2, 3)),
+    dict(N=1, C=4, H=4, W=4, Kout=5, R=1, S=1, pad=(0, 0), stride=(1, 1)),
+    dict(N=2, C=2, H=6, W=6, Kout=2, R=3, S=3, pad=(0, 2), stride=(1, 2)),
+]
+
+
+def _bwd_inputs(shape, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((shape["N"], shape["C"], shape["H"], shape["W"])).astype(np.float32)
+    w = rng.standard_normal((shape["Kout"], shape["C"], shape["R"], shape["S"])).astype(np.float32)
+    P, Q = oracle.conv_out_shape(shape["H"], shape["W"], shape["R"], shape["S"], *shape["pad"], *shape["stride"])
+    dy = rng.standard_normal((shape["N"], shape["Kout"], P, Q)).astype(np.float32)
+    return x, w, dy
+
+
+def test_conv_backward_hand_worked_fixture():
+    fx = _read_fixture("conv_hand_worked.txt")
+    x = np.array(fx["x"], dtype=np.float32).reshape(1, 1, 3, 3)
+    w = np.array(fx["w"], dtype=np.float32).reshape(1, 1, 2, 2)
+    dy = np.array(fx["dy"], dtype=np.float32).reshape(1, 1, 2, 2)
+    dx, mag = oracle.conv2d_bwd_data(dy, w, x.shape)
+    assert np.array_equal(dx.reshape(-1), np.array(fx["dx_pad0_stride1"]))
+    assert np.array_equal(mag, dx)
+    dw, mag = oracle.conv2d_bwd_filter(x, dy, w.shape)
+    assert np.array_equal(dw.reshape(-1), np.array(fx["dw_pad0_stride1"]))
+    assert np.array_equal(mag, dw)
+
+
+@pytest.mark.parametrize("shape", BWD_SHAPES)
+def test_conv_backward_is_the_adjoint_of_forward(shape):
+    """<dy, conv(x, w)> == <bwd_data(dy, w), x> == <bwd_filter(x, dy), w>: fixes both backward oracles
+    against the (independently pinned) forward one."""
+    x, w, dy = _bwd_inputs(shape, 51)
+    y, _ = oracle.conv2d_fwd(x, w, pad=shape["pad"], stride=shape["stride"])
+    lhs = float(np.sum(dy.astype(np.float64) * y))
+    dx, _ = oracle.conv2d_bwd_data(dy, w, x.shape, pad=shape["pad"], stride=shape["stride"])
+    dw, _ = oracle.conv2d_bwd_filter(x, dy, w.shape, pad=shape["pad"], stride=shape["stride"])
+    scale = float(np.sum(np.abs(dy.astype(np.float64)) * np.abs(y))) + 1e-30
+    assert abs(float(np.sum(dx * x.astype(np.float64))) - lhs) <= 1e-12 * scale
+    assert abs(float(np.sum(dw * w.astype(np.float64))) - lhs) <= 1e-12 * scale
+
+
+@pytest.mark.parametrize("shape", BWD_SHAPES)
+def test_conv_backward_matches_brute_force_and_torch(shape):
+    import torch
+    x, w, dy = _bwd_inputs(shape, 53)
+    N, C, H, W = x.shape
+    Kout, _, R, S = w.shape
+    _, _, P, Q = dy.shape
+    ph, pw = shape["pad"]
+    sh, sw = shape["stride"]
+    # second statement of the definitions: scatter form, python loops, float64
+    dx_b = np.zeros((N, C, H, W))
+    dw_b = np.zeros((Kout, C, R, S))
+    dxm_b = np.zeros_like(dx_b)
+    dwm_b = np.zeros_like(dw_b)
+    for n in range(N):
+        for j in range(Kout):
+            for p in range(P):
+                for q in range(Q):
+                    g = float(dy[n, j, p, q])
+                    for c in range(C):
+                        for r in range(R):
+                            for s in range(S):
+                                ih, iw = p * sh + r - ph, q * sw + s - pw
+                                if 0 <= ih < H and 0 <= iw < W:
+                                    dx_b[n, c, ih, iw] += g * float(w[j, c, r, s])
+                                    dxm_b[n, c, ih, iw] += abs(g) * abs(float(w[j, c, r, s]))
+                                    dw_b[j, c, r, s] += g * float(x[n, c, ih, iw])
+                                    dwm_b[j, c, r, s] += abs(g) * abs(float(x[n, c, ih, iw]))
+    dx, dxm = oracle.conv2d_bwd_data(dy, w, x.shape, pad=shape["pad"], stride=shape["stride"])
+    dw, dwm = oracle.conv2d_bwd_filter(x, dy, w.shape, pad=shape["pad"], stride=shape["stride"])
+    for got, want in ((dx, dx_b), (dxm, dxm_b), (dw, dw_b), (dwm, dwm_b)):
+        assert np.max(np.abs(got - want)) <= 1e-12 * max(1.0, np.max(np.abs(want)))
+    # library routines in float64
+    tx, tw, tdy = (torch.from_numpy(a).double() for a in (x, w, dy))
+    lib_dx = torch.nn.grad.conv2d_input(x.shape, tw, tdy, stride=shape["stride"], padding=shape["pad"]).numpy()
+    lib_dw = torch.nn.grad.conv2d_weight(tx, w.shape, tdy, stride=shape["stride"], padding=shape["pad"]).numpy()
+    assert np.max(np.abs(dx - lib_dx)) <= 1e-12 * max(1.0, np.max(np.abs(lib_dx)))
+    assert np.max(np.abs(dw - lib_dw)) <= 1e-12 * max(1.0, np.max(np.abs(lib_dw)))
+    # alpha / beta and the sampled form
+    rng = np.random.default_rng(3)
+    dx0 = rng.standard_normal(x.shape).astype(np.float32)
+    dw0 = rng.standard_normal(w.shape).astype(np.float32)
+    dx2, dxm2 = oracle.conv2d_bwd_data(dy, w, x.shape, pad=shape["pad"], stride=shape["stride"], alpha=2.0, beta=-0.5,
+                                       dx0=dx0)
+    assert np.array_equal(dx2, 2.0 * dx - 0.5 * dx0.astype(np.float64))
+    assert np.array_equal(dxm2, 2.0 * dxm + 0.5 * np.abs(dx0.astype(np.float64)))
+    dw2, dwm2 = oracle.conv2d_bwd_filter(x, dy, w.shape, pad=shape["pad"], stride=shape["stride"], alpha=-1.0, beta=3.0,
+                                         dw0=dw0)
+    assert np.array_equal(dw2, -dw + 3.0 * dw0.astype(np.float64))
+    assert np.array_equal(dwm2, dwm + 3.0 * np.abs(dw0.astype(np.float64)))
+    idx = np.arange(dx.size)[::2]
+    r, m = oracle.conv2d_bwd_data(dy, w, x.shape, pad=shape["pad"], stride=shape["stride"], alpha=2.0, beta=-0.5,
+                                  dx0=dx0, idx=idx)
+    assert np.array_equal(r, dx2.reshape(-1)[idx]) and np.array_equal(m, dxm2.reshape(-1)[idx])
+    idx = np.arange(dw.size)[::3]
+    r, m = oracle.conv2d_bwd_filter(x, dy, w.shape, pad=shape["pad"], stride=shape["stride"], alpha=-1.0, beta=3.0,
+                                    dw0=dw0, idx=idx)
+    assert np.array_equal(r, dw2.reshape(-1)[idx]) and np.array_equal(m, dwm2.reshape(-1)[idx])
+
+
+def test_conv_backward_closed_forms():
+    # centre-delta filter, pad 1: forward is the identity, so dx = dy; dw[j][c] at the centre = <dy_j, x_c>
+    rng = np.random.default_rng(59)
+    N, C, H, W = 2, 3, 5, 4
+    x = rng.integers(-3, 4, size=(N, C, H, W)).astype(np.float32)
+    dy = rng.integers(-3, 4, size=(N, C, H, W)).astype(np.float32)
+    centre = np.zeros((C, C, 3, 3), dtype=np.float32)
+    for c in range(C):
+        centre[c, c, 1, 1] = 1.0
+    dx, _ = oracle.conv2d_bwd_data(dy, centre, x.shape, pad=(1, 1))
+    assert np.array_equal(dx, dy.astype(np.float64))
+    dw, _ = oracle.conv2d_bwd_filter(x, dy, centre.shape, pad=(1, 1))
+    want_centre = np.einsum("njhw,nchw->jc", dy.astype(np.int64), x.astype(np.int64))
+    assert np.array_equal(dw[:, :, 1, 1], want_centre.astype(np.float64))
+    # corner tap (0,0) sees x shifted by (-1,-1): dw[j][c][0][0] = sum dy[p][q] * x[p-1][q-1]
+    want_corner = np.einsum("njhw,nchw->jc", dy[:, :, 1:, 1:].astype(np.int64), x[:, :, :-1, :-1].astype(np.int64))
+    assert np.array_equal(dw[:, :, 0, 0], want_corner.astype(np.float64))
+    # all ones: every dx element counts the (j, r, s) terms that reach it
+    ones_dy = np.ones((1, 2, 4, 4), dtype=np.float32)
+    ones_w = np.ones((2, 3, 3, 3), dtype=np.float32)
+    dx, _ = oracle.conv2d_bwd_data(ones_dy, ones_w, (1, 3, 4, 4), pad=(1, 1))
+    want = np.full((4, 4), 9.0)
+    want[0, :] = want[-1, :] = 6.0
+    want[:, 0] = want[:, -1] = 6.0
+    want[0, 0] = want[0, -1] = want[-1, 0] = want[-1, -1] = 4.0
+    assert np.array_equal(dx, np.broadcast_to(2 * want, dx.shape))
+    # 1x1: dx = W^T dy per pixel, dw = dy x^T summed over pixels (integer exact)
+    w11 = rng.integers(-3, 4, size=(4, 3, 1, 1)).astype(np.float32)
+    dy11 = rng.integers(-3, 4, size=(2, 4, 5, 4)).astype(np.float32)
+    dx, _ = oracle.conv2d_bwd_data(dy11, w11, (2, 3, 5, 4))
+    assert np.array_equal(dx, np.einsum("jc,njhw->nchw", w11[:, :, 0, 0].astype(np.int64), dy11.astype(np.int64)).astype(np.float64))
+    dw, _ = oracle.conv2d_bwd_filter(x, dy11, w11.shape)
+    assert np.array_equal(dw[:, :, 0, 0], np.einsum("njhw,nchw->jc", dy11.astype(np.int64), x.astype(np.int64)).astype(np.float64))
