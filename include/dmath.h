@@ -114,6 +114,30 @@ dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W,
                               float beta, float *y, void *stream);
 
 /*
+ * Gradient of dmath_conv2d_fwd with respect to x (the backward pass of the same DNN primitive; the
+ * paper's pipeline is forward and backward):
+ *
+ *     dx[n][c][h][w] = alpha * sum over (j, r, s) and the (p, q) with p*stride_h + r - pad_h == h and
+ *                              q*stride_w + s - pad_w == w of  dy[n][j][p][q] * w[j][c][r][s]
+ *                      + beta * dx[n][c][h][w]
+ *
+ * N, C, H, W, Kout, R, S, pads and strides describe the FORWARD convolution; dy is N x Kout x P x Q
+ * with P, Q as defined there, w is Kout x C x R x S, dx is N x C x H x W.  It runs on the same kernels
+ * as the forward pass with the roles of the channel dimensions exchanged, and always needs a registered
+ * workspace of at least C*Kout*R*S*4 bytes (rounded up to 256) for the transposed filters: without one
+ * it returns WORKSPACE.  Stride 1 with pads smaller than the filter takes the fast forward-style path;
+ * other strides and pads use a general gather.  Conventions for empty tensors, alpha == 0 and beta == 0,
+ * and the error codes are those of dmath_conv2d_fwd (argument positions likewise, dy in place of x and
+ * dx in place of y).
+ */
+dmath_status dmath_conv2d_bwd_data(int64_t N, int64_t C, int64_t H, int64_t W,
+                                   int64_t Kout, int64_t R, int64_t S,
+                                   int64_t pad_h, int64_t pad_w,
+                                   int64_t stride_h, int64_t stride_w,
+                                   float alpha, const float *dy, const float *w,
+                                   float beta, float *dx, void *stream);
+
+/*
  * Scratch for the split-K path of dmath_gemm (used when the output alone has
  * too few tiles to fill the device, as for the skinny products of a fully
  * connected layer).  dmath_gemm_workspace_bytes() returns how many bytes the

@@ -21,7 +21,7 @@ struct CfgDesc {
     const char *name;
     int BM, BN, BK, NT, lds_bytes;
     int (*gemm)(const GemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);
-    int (*conv)(const ConvArgs &, bool vec, bool tap_major, hipStream_t);
+    int (*conv)(const ConvArgs &, bool vec, int loader_kind, hipStream_t);
 };
 
 // Defined one per translation unit.

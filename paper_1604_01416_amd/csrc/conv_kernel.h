@@ -8,6 +8,7 @@
 // never stored: the loaders below generate each of its elements from x with the zero halo applied.
 // column = (n*P + p)*Q + q.  Two orders of k are implemented (any order gives the same sums):
 //   - generic (LoaderConvX): k = (c*R + r)*S + s, the order of w in memory; works for every shape.
+//     Its backward-data form generates the operand of the data gradient instead (see below).
 //   - tap-major (LoaderConvTap): k = ((cb*R + r)*S + s)*BK + cc for channel c = cb*BK + cc, with C a
 //     multiple of the K tile BK, so a K tile is BK channels of ONE filter tap: the halo test and the
 //     tap offset are per tile instead of per element, and a K row is a plain scalar offset H*W away
@@ -28,6 +29,7 @@ struct ConvArgs {
     int RS, PQ;
     int64_t CRS, NPQ;
     uint32_t magic_RS, magic_S;  // ceil(2^32 / d) for d > 1 (see fast_div); unused for d == 1
+    uint32_t magic_sh, magic_sw; // the same for the strides (backward-data form of the generic loader)
     float alpha, beta;
     int tiles_m, tiles_n;
     int yvec;  // y is 16-byte aligned and P*Q is a multiple of 4
@@ -46,7 +48,13 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t magic, int d)
 // Loader of the generated operand.  Lanes run along the output pixels (contiguous q in x), each
 // thread keeps one column and walks k; k is uniform over a wave, so (c, r, s) and the offset of the
 // tap are scalar work, and only the halo test and the load itself are per lane.
-template <int BN, int BK, int NT, int LD, int ROT>
+//
+// BWD = true generates the operand of the data gradient: the columns are the pixels (n, h, w) of dx,
+// k = (j*R + r)*S + s runs over output channels and taps, and the element is dy[n][j][p][q] with
+// p = (h + pad_h - r) / stride_h, q = (w + pad_w - s) / stride_w when both divisions are exact and
+// land inside dy, else 0.  In that form the ConvArgs fields describe the roles, not the names:
+// x = dy, C = Kout, H x W = the P x Q extent of dy, P x Q = the H x W extent of dx.
+template <int BN, int BK, int NT, int LD, int ROT, bool BWD>
 struct LoaderConvX {
     static constexpr int KG = NT / BN;  // k rows loaded side by side
     static constexpr int NQ = BK / KG;  // k rows per thread and tile
@@ -60,6 +68,8 @@ struct LoaderConvX {
     int H, W, S, RS, HW;
     int64_t CRS;
     uint32_t magic_RS, magic_S;
+    int sh, sw;
+    uint32_t magic_sh, magic_sw;
     float v[NQ];
 
     __device__ __forceinline__ void init(const ConvArgs &a, int64_t c0, int kstart, int tid)
@@ -69,15 +79,22 @@ struct LoaderConvX {
         knext = kstart;
         H = a.H; W = a.W; S = a.S; RS = a.RS; HW = a.H * a.W; CRS = a.CRS;
         magic_RS = a.magic_RS; magic_S = a.magic_S;
+        sh = a.stride_h; sw = a.stride_w; magic_sh = a.magic_sh; magic_sw = a.magic_sw;
         int64_t gc = c0 + col;
         col_ok = gc < a.NPQ;
         gc = col_ok ? gc : a.NPQ - 1;
         const int n = (int)(gc / a.PQ);
         const int pq = (int)(gc - (int64_t)n * a.PQ);
         const int p = pq / a.Q, q = pq - p * a.Q;
-        ih0 = p * a.stride_h - a.pad_h;
-        iw0 = q * a.stride_w - a.pad_w;
-        xcol = a.x + (int64_t)n * a.C * HW + (int64_t)ih0 * W + iw0;
+        if (BWD) {
+            ih0 = p + a.pad_h;
+            iw0 = q + a.pad_w;
+            xcol = a.x + (int64_t)n * a.C * HW;
+        } else {
+            ih0 = p * a.stride_h - a.pad_h;
+            iw0 = q * a.stride_w - a.pad_w;
+            xcol = a.x + (int64_t)n * a.C * HW + (int64_t)ih0 * W + iw0;
+        }
     }
     template <int I>
     __device__ __forceinline__ void load_piece()
@@ -87,10 +104,19 @@ struct LoaderConvX {
         const uint32_t rs = k - c * (uint32_t)RS;
         const uint32_t r = fast_div(rs, magic_S, S);
         const uint32_t s = rs - r * (uint32_t)S;
-        const int off = (int)c * HW + (int)r * W + (int)s;
-        const bool ok = col_ok && (int64_t)k < CRS && (unsigned)(ih0 + (int)r) < (unsigned)H &&
-                        (unsigned)(iw0 + (int)s) < (unsigned)W;
-        v[I] = ok ? xcol[off] : 0.0f;
+        if (BWD) {
+            const int th = ih0 - (int)r, tw = iw0 - (int)s;
+            const uint32_t p = fast_div((uint32_t)(th < 0 ? 0 : th), magic_sh, sh);
+            const uint32_t q = fast_div((uint32_t)(tw < 0 ? 0 : tw), magic_sw, sw);
+            const bool ok = col_ok && (int64_t)k < CRS && th >= 0 && tw >= 0 && (int)(p * (uint32_t)sh) == th &&
+                            (int)(q * (uint32_t)sw) == tw && p < (uint32_t)H && q < (uint32_t)W;
+            v[I] = ok ? xcol[(int)c * HW + (int)p * W + (int)q] : 0.0f;
+        } else {
+            const int off = (int)c * HW + (int)r * W + (int)s;
+            const bool ok = col_ok && (int64_t)k < CRS && (unsigned)(ih0 + (int)r) < (unsigned)H &&
+                            (unsigned)(iw0 + (int)s) < (unsigned)W;
+            v[I] = ok ? xcol[off] : 0.0f;
+        }
     }
     __device__ __forceinline__ void advance() { knext += BK; }
     // the partial last tile needs nothing special: k >= C*R*S is already generated as zero
@@ -183,17 +209,21 @@ struct LoaderConvTap {
     }
 };
 
-template <class Cfg, bool TAP>
+// Which generator of the unfolded operand a kernel uses.
+enum ConvLoaderKind { kConvGeneric = 0, kConvTapMajor = 1, kConvBwdData = 2 };
+
+template <class Cfg, int KIND>
 struct ConvColLoaderSel {
-    typedef LoaderConvX<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT> type;
+    typedef LoaderConvX<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, KIND == kConvBwdData> type;
 };
 template <class Cfg>
-struct ConvColLoaderSel<Cfg, true> {
+struct ConvColLoaderSel<Cfg, kConvTapMajor> {
     typedef LoaderConvTap<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT> type;
 };
 
-// VEC: 16-byte loads of the filter matrix are aligned.  TAP: tap-major k order (a.w is then w').
-template <class Cfg, bool VEC, bool TAP>
+// VEC: 16-byte loads of the filter matrix are aligned.  KIND: generator of the other operand; for the
+// tap-major and backward-data kinds a.w is the filter matrix re-laid out in the workspace.
+template <class Cfg, bool VEC, int KIND>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(const ConvArgs a)
 {
     __shared__ __attribute__((aligned(16))) float smem[Cfg::STAGES * Cfg::STAGE_FLOATS];
@@ -209,7 +239,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
     slice_range(ktiles_total, (int)(a.CRS - (int64_t)ktiles_total * Cfg::BK), wi.slice, wi.nslice, kt0, T, krem);
 
     typename LoaderKSel<Cfg::LKV, Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC>::type rl;
-    typename ConvColLoaderSel<Cfg, TAP>::type cl;
+    typename ConvColLoaderSel<Cfg, KIND>::type cl;
     rl.init(a.w, a.CRS, m0, a.Kout, (int64_t)kt0 * Cfg::BK, threadIdx.x);
     cl.init(a, n0, kt0 * Cfg::BK, threadIdx.x);
 
@@ -278,17 +308,22 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
 }
 
 template <class Cfg>
-int launch_conv_cfg(const ConvArgs &a, bool vec, bool tap, hipStream_t stream)
+int launch_conv_cfg(const ConvArgs &a, bool vec, int kind, hipStream_t stream)
 {
     const int tiles = a.tiles_m * a.tiles_n;
     const dim3 grid((unsigned)(a.split.dp_tiles + (tiles - a.split.dp_tiles) * a.split.splits)), block(Cfg::NT);
-    if (tap) {
+    if (kind == kConvTapMajor) {
         if (a.C % Cfg::BK != 0 || !vec) return (int)hipErrorInvalidValue;  // the caller checks this first
-        hipLaunchKernelGGL((conv_tile_kernel<Cfg, true, true>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((conv_tile_kernel<Cfg, true, kConvTapMajor>), grid, block, 0, stream, a);
+    } else if (kind == kConvBwdData) {
+        if (vec)
+            hipLaunchKernelGGL((conv_tile_kernel<Cfg, true, kConvBwdData>), grid, block, 0, stream, a);
+        else
+            hipLaunchKernelGGL((conv_tile_kernel<Cfg, false, kConvBwdData>), grid, block, 0, stream, a);
     } else if (vec) {
-        hipLaunchKernelGGL((conv_tile_kernel<Cfg, true, false>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((conv_tile_kernel<Cfg, true, kConvGeneric>), grid, block, 0, stream, a);
     } else {
-        hipLaunchKernelGGL((conv_tile_kernel<Cfg, false, false>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((conv_tile_kernel<Cfg, false, kConvGeneric>), grid, block, 0, stream, a);
     }
     return (int)hipGetLastError();
 }

@@ -96,16 +96,30 @@ __global__ void zero_u32_kernel(unsigned *p, int n)
     if (i < n) p[i] = 0u;
 }
 
-// w'[j][cb][rs][cc] = w[j][cb*BK + cc][rs]: the filter matrix in the tap-major k order of LoaderConvTap.
-__global__ void conv_filter_tap_major_kernel(const float *w, float *wt, int64_t Kout, int C, int RS, int BK)
+// Copies the filters into the workspace as the rows x (chans*RS) matrix a convolution kernel reads.
+// Forward (transposed == 0): rows = Kout, chans = C, source w[row][ch][tap].  Backward-data
+// (transposed == 1): rows = C, chans = Kout, source w[ch][row][tap].  flip reverses the tap index
+// (r, s) -> (R-1-r, S-1-s).  tap_major: destination k = ((cb*RS + tap)*BK + cc) for channel cb*BK + cc
+// (the order LoaderConvTap walks); else k = ch*RS + tap.
+__global__ void conv_filter_copy_kernel(const float *w, float *wt, int64_t rows, int chans, int RS, int BK,
+                                        int transposed, int flip, int tap_major)
 {
-    const int64_t CRS = (int64_t)C * RS, total = Kout * CRS;
+    const int64_t KK = (int64_t)chans * RS, total = rows * KK;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t j = e / CRS;
-        const int rem = (int)(e - j * CRS);
-        const int t = rem / BK, cc = rem - t * BK;
-        const int cb = t / RS, rs = t - cb * RS;
-        wt[e] = w[(j * C + cb * BK + cc) * RS + rs];
+        const int64_t row = e / KK;
+        const int rem = (int)(e - row * KK);
+        int ch, tap;
+        if (tap_major) {
+            const int t = rem / BK, cc = rem - t * BK;
+            const int cb = t / RS;
+            tap = t - cb * RS;
+            ch = cb * BK + cc;
+        } else {
+            ch = rem / RS;
+            tap = rem - ch * RS;
+        }
+        if (flip) tap = RS - 1 - tap;
+        wt[e] = transposed ? w[((int64_t)ch * rows + row) * RS + tap] : w[(row * chans + ch) * RS + tap];
     }
 }
 
@@ -408,11 +422,13 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     return DMATH_OK;
 }
 
-dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W, int64_t Kout, int64_t R, int64_t S,
-                              int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, float alpha,
-                              const float *x, const float *w, float beta, float *y, void *stream_)
+// Shared body of the convolution entry points.  The kernel computes  out_mat[rows x cols] =
+// filt_mat[rows x KK] * unfolded(in)[KK x cols]  where, forward: rows = Kout, cols = N*P*Q pixels of y,
+// KK = C*R*S, in = x; backward-data: rows = C, cols = N*H*W pixels of dx, KK = Kout*R*S, in = dy.
+static dmath_status run_conv(bool bwd_data, int64_t N, int64_t C, int64_t H, int64_t W, int64_t Kout, int64_t R,
+                             int64_t S, int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, float alpha,
+                             const float *in, const float *w, float beta, float *out, hipStream_t stream)
 {
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 1);
     if (C < 0) return fail(DMATH_ERR_INVALID_ARG, 2);
     if (H < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
@@ -428,82 +444,112 @@ dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W, int64_
     if (W + 2 * pad_w < S) return fail(DMATH_ERR_INVALID_ARG, 7);
     const int64_t P = (H + 2 * pad_h - R) / stride_h + 1;
     const int64_t Q = (W + 2 * pad_w - S) / stride_w + 1;
-    const int64_t PQ = P * Q, NPQ = N * PQ, CRS = C * R * S;
-    if (NPQ == 0 || Kout == 0) return DMATH_OK;
-    if (y == nullptr) return fail(DMATH_ERR_NULL_PTR, 16);
-    const bool no_product = (CRS == 0 || alpha == 0.0f);
+    const int64_t RS = R * S;
+    // roles
+    const int64_t rows = bwd_data ? C : Kout;          // rows of the product = channels of the output tensor
+    const int64_t chans = bwd_data ? Kout : C;         // channels of the input tensor
+    const int64_t in_h = bwd_data ? P : H, in_w = bwd_data ? Q : W;
+    const int64_t out_h = bwd_data ? H : P, out_w = bwd_data ? W : Q;
+    const int64_t out_pix = out_h * out_w, cols = N * out_pix, KK = chans * RS;
+    if (cols == 0 || rows == 0) return DMATH_OK;
+    if (out == nullptr) return fail(DMATH_ERR_NULL_PTR, 16);
+    const bool no_product = (KK == 0 || in_h * in_w == 0 || alpha == 0.0f);
     if (!no_product) {
-        if (x == nullptr) return fail(DMATH_ERR_NULL_PTR, 13);
+        if (in == nullptr) return fail(DMATH_ERR_NULL_PTR, 13);
         if (w == nullptr) return fail(DMATH_ERR_NULL_PTR, 14);
     }
     // in-kernel tap offsets, magic divisions and tile counters are 32-bit
     const int64_t lim = (int64_t)1 << 31;
-    if (C * H * W >= lim || PQ >= lim || (CRS + 64) * R * S >= ((int64_t)1 << 32) || R * S * S >= lim ||
-        Kout * PQ >= ((int64_t)1 << 40) || pad_h >= lim || pad_w >= lim || stride_h >= lim || stride_w >= lim ||
-        N >= lim || Kout >= lim)
+    if (chans * in_h * in_w >= lim || out_pix >= lim || (KK + 64) * RS >= ((int64_t)1 << 32) || RS * S >= lim ||
+        rows * out_pix >= ((int64_t)1 << 40) || pad_h >= (1 << 15) || pad_w >= (1 << 15) || stride_h >= (1 << 15) ||
+        stride_w >= (1 << 15) || H >= (1 << 15) || W >= (1 << 15) || N >= lim || rows >= lim || KK > ((int64_t)1 << 22))
         return fail(DMATH_ERR_UNSUPPORTED, 2);
 
     if (no_product) {
         if (beta == 1.0f) return DMATH_OK;
-        const int64_t total = NPQ * Kout;
+        const int64_t total = cols * rows;
         const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
-        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, y, total, (int64_t)1, total, beta);
+        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, out, total, (int64_t)1, total, beta);
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
 
-    // The filter copy of the tap-major path sits at the start of the workspace; slices come after it.
-    const size_t wt_bytes = align256((size_t)Kout * (size_t)CRS * sizeof(float));
+    // The filter copy (tap-major forward, every backward-data call) sits at the start of the workspace;
+    // the slices of split tiles come after it.
+    const size_t wt_bytes = align256((size_t)rows * (size_t)KK * sizeof(float));
     const size_t ws_total = g_state.ws ? g_state.ws_bytes : 0;
-    const bool tap_shape = R * S <= 32 && C % 16 == 0 && N * C * H * W * 4 + (pad_h * W + pad_w) * 4 < lim &&
-                           ws_total >= wt_bytes;
-    const size_t split_off = tap_shape ? wt_bytes : 0;
-    Plan plan = resolve_plan(Kout, NPQ, CRS, ws_total - split_off, false);
+    const bool room = ws_total >= wt_bytes;
+    if (bwd_data && !room) return fail(DMATH_ERR_WORKSPACE, 0);
+    // backward-data as a forward convolution of dy with the flipped filters: stride 1 and pads inside the filter
+    const bool as_forward = bwd_data && stride_h == 1 && stride_w == 1 && pad_h <= R - 1 && pad_w <= S - 1;
+    const bool tap_shape = (!bwd_data || as_forward) && room && RS <= 32 && chans % 16 == 0 &&
+                           N * chans * in_h * in_w * 4 + (R * in_w + S) * 4 < lim;
+    const bool copy_filters = bwd_data || tap_shape;
+    const size_t split_off = copy_filters ? wt_bytes : 0;
+    Plan plan = resolve_plan(rows, cols, KK, ws_total - split_off, false);
     if (plan.splits > 1 && plan.dp_tiles == 0)  // the convolution has no plain split-K path: tail splits only
-        plan = choose_plan(Kout, NPQ, CRS, false, g_state.force_cfg, -1);
+        plan = choose_plan(rows, cols, KK, false, g_state.force_cfg, -1);
     const CfgDesc &d = desc(plan.cfg);
-    const int64_t tiles_m = ceil_div(Kout, d.BM), tiles_n = ceil_div(NPQ, d.BN);
+    const int64_t tiles_m = ceil_div(rows, d.BM), tiles_n = ceil_div(cols, d.BN);
     if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 1);
-    if (CRS > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, 2);
+    const bool tap = tap_shape && chans % d.BK == 0;
+    const int kind = tap ? kConvTapMajor : (bwd_data && !as_forward ? kConvBwdData : kConvGeneric);
 
     ConvArgs a;
-    a.x = x;
+    a.x = in;
     a.w = w;
-    a.y = y;
-    a.N = (int)N; a.C = (int)C; a.H = (int)H; a.W = (int)W; a.Kout = (int)Kout;
-    a.R = (int)R; a.S = (int)S; a.P = (int)P; a.Q = (int)Q;
-    a.pad_h = (int)pad_h; a.pad_w = (int)pad_w; a.stride_h = (int)stride_h; a.stride_w = (int)stride_w;
-    a.RS = (int)(R * S);
-    a.PQ = (int)PQ;
-    a.CRS = CRS;
-    a.NPQ = NPQ;
-    a.magic_RS = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)a.RS - 1) / (uint64_t)a.RS);
+    a.y = out;
+    a.N = (int)N; a.C = (int)chans; a.H = (int)in_h; a.W = (int)in_w; a.Kout = (int)rows;
+    a.R = (int)R; a.S = (int)S; a.P = (int)out_h; a.Q = (int)out_w;
+    if (as_forward) {
+        a.pad_h = (int)(R - 1 - pad_h); a.pad_w = (int)(S - 1 - pad_w); a.stride_h = 1; a.stride_w = 1;
+    } else {
+        a.pad_h = (int)pad_h; a.pad_w = (int)pad_w; a.stride_h = (int)stride_h; a.stride_w = (int)stride_w;
+    }
+    a.RS = (int)RS;
+    a.PQ = (int)out_pix;
+    a.CRS = KK;
+    a.NPQ = cols;
+    a.magic_RS = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)RS - 1) / (uint64_t)RS);
     a.magic_S = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)S - 1) / (uint64_t)S);
+    a.magic_sh = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)stride_h - 1) / (uint64_t)stride_h);
+    a.magic_sw = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)stride_w - 1) / (uint64_t)stride_w);
     a.alpha = alpha;
     a.beta = beta;
     a.tiles_m = (int)tiles_m;
     a.tiles_n = (int)tiles_n;
-    a.yvec = (aligned16(y) && PQ % 4 == 0) ? 1 : 0;
-    a.x_bytes = N * C * H * W * 4;
-    bool vec = aligned16(w) && CRS % 4 == 0;
-    // Tap-major path: needs room for the re-laid-out filters, whole K tiles per tap, a tap mask that
-    // fits 32 bits and 31-bit byte offsets into x.
-    const bool tap = tap_shape && C % d.BK == 0;
-    if (tap) {
+    a.yvec = (aligned16(out) && out_pix % 4 == 0) ? 1 : 0;
+    a.x_bytes = N * chans * in_h * in_w * 4;
+    bool vec = aligned16(w) && KK % 4 == 0;
+    if (copy_filters) {
         float *wt = static_cast<float *>(g_state.ws);
-        const int64_t total = Kout * CRS;
+        const int64_t total = rows * KK;
         const int blocks = (int)(ceil_div(total, 256) < 2048 ? ceil_div(total, 256) : 2048);
-        hipLaunchKernelGGL(conv_filter_tap_major_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, Kout, (int)C,
-                           (int)(R * S), d.BK);
+        hipLaunchKernelGGL(conv_filter_copy_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, rows, (int)chans, (int)RS,
+                           d.BK, bwd_data ? 1 : 0, as_forward ? 1 : 0, tap ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
         a.w = wt;
-        vec = true;  // the workspace is 16-byte aligned and C is a multiple of 4
+        vec = KK % 4 == 0;  // the workspace is 16-byte aligned
     }
-    // K slices of the tap-major order must start on a tap's channel block: they do, a slice starts at
-    // a multiple of the K tile and C is a multiple of it.
-    if (!prepare_split(plan, tiles_m * tiles_n, Kout, NPQ, static_cast<char *>(g_state.ws) + split_off, stream, a.split))
+    if (!prepare_split(plan, tiles_m * tiles_n, rows, cols, static_cast<char *>(g_state.ws) + split_off, stream, a.split))
         return fail(DMATH_ERR_LAUNCH, 0);
-    if (d.conv(a, vec, tap, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    if (d.conv(a, vec, kind, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
     return DMATH_OK;
+}
+
+dmath_status dmath_conv2d_fwd(int64_t N, int64_t C, int64_t H, int64_t W, int64_t Kout, int64_t R, int64_t S,
+                              int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, float alpha,
+                              const float *x, const float *w, float beta, float *y, void *stream)
+{
+    return run_conv(false, N, C, H, W, Kout, R, S, pad_h, pad_w, stride_h, stride_w, alpha, x, w, beta, y,
+                    static_cast<hipStream_t>(stream));
+}
+
+dmath_status dmath_conv2d_bwd_data(int64_t N, int64_t C, int64_t H, int64_t W, int64_t Kout, int64_t R, int64_t S,
+                                   int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, float alpha,
+                                   const float *dy, const float *w, float beta, float *dx, void *stream)
+{
+    return run_conv(true, N, C, H, W, Kout, R, S, pad_h, pad_w, stride_h, stride_w, alpha, dy, w, beta, dx,
+                    static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

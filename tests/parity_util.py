@@ -122,3 +122,45 @@ def run_conv_case(dm, torch, N, C, H, W, Kout, R, S, pad, stride, alpha=1.0, bet
         assert np.array_equal(got.astype(np.float64), ref), "integer case must be bit-exact"
         return 0.0
     return check_bound(got, ref, mag, max(1, C * R * S), "conv %s" % ((N, C, H, W, Kout, R, S, pad, stride),))
+
+
+def run_conv_bwd_data_case(dm, torch, N, C, H, W, Kout, R, S, pad, stride, alpha=1.0, beta=0.0, seed=0, ints=False,
+                           exact=False, lead=0):
+    """dmath_conv2d_bwd_data against the oracle's adjoint-of-forward definition."""
+    rng = np.random.default_rng(seed)
+    P = (H + 2 * pad[0] - R) // stride[0] + 1
+    Q = (W + 2 * pad[1] - S) // stride[1] + 1
+    if ints:
+        dy = rng.integers(-3, 4, size=(N, Kout, P, Q)).astype(np.float32)
+        w = rng.integers(-3, 4, size=(Kout, C, R, S)).astype(np.float32)
+        dx0 = rng.integers(-3, 4, size=(N, C, H, W)).astype(np.float32)
+    else:
+        dy = (rng.standard_normal((N, Kout, P, Q)) * 0.1).astype(np.float32)
+        w = (rng.standard_normal((Kout, C, R, S)) * np.sqrt(2.0 / max(1, C * R * S))).astype(np.float32)
+        dx0 = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    if beta == 0.0:
+        dx0[:] = np.nan
+    tail = 8
+
+    def flat_of(t):
+        f = np.full(lead + t.size + tail, GUARD, dtype=np.float32)
+        f[lead:lead + t.size] = t.reshape(-1)
+        return f
+
+    gf, wf, xf = flat_of(dy), flat_of(w), flat_of(dx0)
+    dg, dw, dxd = (torch.from_numpy(f).cuda() for f in (gf, wf, xf))
+    st = dm.dmath_conv2d_bwd_data(N, C, H, W, Kout, R, S, pad[0], pad[1], stride[0], stride[1], alpha,
+                                  dg[lead:], dw[lead:], beta, dxd[lead:])
+    assert st == dm.OK, (dm.dmath_status_string(st), dm.dmath_last_error_arg())
+    torch.cuda.synchronize()
+    out = dxd.cpu().numpy()
+    assert np.isnan(out[:lead]).all() and np.isnan(out[lead + dx0.size:]).all(), "wrote outside dx"
+    got = out[lead:lead + dx0.size].reshape(dx0.shape)
+    ref, mag = oracle.conv2d_bwd_data(dy, w, (N, C, H, W), pad=pad, stride=stride, alpha=alpha, beta=beta,
+                                      dx0=dx0 if beta != 0.0 else None)
+    if got.size == 0:
+        return 0.0
+    if exact:
+        assert np.array_equal(got.astype(np.float64), ref), "integer case must be bit-exact"
+        return 0.0
+    return check_bound(got, ref, mag, max(1, Kout * R * S), "conv bwd-data %s" % ((N, C, H, W, Kout, R, S, pad, stride),))

@@ -14,7 +14,7 @@ import pytest
 
 import oracle
 from paper_1604_01416_amd import workloads
-from parity_util import check_bound, run_conv_case, run_gemm_case
+from parity_util import check_bound, run_conv_bwd_data_case, run_conv_case, run_gemm_case
 
 pytestmark = pytest.mark.gpu
 
@@ -388,3 +388,68 @@ def test_config5_shape_small_batch_every_element(dm, torch):
     torch.cuda.synchronize()
     ref, mag = oracle.conv2d_fwd(wl.x, wl.w, pad=wl.pad, stride=wl.stride)
     check_bound(dy.cpu().numpy(), ref, mag, 2304, "config 5 shape, batch 2")
+
+
+# ------------------------------------------------------------------ convolution, backward-data
+
+CONV_BWD_DATA = [
+    dict(N=2, C=3, H=7, W=5, Kout=4, R=3, S=3, pad=(1, 1), stride=(1, 1)),       # forward-style path, generic order
+    dict(N=1, C=2, H=9, W=6, Kout=3, R=3, S=2, pad=(0, 0), stride=(2, 2)),       # strided gather
+    dict(N=2, C=5, H=8, W=11, Kout=2, R=5, S=3, pad=(2, 1), stride=(2, 3)),
+    dict(N=3, C=20, H=14, W=14, Kout=32, R=3, S=3, pad=(1, 1), stride=(1, 1)),   # Kout multiple of 16: tap-major
+    dict(N=2, C=130, H=9, W=10, Kout=48, R=3, S=3, pad=(1, 1), stride=(1, 1)),
+    dict(N=2, C=40, H=6, W=6, Kout=16, R=1, S=1, pad=(1, 1), stride=(1, 1)),     # pad beyond the filter: gather
+    dict(N=2, C=33, H=12, W=12, Kout=64, R=3, S=3, pad=(1, 1), stride=(2, 2)),
+    dict(N=1, C=4, H=5, W=5, Kout=6, R=5, S=5, pad=(0, 0), stride=(1, 1)),
+]
+
+
+@pytest.mark.parametrize("shape", CONV_BWD_DATA)
+def test_conv_bwd_data_small(dm, torch, shape):
+    run_conv_bwd_data_case(dm, torch, seed=shape["H"], **shape)
+    run_conv_bwd_data_case(dm, torch, seed=shape["W"], alpha=0.5, beta=-1.5, lead=1, **shape)
+    run_conv_bwd_data_case(dm, torch, seed=shape["C"], ints=True, exact=True, beta=1.0, **shape)
+
+
+@pytest.mark.parametrize("cfg", range(6))
+def test_conv_bwd_data_every_config(dm, torch, cfg):
+    if cfg >= dm.dmath_num_configs():
+        pytest.skip("no such configuration")
+    dm.dmath_set_override(cfg, 1)
+    run_conv_bwd_data_case(dm, torch, N=2, C=72, H=14, W=14, Kout=32, R=3, S=3, pad=(1, 1), stride=(1, 1), seed=cfg,
+                           ints=True, exact=True)
+    run_conv_bwd_data_case(dm, torch, N=2, C=260, H=11, W=13, Kout=5, R=3, S=3, pad=(1, 1), stride=(2, 1), seed=cfg + 5,
+                           alpha=2.0, beta=1.0, lead=3)
+
+
+def test_conv_bwd_data_needs_a_workspace(dm, torch):
+    ws = dm._test_workspace
+    dm.check(dm.dmath_set_workspace(None, 0))
+    try:
+        t = torch.zeros(4096, device="cuda")
+        assert dm.dmath_conv2d_bwd_data(1, 2, 4, 4, 3, 3, 3, 1, 1, 1, 1, 1.0, t, t, 0.0, t) == dm.ERR_WORKSPACE
+    finally:
+        dm.check(dm.dmath_set_workspace(ws, ws.numel()))
+
+
+def test_config5_shape_bwd_data_full_size_sampled(dm, torch):
+    """Data gradient of the config 5 layer: dy 128x256x28x28, w 256x256x3x3 -> dx 128x256x28x28."""
+    wl = workloads.config5()
+    N, Kout, P, Q = wl.out_shape
+    _, C, H, W = wl.x.shape
+    rng = np.random.default_rng(7)
+    dy = (rng.standard_normal((N, Kout, P, Q)) * 1e-2).astype(np.float32)
+    ddy, dw = torch.from_numpy(dy).cuda(), torch.from_numpy(wl.w).cuda()
+    ddx = torch.full((N, C, H, W), float("nan"), device="cuda")
+    dm.check(dm.dmath_conv2d_bwd_data(N, C, H, W, Kout, 3, 3, 1, 1, 1, 1, 1.0, ddy, dw, 0.0, ddx))
+    torch.cuda.synchronize()
+    got = ddx.cpu().numpy()
+    assert np.isfinite(got).all()
+    idx = rng.choice(got.size, size=200000, replace=False)
+    plane = H * W
+    for n, c in [(0, 0), (N - 1, C - 1), (N // 2, 129)]:
+        base = (n * C + c) * plane
+        idx = np.concatenate([idx, np.arange(base, base + plane)])
+    ref, mag = oracle.conv2d_bwd_data(dy, wl.w, wl.x.shape, pad=wl.pad, stride=wl.stride, idx=idx)
+    r = check_bound(got.reshape(-1)[idx], ref, mag, Kout * 9, "config 5 bwd-data sampled")
+    print("config 5 bwd-data max err/bound %.3g" % r)
