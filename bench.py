@@ -40,7 +40,7 @@ MEASURED_HBM_TRAFFIC_BYTES = {
     "conv": int(((94305.9 + 1812.2) * 2.0 + 119682.4 + 2304.0) * 1024),         # profiles/conv3x3_n128_c256_k256_28x28_kernels.md
 }
 
-WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv")
+WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv", "conv_bwd_data", "conv_bwd_filter")
 
 
 def _device_arrays(torch, arrays):
@@ -160,18 +160,32 @@ def main():
 
     cpu_baseline = None
     conv = None
-    if args.workload == "conv":
+    if args.workload in ("conv", "conv_bwd_data", "conv_bwd_filter"):
         conv = workloads.config5()
         N, Kout, P, Q = conv.out_shape
         _, C, H, W = conv.x.shape
         dx, dw = torch.from_numpy(conv.x).cuda(), torch.from_numpy(conv.w).cuda()
         dy = torch.empty((N, Kout, P, Q), device="cuda")
+        bwd = args.workload == "conv_bwd_data"
+        bwd_filter = args.workload == "conv_bwd_filter"
+        if bwd or bwd_filter:   # gradients of the same layer: dy ~ N(0, 1e-2), seed 5
+            grad = (np.random.default_rng(5).standard_normal((N, Kout, P, Q)) * 1e-2).astype(np.float32)
+            dy = torch.from_numpy(grad).cuda()
+        if bwd:
+            dx = torch.empty((N, C, H, W), device="cuda")
+        if bwd_filter:
+            dw = torch.empty((Kout, C, 3, 3), device="cuda")
 
         def step():
-            dm.check(dm.dmath_conv2d_fwd(N, C, H, W, Kout, 3, 3, 1, 1, 1, 1, 1.0, dx, dw, 0.0, dy))
+            if bwd_filter:
+                dm.check(dm.dmath_conv2d_bwd_filter(N, C, H, W, Kout, 3, 3, 1, 1, 1, 1, 1.0, dx, dy, 0.0, dw))
+            elif bwd:
+                dm.check(dm.dmath_conv2d_bwd_data(N, C, H, W, Kout, 3, 3, 1, 1, 1, 1, 1.0, dy, dw, 0.0, dx))
+            else:
+                dm.check(dm.dmath_conv2d_fwd(N, C, H, W, Kout, 3, 3, 1, 1, 1, 1, 1.0, dx, dw, 0.0, dy))
 
         flop, alg_bytes, launches = conv.flop, conv.algorithmic_bytes, 1
-        wl_name = conv.name
+        wl_name = conv.name + ("_bwd_data" if bwd else "_bwd_filter" if bwd_filter else "")
     else:
         wl = {"gemm4096": workloads.config2, "gemm256": workloads.config1, "summa": workloads.config3,
               "fc": workloads.config4}[args.workload]()
@@ -207,7 +221,9 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        if conv is not None:
+        if conv is not None and args.workload != "conv":
+            cpu_baseline = None   # the forward workload carries the oracle timing of this layer
+        elif conv is not None:
             cpu_baseline = _cpu_baseline_conv(oracle, conv)
         else:
             cpu_baseline = _cpu_baseline_gemm(oracle, wl.calls[0], wl.arrays)

@@ -138,6 +138,27 @@ dmath_status dmath_conv2d_bwd_data(int64_t N, int64_t C, int64_t H, int64_t W,
                                    float beta, float *dx, void *stream);
 
 /*
+ * Gradient of dmath_conv2d_fwd with respect to the filters:
+ *
+ *     dw[j][c][r][s] = alpha * sum over (n, p, q) with the tap inside x of
+ *                              dy[n][j][p][q] * x[n][c][p*stride_h + r - pad_h][q*stride_w + s - pad_w]
+ *                      + beta * dw[j][c][r][s]
+ *
+ * Arguments describe the FORWARD convolution; x is N x C x H x W, dy is N x Kout x P x Q, dw is
+ * Kout x C x R x S.  The reduction over all output pixels is long and the result small, so with a
+ * registered workspace the sum is cut into K slices (dmath_gemm's plain split-K, sized like a GEMM with
+ * M = Kout, N = C*R*S, K = N*P*Q: see dmath_gemm_workspace_bytes); without one it runs unsplit.
+ * Conventions and error codes as for dmath_conv2d_fwd (argument 13 is x, 14 is dy, 16 is dw);
+ * UNSUPPORTED if the rotated-image comparison configuration is forced.
+ */
+dmath_status dmath_conv2d_bwd_filter(int64_t N, int64_t C, int64_t H, int64_t W,
+                                     int64_t Kout, int64_t R, int64_t S,
+                                     int64_t pad_h, int64_t pad_w,
+                                     int64_t stride_h, int64_t stride_w,
+                                     float alpha, const float *x, const float *dy,
+                                     float beta, float *dw, void *stream);
+
+/*
  * Scratch for the split-K path of dmath_gemm (used when the output alone has
  * too few tiles to fill the device, as for the skinny products of a fully
  * connected layer).  dmath_gemm_workspace_bytes() returns how many bytes the

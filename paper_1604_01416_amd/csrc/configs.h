@@ -1,6 +1,7 @@
 // Table of tile configurations.  Each entry is compiled in its own translation unit
 // (tile_instance.hip with -DDMATH_CFG_INDEX=<i>) and reached through the function table below.
 #pragma once
+#include "conv_bwd_filter_kernel.h"
 #include "conv_kernel.h"
 #include "gemm_kernel.h"
 
@@ -22,6 +23,7 @@ struct CfgDesc {
     int BM, BN, BK, NT, lds_bytes;
     int (*gemm)(const GemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);
     int (*conv)(const ConvArgs &, bool vec, int loader_kind, hipStream_t);
+    int (*conv_bwd_filter)(const ConvFilterGradArgs &, bool quad_in_image, hipStream_t);  // fails on the rotated-image entry
 };
 
 // Defined one per translation unit.

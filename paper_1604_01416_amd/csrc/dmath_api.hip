@@ -552,4 +552,85 @@ dmath_status dmath_conv2d_bwd_data(int64_t N, int64_t C, int64_t H, int64_t W, i
                     static_cast<hipStream_t>(stream));
 }
 
+dmath_status dmath_conv2d_bwd_filter(int64_t N, int64_t C, int64_t H, int64_t W, int64_t Kout, int64_t R, int64_t S,
+                                     int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, float alpha,
+                                     const float *x, const float *dy, float beta, float *dw, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (C < 0) return fail(DMATH_ERR_INVALID_ARG, 2);
+    if (H < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
+    if (W < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
+    if (Kout < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
+    if (R < 1) return fail(DMATH_ERR_INVALID_ARG, 6);
+    if (S < 1) return fail(DMATH_ERR_INVALID_ARG, 7);
+    if (pad_h < 0) return fail(DMATH_ERR_INVALID_ARG, 8);
+    if (pad_w < 0) return fail(DMATH_ERR_INVALID_ARG, 9);
+    if (stride_h < 1) return fail(DMATH_ERR_INVALID_ARG, 10);
+    if (stride_w < 1) return fail(DMATH_ERR_INVALID_ARG, 11);
+    if (H + 2 * pad_h < R) return fail(DMATH_ERR_INVALID_ARG, 6);
+    if (W + 2 * pad_w < S) return fail(DMATH_ERR_INVALID_ARG, 7);
+    const int64_t P = (H + 2 * pad_h - R) / stride_h + 1;
+    const int64_t Q = (W + 2 * pad_w - S) / stride_w + 1;
+    const int64_t RS = R * S, CRS = C * RS, PQ = P * Q, NPQ = N * PQ;
+    if (Kout == 0 || CRS == 0) return DMATH_OK;
+    if (dw == nullptr) return fail(DMATH_ERR_NULL_PTR, 16);
+    const bool no_product = (NPQ == 0 || alpha == 0.0f);
+    if (!no_product) {
+        if (x == nullptr) return fail(DMATH_ERR_NULL_PTR, 13);
+        if (dy == nullptr) return fail(DMATH_ERR_NULL_PTR, 14);
+    }
+    const int64_t lim = (int64_t)1 << 31;
+    if (C * H * W >= lim || PQ >= lim || CRS >= lim || Kout >= lim || H >= (1 << 15) || W >= (1 << 15) ||
+        pad_h >= (1 << 15) || pad_w >= (1 << 15) || stride_h >= (1 << 15) || stride_w >= (1 << 15) || NPQ >= ((int64_t)1 << 33))
+        return fail(DMATH_ERR_UNSUPPORTED, 2);
+    if (no_product) {
+        if (beta == 1.0f) return DMATH_OK;
+        const int64_t total = Kout * CRS;
+        const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
+        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, dw, total, (int64_t)1, total, beta);
+        return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
+    }
+
+    const Plan plan = resolve_plan(Kout, CRS, NPQ, g_state.ws ? g_state.ws_bytes : 0, false);
+    const CfgDesc &d = desc(plan.cfg);
+    const int64_t tiles_m = ceil_div(Kout, d.BM), tiles_n = ceil_div(CRS, d.BN);
+    if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 1);
+
+    ConvFilterGradArgs a;
+    a.x = x;
+    a.dy = dy;
+    a.dw = dw;
+    a.N = (int)N; a.C = (int)C; a.H = (int)H; a.W = (int)W; a.Kout = (int)Kout;
+    a.R = (int)R; a.S = (int)S; a.P = (int)P; a.Q = (int)Q;
+    a.pad_h = (int)pad_h; a.pad_w = (int)pad_w; a.stride_h = (int)stride_h; a.stride_w = (int)stride_w;
+    a.PQ = (int)PQ;
+    a.RS = (int)RS;
+    a.CRS = CRS;
+    a.NPQ = NPQ;
+    a.alpha = alpha;
+    a.beta = beta;
+    a.tiles_m = (int)tiles_m;
+    a.tiles_n = (int)tiles_n;
+    a.cvec = (aligned16(dw) && CRS % 4 == 0) ? 1 : 0;
+    if (!prepare_split(plan, tiles_m * tiles_n, Kout, CRS, g_state.ws, stream, a.split)) return fail(DMATH_ERR_LAUNCH, 0);
+    const bool quad_in_image = PQ % 4 == 0 && aligned16(dy);
+    const int rc = d.conv_bwd_filter(a, quad_in_image, stream);
+    if (rc == (int)hipErrorInvalidValue) return fail(DMATH_ERR_UNSUPPORTED, 0);
+    if (rc != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    if (a.split.plain) {
+        const bool v4 = a.cvec != 0;
+        const int64_t items = v4 ? Kout * (CRS / 4) : Kout * CRS;
+        const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
+        if (v4)
+            hipLaunchKernelGGL(splitk_reduce_kernel_v4, dim3(blocks), dim3(256), 0, stream,
+                               static_cast<const float *>(g_state.ws), plan.splits, Kout * CRS, dw, CRS, Kout, CRS, alpha, beta);
+        else
+            hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
+                               static_cast<const float *>(g_state.ws), plan.splits, Kout * CRS, dw, CRS, Kout, CRS, alpha, beta);
+        if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    }
+    return DMATH_OK;
+}
+
 }  // extern "C"

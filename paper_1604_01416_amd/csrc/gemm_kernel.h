@@ -35,6 +35,65 @@ struct ColLoaderSel<Cfg, false, VEC> {
     typedef LoaderMN<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC> type;
 };
 
+// Epilogue of a product whose result is a row-major matrix: out = alpha*acc + beta*out with edge
+// predication.  Lane (i, h) owns, for block row bm and accumulator register r, the NB consecutive
+// columns n0 + wn0 + NB*i .. of row m0 + wm0 + MB*(8*(r/4) + 4*h + r%4) + bm.  A slice of a plain
+// split-K launch writes its raw sums to its M x N array in the workspace instead.
+template <class Cfg>
+__device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::MB][Cfg::NB], float *C, int64_t ldc_,
+                                                    int64_t M, int64_t N, float alpha_, float beta_, bool cvec,
+                                                    int64_t m0, int64_t n0, const SplitPlan &split, const WorkItem &w)
+{
+    typedef typename VecOf<Cfg::NB>::type CV;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
+    const int64_t col = n0 + wn0 + Cfg::NB * i;
+    const bool raw_slice = split.plain && w.nslice > 1;  // plain split-K: raw sums to the workspace
+    float *Cz = raw_slice ? split.partials + (int64_t)w.slice * split.slice_stride : C;
+    const int64_t ldc = raw_slice ? N : ldc_;
+    const float alpha = raw_slice ? 1.0f : alpha_, beta = raw_slice ? 0.0f : beta_;
+    const bool full_vec = (raw_slice ? (N % 4 == 0) : cvec) && (col + Cfg::NB <= N);
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+            if (row >= M) continue;
+            float *dst = Cz + row * ldc + col;
+            float out[Cfg::NB];
+#pragma unroll
+            for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] = alpha * acc[bm][bn][r];
+            if (full_vec) {
+                CV o;
+                if constexpr (Cfg::NB == 1) {
+                    o = out[0];
+                    if (beta != 0.0f) o += beta * *dst;
+                    *dst = o;
+                } else {
+                    if (beta != 0.0f) {
+                        const CV old = *reinterpret_cast<const CV *>(dst);
+#pragma unroll
+                        for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] += beta * old[bn];
+                    }
+#pragma unroll
+                    for (int bn = 0; bn < Cfg::NB; ++bn) o[bn] = out[bn];
+                    *reinterpret_cast<CV *>(dst) = o;
+                }
+            } else {
+#pragma unroll
+                for (int bn = 0; bn < Cfg::NB; ++bn) {
+                    if (col + bn < N) {
+                        float o = out[bn];
+                        if (beta != 0.0f) o += beta * dst[bn];
+                        dst[bn] = o;
+                    }
+                }
+            }
+        }
+    }
+}
+
 // A_KCONTIG: A stored M x K (transA == N).  B_KCONTIG: B stored N x K (transB == T).
 // VEC: every 16-byte global load of A and B is aligned and wholly inside the matrix.
 template <class Cfg, bool A_KCONTIG, bool B_KCONTIG, bool VEC>
@@ -75,56 +134,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
     mainloop<Cfg>(rl, cl, T, krem, acc, smem);
     if (!combine_slices<Cfg>(acc, g.split, w)) return;
 
-    // Epilogue.  Lane (i, h) owns, for block row bm and accumulator register r, the NB consecutive
-    // columns n0 + wn0 + NB*i .. of row m0 + wm0 + MB*(8*(r/4) + 4*h + r%4) + bm.
-    typedef typename VecOf<Cfg::NB>::type CV;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i = lane & 31, h = lane >> 5;
-    const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
-    const int64_t col = n0 + wn0 + Cfg::NB * i;
-    const bool raw_slice = g.split.plain && w.nslice > 1;  // plain split-K: raw sums to the workspace
-    float *Cz = raw_slice ? g.split.partials + (int64_t)w.slice * g.split.slice_stride : g.C;
-    const int64_t ldc = raw_slice ? g.N : g.ldc;
-    const float alpha = raw_slice ? 1.0f : g.alpha, beta = raw_slice ? 0.0f : g.beta;
-    const bool full_vec = (raw_slice ? (g.N % 4 == 0) : (g.cvec != 0)) && (col + Cfg::NB <= g.N);
-#pragma unroll
-    for (int bm = 0; bm < Cfg::MB; ++bm) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
-            if (row >= g.M) continue;
-            float *dst = Cz + row * ldc + col;
-            float out[Cfg::NB];
-#pragma unroll
-            for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] = alpha * acc[bm][bn][r];
-            if (full_vec) {
-                CV o;
-                if constexpr (Cfg::NB == 1) {
-                    o = out[0];
-                    if (beta != 0.0f) o += beta * *dst;
-                    *dst = o;
-                } else {
-                    if (beta != 0.0f) {
-                        const CV old = *reinterpret_cast<const CV *>(dst);
-#pragma unroll
-                        for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] += beta * old[bn];
-                    }
-#pragma unroll
-                    for (int bn = 0; bn < Cfg::NB; ++bn) o[bn] = out[bn];
-                    *reinterpret_cast<CV *>(dst) = o;
-                }
-            } else {
-#pragma unroll
-                for (int bn = 0; bn < Cfg::NB; ++bn) {
-                    if (col + bn < g.N) {
-                        float o = out[bn];
-                        if (beta != 0.0f) o += beta * dst[bn];
-                        dst[bn] = o;
-                    }
-                }
-            }
-        }
-    }
+    store_tile_rowmajor<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, g.cvec != 0, m0, n0, g.split, w);
     if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
         g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
         g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();

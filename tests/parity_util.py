@@ -164,3 +164,45 @@ def run_conv_bwd_data_case(dm, torch, N, C, H, W, Kout, R, S, pad, stride, alpha
         assert np.array_equal(got.astype(np.float64), ref), "integer case must be bit-exact"
         return 0.0
     return check_bound(got, ref, mag, max(1, Kout * R * S), "conv bwd-data %s" % ((N, C, H, W, Kout, R, S, pad, stride),))
+
+
+def run_conv_bwd_filter_case(dm, torch, N, C, H, W, Kout, R, S, pad, stride, alpha=1.0, beta=0.0, seed=0, ints=False,
+                             exact=False, lead=0):
+    """dmath_conv2d_bwd_filter against the oracle's adjoint-of-forward definition."""
+    rng = np.random.default_rng(seed)
+    P = (H + 2 * pad[0] - R) // stride[0] + 1
+    Q = (W + 2 * pad[1] - S) // stride[1] + 1
+    if ints:
+        x = rng.integers(-3, 4, size=(N, C, H, W)).astype(np.float32)
+        dy = rng.integers(-3, 4, size=(N, Kout, P, Q)).astype(np.float32)
+        dw0 = rng.integers(-3, 4, size=(Kout, C, R, S)).astype(np.float32)
+    else:
+        x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+        dy = (rng.standard_normal((N, Kout, P, Q)) * 0.1).astype(np.float32)
+        dw0 = rng.standard_normal((Kout, C, R, S)).astype(np.float32)
+    if beta == 0.0:
+        dw0[:] = np.nan
+    tail = 8
+
+    def flat_of(t):
+        f = np.full(lead + t.size + tail, GUARD, dtype=np.float32)
+        f[lead:lead + t.size] = t.reshape(-1)
+        return f
+
+    xf, gf, wf = flat_of(x), flat_of(dy), flat_of(dw0)
+    dx, dg, dwd = (torch.from_numpy(f).cuda() for f in (xf, gf, wf))
+    st = dm.dmath_conv2d_bwd_filter(N, C, H, W, Kout, R, S, pad[0], pad[1], stride[0], stride[1], alpha,
+                                    dx[lead:], dg[lead:], beta, dwd[lead:])
+    assert st == dm.OK, (dm.dmath_status_string(st), dm.dmath_last_error_arg())
+    torch.cuda.synchronize()
+    out = dwd.cpu().numpy()
+    assert np.isnan(out[:lead]).all() and np.isnan(out[lead + dw0.size:]).all(), "wrote outside dw"
+    got = out[lead:lead + dw0.size].reshape(dw0.shape)
+    ref, mag = oracle.conv2d_bwd_filter(x, dy, (Kout, C, R, S), pad=pad, stride=stride, alpha=alpha, beta=beta,
+                                        dw0=dw0 if beta != 0.0 else None)
+    if got.size == 0:
+        return 0.0
+    if exact:
+        assert np.array_equal(got.astype(np.float64), ref), "integer case must be bit-exact"
+        return 0.0
+    return check_bound(got, ref, mag, max(1, N * P * Q), "conv bwd-filter %s" % ((N, C, H, W, Kout, R, S, pad, stride),))

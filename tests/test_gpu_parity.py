@@ -14,7 +14,7 @@ import pytest
 
 import oracle
 from paper_1604_01416_amd import workloads
-from parity_util import check_bound, run_conv_bwd_data_case, run_conv_case, run_gemm_case
+from parity_util import check_bound, run_conv_bwd_data_case, run_conv_bwd_filter_case, run_conv_case, run_gemm_case
 
 pytestmark = pytest.mark.gpu
 
@@ -453,3 +453,73 @@ def test_config5_shape_bwd_data_full_size_sampled(dm, torch):
     ref, mag = oracle.conv2d_bwd_data(dy, wl.w, wl.x.shape, pad=wl.pad, stride=wl.stride, idx=idx)
     r = check_bound(got.reshape(-1)[idx], ref, mag, Kout * 9, "config 5 bwd-data sampled")
     print("config 5 bwd-data max err/bound %.3g" % r)
+
+
+# ------------------------------------------------------------------ convolution, backward-filter
+
+CONV_BWD_FILTER = [
+    dict(N=2, C=3, H=7, W=5, Kout=4, R=3, S=3, pad=(1, 1), stride=(1, 1)),       # P*Q = 35: quads straddle images
+    dict(N=1, C=2, H=9, W=6, Kout=3, R=3, S=2, pad=(0, 0), stride=(2, 2)),
+    dict(N=2, C=5, H=8, W=11, Kout=2, R=5, S=3, pad=(2, 1), stride=(2, 3)),
+    dict(N=3, C=20, H=14, W=14, Kout=32, R=3, S=3, pad=(1, 1), stride=(1, 1)),   # P*Q = 196: vector loads of dy
+    dict(N=5, C=30, H=9, W=10, Kout=300, R=3, S=3, pad=(1, 1), stride=(1, 1)),   # several row and column tiles
+    dict(N=2, C=40, H=6, W=6, Kout=16, R=1, S=1, pad=(1, 1), stride=(1, 1)),     # pad beyond the filter
+    dict(N=4, C=33, H=12, W=12, Kout=64, R=3, S=3, pad=(1, 1), stride=(2, 2)),
+    dict(N=1, C=4, H=5, W=5, Kout=6, R=5, S=5, pad=(0, 0), stride=(1, 1)),       # one output pixel per image
+    dict(N=40, C=8, H=3, W=2, Kout=9, R=2, S=2, pad=(0, 0), stride=(1, 1)),      # images shorter than a K tile
+    dict(N=0, C=4, H=5, W=5, Kout=6, R=3, S=3, pad=(1, 1), stride=(1, 1)),       # empty reduction: dw = beta*dw
+]
+
+
+@pytest.mark.parametrize("shape", CONV_BWD_FILTER)
+def test_conv_bwd_filter_small(dm, torch, shape):
+    run_conv_bwd_filter_case(dm, torch, seed=shape["H"], beta=0.25, **shape)
+    run_conv_bwd_filter_case(dm, torch, seed=shape["W"], alpha=0.5, beta=-1.5, lead=1, **shape)
+    run_conv_bwd_filter_case(dm, torch, seed=shape["C"], ints=True, exact=True, beta=1.0, **shape)
+    if shape["N"]:
+        run_conv_bwd_filter_case(dm, torch, seed=shape["Kout"], **shape)
+
+
+@pytest.mark.parametrize("cfg", range(6))
+@pytest.mark.parametrize("split", [1, 3])
+def test_conv_bwd_filter_every_config(dm, torch, cfg, split):
+    if cfg >= dm.dmath_num_configs():
+        pytest.skip("no such configuration")
+    dm.dmath_set_override(cfg, split)
+    if "_l2" in dm.dmath_config_name(cfg):
+        t = torch.zeros(4096, device="cuda")
+        assert dm.dmath_conv2d_bwd_filter(1, 2, 4, 4, 3, 3, 3, 1, 1, 1, 1, 1.0, t, t, 0.0, t) == dm.ERR_UNSUPPORTED
+        return
+    run_conv_bwd_filter_case(dm, torch, N=3, C=72, H=14, W=14, Kout=40, R=3, S=3, pad=(1, 1), stride=(1, 1), seed=cfg,
+                             ints=True, exact=True)
+    run_conv_bwd_filter_case(dm, torch, N=2, C=60, H=11, W=13, Kout=261, R=3, S=3, pad=(1, 1), stride=(2, 1),
+                             seed=cfg + 5, alpha=2.0, beta=1.0, lead=3)
+
+
+def test_conv_bwd_filter_without_workspace(dm, torch):
+    ws = dm._test_workspace
+    dm.check(dm.dmath_set_workspace(None, 0))
+    try:
+        run_conv_bwd_filter_case(dm, torch, N=3, C=20, H=14, W=14, Kout=32, R=3, S=3, pad=(1, 1), stride=(1, 1), seed=3)
+    finally:
+        dm.check(dm.dmath_set_workspace(ws, ws.numel()))
+
+
+def test_config5_shape_bwd_filter_full_size_sampled(dm, torch):
+    """Filter gradient of the config 5 layer: x 128x256x28x28, dy 128x256x28x28 -> dw 256x256x3x3."""
+    wl = workloads.config5()
+    N, Kout, P, Q = wl.out_shape
+    _, C, H, W = wl.x.shape
+    rng = np.random.default_rng(11)
+    dy = (rng.standard_normal((N, Kout, P, Q)) * 1e-2).astype(np.float32)
+    dx, ddy = torch.from_numpy(wl.x).cuda(), torch.from_numpy(dy).cuda()
+    ddw = torch.full((Kout, C, 3, 3), float("nan"), device="cuda")
+    dm.check(dm.dmath_conv2d_bwd_filter(N, C, H, W, Kout, 3, 3, 1, 1, 1, 1, 1.0, dx, ddy, 0.0, ddw))
+    torch.cuda.synchronize()
+    got = ddw.cpu().numpy()
+    assert np.isfinite(got).all()
+    idx = rng.choice(got.size, size=1500, replace=False)
+    idx = np.concatenate([idx, np.arange(9 * C), got.size - 1 - np.arange(9 * C)])   # first and last filter rows
+    ref, mag = oracle.conv2d_bwd_filter(wl.x, dy, (Kout, C, 3, 3), pad=wl.pad, stride=wl.stride, idx=idx)
+    r = check_bound(got.reshape(-1)[idx], ref, mag, N * P * Q, "config 5 bwd-filter sampled")
+    print("config 5 bwd-filter max err/bound %.3g" % r)
