@@ -10,6 +10,8 @@
 // K is long (100352 at the benchmark layer) and the output small (256 x 2304), so the launch is a plain
 // split-K over many K slices.
 #pragma once
+#include <type_traits>
+
 #include "gemm_kernel.h"
 
 namespace dmath {
@@ -21,7 +23,7 @@ struct ConvFilterGradArgs {
     int N, C, H, W, Kout, R, S, P, Q;
     int pad_h, pad_w, stride_h, stride_w;
     int PQ, RS;
-    int64_t CRS, NPQ;
+    int64_t CRS, NPQ, x_bytes;
     float alpha, beta;
     int tiles_m, tiles_n;
     int cvec;
@@ -213,7 +215,106 @@ struct LoaderXTaps {
     }
 };
 
-template <class Cfg, bool QUAD_IN_IMAGE>
+// The same operand when Q is a multiple of 4 and x is smaller than 2 GiB: the four pixels of a quad
+// then lie in one output row, so a thread keeps ONE running position, the row test is shared by the
+// quad, and the loads are raw buffer loads with 32-bit byte offsets whose out-of-range marker returns
+// zero for the halo without a branch or a select on the data.
+template <int BR, int BK, int NT, int LD>
+struct LoaderXRowQuad {
+    static constexpr int QPR = BK / 4;
+    static constexpr int NQ = (BR * QPR) / NT;
+    static constexpr int NLOAD = NQ, NSTORE = NQ * 4;
+    static_assert((BR * QPR) % NT == 0 && NQ >= 1, "tile must split evenly over the threads");
+    __amdgpu_buffer_rsrc_t rsrc;
+    unsigned pix;          // n*C*H*W + (p*stride_h)*W + q*stride_w of the quad's first pixel (element index)
+    int ihb, iwb;          // p*stride_h, q*stride_w of the first pixel
+    int coff[NQ];          // c*H*W + (r - pad_h)*W + (s - pad_w) for each owned column
+    int rph[NQ], spw[NQ];  // r - pad_h (far negative for a column past C*R*S), s - pad_w
+    int64_t kglob, Ktot;
+    unsigned CHW, PshW;
+    int H, W, Qsw, Psh, sw, sh, shW;
+    floatx4 v[NQ];
+    int col0, kq;
+
+    __device__ __forceinline__ void init(const ConvFilterGradArgs &a, int64_t c0, int64_t kstart, int tid)
+    {
+        col0 = tid / QPR;
+        kq = tid % QPR;
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, (int)a.x_bytes, 0x00020000);
+        H = a.H; W = a.W; sw = a.stride_w; sh = a.stride_h; shW = a.stride_h * a.W;
+        Qsw = a.Q * a.stride_w; Psh = a.P * a.stride_h;
+        CHW = (unsigned)(a.C * a.H * a.W);
+        PshW = (unsigned)(Psh * a.W);
+        Ktot = a.NPQ;
+        kglob = kstart + kq * 4;
+        {
+            const int64_t n = kglob / a.PQ;
+            const int pq = (int)(kglob - n * a.PQ);
+            const int p = pq / a.Q, q = pq - p * a.Q;
+            ihb = p * a.stride_h;
+            iwb = q * a.stride_w;
+            pix = (unsigned)n * CHW + (unsigned)(ihb * a.W + iwb);
+        }
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) {
+            int64_t col = c0 + col0 + it * (NT / QPR);
+            const bool col_ok = col < a.CRS;
+            col = col_ok ? col : a.CRS - 1;
+            const int c = (int)(col / a.RS);
+            const int rs = (int)(col - (int64_t)c * a.RS);
+            const int r = rs / a.S, s = rs - r * a.S;
+            spw[it] = s - a.pad_w;
+            coff[it] = c * a.H * a.W + (r - a.pad_h) * a.W + spw[it];
+            rph[it] = col_ok ? r - a.pad_h : -(1 << 30);
+        }
+    }
+    __device__ __forceinline__ void quad(int it, bool live)
+    {
+        const bool row_ok = live && (unsigned)(ihb + rph[it]) < (unsigned)H;
+        const int iw0 = iwb + spw[it];
+        const unsigned base = (pix + (unsigned)coff[it]) * 4u;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool ok = row_ok && (unsigned)(iw0 + e * sw) < (unsigned)W;
+            const unsigned off = ok ? base + (unsigned)(e * sw) * 4u : 0x80000000u;
+            v[it][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0));
+        }
+    }
+    template <int I>
+    __device__ __forceinline__ void load_piece()
+    {
+        quad(I, true);
+    }
+    __device__ __forceinline__ void advance()
+    {
+        kglob += BK;
+        iwb += BK * sw;
+        pix += (unsigned)(BK * sw);
+        while (iwb >= Qsw) {   // next output row
+            iwb -= Qsw;
+            pix += (unsigned)(shW - Qsw);
+            ihb += sh;
+            if (ihb >= Psh) {  // next image
+                ihb -= Psh;
+                pix += CHW - PshW;
+            }
+        }
+    }
+    // N*P*Q and the quad's first k are multiples of 4: a quad is entirely inside or outside the reduction
+    __device__ __forceinline__ void load_tail(int)
+    {
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) quad(it, kglob < Ktot);
+    }
+    template <int I>
+    __device__ __forceinline__ void store_piece(float *S) const
+    {
+        constexpr int it = I / 4, j = I % 4;
+        S[(kq * 4 + j) * LD + col0 + it * (NT / QPR)] = v[it][j];
+    }
+};
+
+template <class Cfg, bool QUAD_IN_IMAGE, bool QUAD_IN_ROW>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_bwd_filter_tile_kernel(const ConvFilterGradArgs a)
 {
     static_assert(Cfg::LKV == 0, "these loaders write the padded LDS image");
@@ -230,7 +331,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_bwd_filter_tile_
     slice_range(ktiles_total, (int)(a.NPQ - (int64_t)ktiles_total * Cfg::BK), w.slice, w.nslice, kt0, T, krem);
 
     LoaderDyK<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, QUAD_IN_IMAGE> rl;
-    LoaderXTaps<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB> cl;
+    std::conditional_t<QUAD_IN_ROW, LoaderXRowQuad<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB>,
+                       LoaderXTaps<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB>> cl;
     rl.init(a, m0, (int64_t)kt0 * Cfg::BK, threadIdx.x);
     cl.init(a, n0, (int64_t)kt0 * Cfg::BK, threadIdx.x);
 
@@ -248,15 +350,19 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_bwd_filter_tile_
 }
 
 template <class Cfg>
-int launch_conv_bwd_filter_cfg(const ConvFilterGradArgs &a, bool quad_in_image, hipStream_t stream)
+int launch_conv_bwd_filter_cfg(const ConvFilterGradArgs &a, bool quad_in_image, bool quad_in_row, hipStream_t stream)
 {
     const int tiles = a.tiles_m * a.tiles_n;
     const dim3 grid((unsigned)(a.split.dp_tiles + (tiles - a.split.dp_tiles) * a.split.splits)), block(Cfg::NT);
     if constexpr (Cfg::LKV == 0) {
-        if (quad_in_image)
-            hipLaunchKernelGGL((conv_bwd_filter_tile_kernel<Cfg, true>), grid, block, 0, stream, a);
+        if (quad_in_image && quad_in_row)
+            hipLaunchKernelGGL((conv_bwd_filter_tile_kernel<Cfg, true, true>), grid, block, 0, stream, a);
+        else if (quad_in_image)
+            hipLaunchKernelGGL((conv_bwd_filter_tile_kernel<Cfg, true, false>), grid, block, 0, stream, a);
+        else if (quad_in_row)
+            hipLaunchKernelGGL((conv_bwd_filter_tile_kernel<Cfg, false, true>), grid, block, 0, stream, a);
         else
-            hipLaunchKernelGGL((conv_bwd_filter_tile_kernel<Cfg, false>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL((conv_bwd_filter_tile_kernel<Cfg, false, false>), grid, block, 0, stream, a);
         return (int)hipGetLastError();
     } else {
         return (int)hipErrorInvalidValue;  // the rotated-image comparison configuration has no filter-gradient kernel

@@ -123,6 +123,8 @@ __global__ void conv_filter_copy_kernel(const float *w, float *wt, int64_t rows,
     }
 }
 
+constexpr int kMaxSplits = 64;
+
 struct Plan {
     int cfg;
     int dp_tiles;  // tiles computed whole; the remaining tiles - dp_tiles are cut into `splits` slices
@@ -187,8 +189,10 @@ double plan_cost(int c, int64_t tiles, int64_t dp, int s, int64_t K)
 }
 
 // only_cfg >= 0 restricts the search to that configuration; forced_split >= 1 fixes the split factor
-// (then every tile is split); allow_split == false forbids splitting.
-Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split, int only_cfg = -1, int forced_split = -1)
+// (then every tile is split); allow_split == false forbids splitting; plans whose scratch would not
+// fit into avail bytes are not considered.
+Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split, int only_cfg = -1, int forced_split = -1,
+                 size_t avail = ~(size_t)0)
 {
     Plan best = {only_cfg >= 0 ? only_cfg : 0, 0, 1};
     double best_cost = 1e300;
@@ -208,11 +212,23 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split, int only_cfg
             }
             continue;
         }
-        for (int s = 1; s <= (allow_split ? 16 : 1); s *= 2) {
-            if (s > 1 && ktiles / s < 8) break;
+        // Split factors tried: powers of two, and the factors that make the slices of all tiles fill
+        // one to four rounds over the compute units exactly (long reductions into few tiles, as in the
+        // filter gradient of a convolution, want more than 16 slices).
+        int cand[9] = {1, 2, 4, 8, 16, 0, 0, 0, 0};
+        int ncand = allow_split ? 5 : 1;
+        for (int r = 1; allow_split && r <= 4; ++r) {
+            const int64_t f = (int64_t)r * kNumCU / tiles;
+            if (f >= 3 && f <= kMaxSplits && (f & (f - 1)) != 0) cand[ncand++] = (int)f;
+        }
+        for (int ci = 0; ci < ncand; ++ci) {
+            const int s = cand[ci];
+            if (s > 1 && ktiles / s < 8) continue;
             // s == 1: no split.  s > 1: all tiles split, and (if there is a full round) only the tail split.
             const int64_t dps[2] = {s == 1 ? tiles : 0, full};
             for (int v = 0; v < (s > 1 && full > 0 && full < tiles ? 2 : 1); ++v) {
+                const Plan cand_plan = {c, (int)dps[v], s};
+                if (s > 1 && plan_bytes(cand_plan, tiles, M, N) > avail) continue;
                 const double cost = plan_cost(c, tiles, dps[v], s, K);
                 if (cost < best_cost) {
                     best_cost = cost;
@@ -229,7 +245,7 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split, int only_cfg
 Plan resolve_plan(int64_t M, int64_t N, int64_t K, size_t avail, bool measure_only)
 {
     const ThreadState &st = g_state;
-    Plan p = choose_plan(M, N, K, true, st.force_cfg, st.force_split);
+    Plan p = choose_plan(M, N, K, true, st.force_cfg, st.force_split, measure_only ? ~(size_t)0 : avail);
     const CfgDesc &d = desc(p.cfg);
     if (!measure_only && plan_bytes(p, ceil_div(M, d.BM) * ceil_div(N, d.BN), M, N) > avail)
         p = choose_plan(M, N, K, false, st.force_cfg, -1);  // no room: best plan that needs no scratch
@@ -614,8 +630,11 @@ dmath_status dmath_conv2d_bwd_filter(int64_t N, int64_t C, int64_t H, int64_t W,
     a.tiles_n = (int)tiles_n;
     a.cvec = (aligned16(dw) && CRS % 4 == 0) ? 1 : 0;
     if (!prepare_split(plan, tiles_m * tiles_n, Kout, CRS, g_state.ws, stream, a.split)) return fail(DMATH_ERR_LAUNCH, 0);
+    const bool x_small = C * H * W <= (lim / 4 - 1) / N;  // x below 2 GiB: 32-bit byte offsets reach all of it
+    a.x_bytes = x_small ? N * C * H * W * (int64_t)sizeof(float) : 0;
     const bool quad_in_image = PQ % 4 == 0 && aligned16(dy);
-    const int rc = d.conv_bwd_filter(a, quad_in_image, stream);
+    const bool quad_in_row = Q % 4 == 0 && x_small;
+    const int rc = d.conv_bwd_filter(a, quad_in_image, quad_in_row, stream);
     if (rc == (int)hipErrorInvalidValue) return fail(DMATH_ERR_UNSUPPORTED, 0);
     if (rc != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
     if (a.split.plain) {

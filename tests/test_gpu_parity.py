@@ -468,6 +468,10 @@ CONV_BWD_FILTER = [
     dict(N=1, C=4, H=5, W=5, Kout=6, R=5, S=5, pad=(0, 0), stride=(1, 1)),       # one output pixel per image
     dict(N=40, C=8, H=3, W=2, Kout=9, R=2, S=2, pad=(0, 0), stride=(1, 1)),      # images shorter than a K tile
     dict(N=0, C=4, H=5, W=5, Kout=6, R=3, S=3, pad=(1, 1), stride=(1, 1)),       # empty reduction: dw = beta*dw
+    dict(N=3, C=21, H=10, W=12, Kout=35, R=3, S=3, pad=(1, 1), stride=(1, 1)),   # Q = 12: quads stay in a row
+    dict(N=2, C=18, H=9, W=16, Kout=20, R=5, S=3, pad=(2, 1), stride=(1, 2)),    # Q = 8 with a column stride
+    dict(N=7, C=6, H=4, W=4, Kout=10, R=3, S=3, pad=(1, 1), stride=(1, 1)),      # Q = 4: a row per quad
+    dict(N=2, C=10, H=5, W=9, Kout=12, R=2, S=2, pad=(0, 0), stride=(3, 1)),     # Q = 8, P*Q = 16 = one K tile
 ]
 
 
@@ -490,7 +494,7 @@ def test_conv_bwd_filter_every_config(dm, torch, cfg, split):
         t = torch.zeros(4096, device="cuda")
         assert dm.dmath_conv2d_bwd_filter(1, 2, 4, 4, 3, 3, 3, 1, 1, 1, 1, 1.0, t, t, 0.0, t) == dm.ERR_UNSUPPORTED
         return
-    run_conv_bwd_filter_case(dm, torch, N=3, C=72, H=14, W=14, Kout=40, R=3, S=3, pad=(1, 1), stride=(1, 1), seed=cfg,
+    run_conv_bwd_filter_case(dm, torch, N=3, C=72, H=14, W=16, Kout=40, R=3, S=3, pad=(1, 1), stride=(1, 1), seed=cfg,
                              ints=True, exact=True)
     run_conv_bwd_filter_case(dm, torch, N=2, C=60, H=11, W=13, Kout=261, R=3, S=3, pad=(1, 1), stride=(2, 1),
                              seed=cfg + 5, alpha=2.0, beta=1.0, lead=3)
