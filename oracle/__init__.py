@@ -37,6 +37,10 @@ def _load():
         lib.oracle_gemm_points.restype = ctypes.c_int
         lib.oracle_gemm_points.argtypes = [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _dbl, _fp,
                                            _i64, _fp, _i64, _dbl, _fp, _i64, _i64, _ip, _ip, _dp, _dp]
+        lib.oracle_gemm_panels.restype = ctypes.c_int
+        lib.oracle_gemm_panels.argtypes = [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _i64, _dbl,
+                                           ctypes.POINTER(_fp), _i64, ctypes.POINTER(_fp), _i64, _dbl, _fp, _i64,
+                                           _i64, _ip, _ip, _dp, _dp]
         lib.oracle_conv2d_fwd.restype = ctypes.c_int
         lib.oracle_conv2d_fwd.argtypes = [_i64] * 11 + [_dbl, _fp, _fp, _dbl, _fp, _dp, _dp]
         lib.oracle_conv2d_fwd_points.restype = ctypes.c_int
@@ -122,6 +126,42 @@ def gemm_points(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0, ldc, p
                                     ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
     if rc != 0:
         raise RuntimeError("oracle_gemm_points rejected its arguments")
+    return ref, mag
+
+
+def gemm_panels(transA, transB, M, N, K, alpha, A_panels, lda, B_panels, ldb, beta=0.0, C0=None, ldc=None, pi=None,
+                pj=None):
+    """ref, mag of alpha * sum_p op(A_p)*op(B_p) + beta*C0 for lists of equally shaped panels; all M x N
+    elements, or only the positions (pi[t], pj[t])."""
+    ldc = N if ldc is None else ldc
+    assert len(A_panels) == len(B_panels)
+    keep = []
+    for a, b in zip(A_panels, B_panels):
+        a, b, _ = _check_gemm(transA, transB, M, N, K, alpha, a, lda, b, ldb, 0.0, None, ldc)
+        keep.append((a, b))
+    C0 = _f32(C0, "C0")
+    if beta != 0.0:
+        _need(C0, _extent(M, N, ldc), "C0")
+    n = len(keep)
+    fpp = ctypes.POINTER(ctypes.c_float) * max(1, n)
+    Ap = fpp(*[_ptr(a) for a, _ in keep])
+    Bp = fpp(*[_ptr(b) for _, b in keep])
+    if pi is None:
+        shape, npts = (M, N), 0
+        ip = jp = ctypes.cast(None, _ip)
+    else:
+        pi = np.ascontiguousarray(pi, dtype=np.int64)
+        pj = np.ascontiguousarray(pj, dtype=np.int64)
+        assert pi.shape == pj.shape and pi.ndim == 1
+        shape, npts = pi.shape, pi.size
+        ip, jp = pi.ctypes.data_as(_ip), pj.ctypes.data_as(_ip)
+    ref = np.empty(shape, dtype=np.float64)
+    mag = np.empty(shape, dtype=np.float64)
+    rc = _load().oracle_gemm_panels(int(bool(transA)), int(bool(transB)), M, N, K, n, float(alpha), Ap, lda, Bp, ldb,
+                                    float(beta), _ptr(C0), ldc, npts, ip, jp,
+                                    ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
+    if rc != 0:
+        raise RuntimeError("oracle_gemm_panels rejected its arguments")
     return ref, mag
 
 

@@ -163,6 +163,65 @@ int oracle_gemm_points(int transA, int transB, int64_t M, int64_t N, int64_t K,
     return 0;
 }
 
+/*
+ * Accumulating sequence of block products into one C block (section "Matrix
+ * Multiplication": a worker's C block is the sum, over the stages, of the
+ * products of the A and B blocks it holds at each stage; section "Memory
+ * Management" / figure "cyclic_gemm_cache_fwd": with the blocks cached, the
+ * whole sum runs locally):
+ *
+ *     C = alpha * sum_{p < npanels} op(A_p)[M x K] * op(B_p)[K x N] + beta * C0
+ *
+ * A and B are arrays of npanels pointers; every panel has the same K and
+ * leading dimension.  With pi == NULL all M x N elements are produced (ref, mag
+ * dense, row stride N); otherwise only the npts positions (pi[t], pj[t]).
+ * beta is applied once to C0, not once per panel.
+ */
+int oracle_gemm_panels(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t npanels,
+                       double alpha, const float *const *A, int64_t lda,
+                       const float *const *B, int64_t ldb,
+                       double beta, const float *C0, int64_t ldc,
+                       int64_t npts, const int64_t *pi, const int64_t *pj,
+                       double *ref, double *mag)
+{
+    if (M < 0 || N < 0 || K < 0 || npanels < 0 || npts < 0 || !ref) return 1;
+    if (beta != 0.0 && !C0 && M > 0 && N > 0) return 1;
+    const int product = alpha != 0.0 && K > 0 && npanels > 0 && M > 0 && N > 0;
+    if (product) {
+        if (!A || !B) return 1;
+        for (int64_t p = 0; p < npanels; ++p)
+            if (!A[p] || !B[p]) return 1;
+    }
+    const int64_t total = pi ? npts : M * N;
+    if (pi)
+        for (int64_t t = 0; t < npts; ++t)
+            if (pi[t] < 0 || pi[t] >= M || pj[t] < 0 || pj[t] >= N) return 1;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t t = 0; t < total; ++t) {
+        const int64_t i = pi ? pi[t] : t / N, j = pi ? pj[t] : t % N;
+        double s = 0.0, m = 0.0;
+        if (product) {
+            for (int64_t p = 0; p < npanels; ++p)
+                for (int64_t k = 0; k < K; ++k) {
+                    const double a = a_elem(A[p], lda, transA, i, k);
+                    const double b = b_elem(B[p], ldb, transB, k, j);
+                    s += a * b;
+                    m += fabs(a) * fabs(b);
+                }
+        }
+        double r = product ? alpha * s : 0.0;
+        double g = product ? fabs(alpha) * m : 0.0;
+        if (beta != 0.0) {
+            const double c0 = (double)C0[i * ldc + j];
+            r += beta * c0;
+            g += fabs(beta) * fabs(c0);
+        }
+        ref[t] = r;
+        if (mag) mag[t] = g;
+    }
+    return 0;
+}
+
 static inline int64_t conv_out_dim(int64_t in, int64_t pad, int64_t filt, int64_t stride)
 {
     const int64_t span = in + 2 * pad - filt;

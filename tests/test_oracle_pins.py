@@ -248,6 +248,100 @@ def test_gemm_points_on_a_window_with_leading_dimensions():
 
 # ----------------------------------------------------------------------------- convolution
 
+# ----------------------------------------------------------------------------- multi-panel update
+
+def test_gemm_panels_hand_worked_fixture_all_transposes():
+    fx = _read_fixture("gemm_panels_hand_worked.txt")
+    M, N, K, P = (int(fx[k][0]) for k in ("M", "N", "K", "panels"))
+    C0 = np.array(fx["C0"], dtype=np.float32).reshape(M, N)
+    want = np.array(fx["ref"]).reshape(M, N)
+    want_mag = np.array(fx["mag"]).reshape(M, N)
+    for tA, tB in itertools.product((0, 1), (0, 1)):
+        As, Bs = [], []
+        for p in range(P):
+            a, lda = _store(np.array(fx["A%d" % p], dtype=np.float32).reshape(M, K), tA, ld_extra=1)
+            b, ldb = _store(np.array(fx["B%d" % p], dtype=np.float32).reshape(K, N), tB, ld_extra=2)
+            As.append(a)
+            Bs.append(b)
+        ref, mag = oracle.gemm_panels(tA, tB, M, N, K, fx["alpha"][0], As, lda, Bs, ldb, fx["beta"][0], C0, N)
+        assert np.array_equal(ref, want), (tA, tB)
+        assert np.array_equal(mag, want_mag), (tA, tB)
+        pts, _ = oracle.gemm_panels(tA, tB, M, N, K, fx["alpha"][0], As, lda, Bs, ldb, fx["beta"][0], C0, N,
+                                    pi=[1, 0], pj=[0, 1])
+        assert np.array_equal(pts, want[[1, 0], [0, 1]])
+
+
+def test_gemm_panels_closed_forms():
+    # panel p holds A_p = (p+1) everywhere, B_p = 1: every element is K * sum_p (p+1); a dropped or repeated
+    # panel, or a panel used twice, changes the count
+    M, N, K, P = 3, 4, 5, 6
+    As = [np.full((M, K), p + 1, dtype=np.float32) for p in range(P)]
+    Bs = [np.ones((K, N), dtype=np.float32) for _ in range(P)]
+    ref, mag = oracle.gemm_panels(0, 0, M, N, K, 1.0, As, K, Bs, N)
+    assert np.array_equal(ref, np.full((M, N), K * P * (P + 1) / 2))
+    assert np.array_equal(mag, ref)
+    # A_p = e_p e_p^T pattern: panel p contributes only to C[p][p] (pairs A_p with B_p, not B_q)
+    P = 4
+    As, Bs = [], []
+    for p in range(P):
+        a = np.zeros((P, 2), dtype=np.float32)
+        a[p, 1] = 1.0
+        b = np.zeros((2, P), dtype=np.float32)
+        b[1, p] = float(p + 2)
+        As.append(a)
+        Bs.append(b)
+    ref, _ = oracle.gemm_panels(0, 0, P, P, 2, 1.0, As, 2, Bs, P)
+    assert np.array_equal(ref, np.diag(np.arange(P) + 2.0))
+    # no panels, or K == 0: beta * C0 alone; alpha == 0 never reads the panels
+    C0 = np.arange(12, dtype=np.float32).reshape(3, 4)
+    ref, mag = oracle.gemm_panels(0, 0, 3, 4, 5, 2.0, [], 5, [], 4, beta=-1.0, C0=C0)
+    assert np.array_equal(ref, -C0.astype(np.float64)) and np.array_equal(mag, C0.astype(np.float64))
+    nanA = [np.full((3, 5), np.nan, dtype=np.float32)]
+    nanB = [np.full((5, 4), np.nan, dtype=np.float32)]
+    ref, _ = oracle.gemm_panels(0, 0, 3, 4, 5, 0.0, nanA, 5, nanB, 4, beta=1.0, C0=C0)
+    assert np.array_equal(ref, C0.astype(np.float64))
+
+
+@pytest.mark.parametrize("tA,tB", list(itertools.product((0, 1), (0, 1))))
+def test_gemm_panels_matches_numpy_float64_and_brute_force(tA, tB):
+    rng = np.random.default_rng(100 + 2 * tA + tB)
+    M, N, K, P = 6, 5, 7, 3
+    A = [rng.standard_normal((M, K)).astype(np.float32) for _ in range(P)]
+    B = [rng.standard_normal((K, N)).astype(np.float32) for _ in range(P)]
+    C0 = rng.standard_normal((M, N)).astype(np.float32)
+    alpha, beta = -0.75, 1.5
+    stA = [_store(a, tA, ld_extra=3) for a in A]
+    stB = [_store(b, tB, ld_extra=1) for b in B]
+    ref, mag = oracle.gemm_panels(tA, tB, M, N, K, alpha, [s[0] for s in stA], stA[0][1], [s[0] for s in stB],
+                                  stB[0][1], beta, C0, N)
+    want = alpha * sum(a.astype(np.float64) @ b.astype(np.float64) for a, b in zip(A, B)) + beta * C0.astype(np.float64)
+    want_mag = abs(alpha) * sum(np.abs(a).astype(np.float64) @ np.abs(b).astype(np.float64) for a, b in zip(A, B)) \
+        + abs(beta) * np.abs(C0).astype(np.float64)
+    assert np.allclose(ref, want, rtol=0, atol=1e-12)
+    assert np.allclose(mag, want_mag, rtol=0, atol=1e-12)
+    brute = np.zeros((M, N))
+    for i in range(M):
+        for j in range(N):
+            acc = 0.0
+            for p in range(P):
+                for k in range(K):
+                    acc += float(A[p][i, k]) * float(B[p][k, j])
+            brute[i, j] = alpha * acc + beta * float(C0[i, j])
+    assert np.allclose(ref, brute, rtol=0, atol=1e-12)
+
+
+def test_gemm_panels_integer_exact_equals_product_of_concatenations():
+    # [A_0 A_1 ...] * [B_0; B_1; ...] in exact integer arithmetic (int64 numpy, no floating point)
+    rng = np.random.default_rng(5)
+    M, N, K, P = 9, 11, 16, 5
+    A = [rng.integers(-4, 5, size=(M, K)) for _ in range(P)]
+    B = [rng.integers(-4, 5, size=(K, N)) for _ in range(P)]
+    want = np.concatenate(A, axis=1) @ np.concatenate(B, axis=0)
+    ref, _ = oracle.gemm_panels(0, 0, M, N, K, 1.0, [a.astype(np.float32) for a in A], K,
+                                [b.astype(np.float32) for b in B], N)
+    assert np.array_equal(ref, want.astype(np.float64))
+
+
 def _conv_brute(x, w, pad, stride):
     """Second, independent statement of the definition: python loops in float64."""
     N, C, H, W = x.shape
