@@ -40,7 +40,7 @@ MEASURED_HBM_TRAFFIC_BYTES = {
     "conv": int(((94305.9 + 1812.2) * 2.0 + 119682.4 + 2304.0) * 1024),         # profiles/conv3x3_n128_c256_k256_28x28_kernels.md
 }
 
-WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv", "conv_bwd_data", "conv_bwd_filter")
+WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv", "conv_bwd_data", "conv_bwd_filter", "summa_fused")
 
 
 def _device_arrays(torch, arrays):
@@ -188,11 +188,17 @@ def main():
         wl_name = conv.name + ("_bwd_data" if bwd else "_bwd_filter" if bwd_filter else "")
     else:
         wl = {"gemm4096": workloads.config2, "gemm256": workloads.config1, "summa": workloads.config3,
-              "fc": workloads.config4}[args.workload]()
+              "summa_fused": workloads.config3, "fc": workloads.config4}[args.workload]()
         dev = _device_arrays(torch, wl.arrays)
         calls = [(c, dev[c.A], dev[c.B], dev[c.C]) for c in wl.calls]
+        fused = args.workload == "summa_fused"   # the same update sequence as one multi-panel call
 
         def step():
+            if fused:
+                c = wl.calls[0]
+                dm.check(dm.dmath_gemm_panels(c.transA, c.transB, c.M, c.N, c.K, c.alpha, [x[1] for x in calls], c.lda,
+                                              [x[2] for x in calls], c.ldb, c.beta, calls[0][3], c.ldc))
+                return
             for c, a, b, cc in calls:
                 dm.check(dm.dmath_gemm(c.transA, c.transB, c.M, c.N, c.K, c.alpha, a, c.lda, b, c.ldb, c.beta, cc,
                                        c.ldc))
@@ -201,6 +207,11 @@ def main():
         alg_bytes = sum(c.algorithmic_bytes for c in wl.calls)
         launches = len(wl.calls)
         wl_name = wl.name
+        if fused:   # all panels read once, C read and written once
+            c = wl.calls[0]
+            alg_bytes = 4 * (len(wl.calls) * (c.M * c.K + c.K * c.N) + 2 * c.M * c.N)
+            launches = 1
+            wl_name = wl.name + "_fused"
 
     # Clock the tile kernel really runs at (GEMM workloads): the in-kernel stamps stay on during the
     # timed steps (two scalar stores per launch by 8 workgroups); the last launch's values are read.

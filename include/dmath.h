@@ -80,6 +80,32 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB,
                         void *stream);
 
 /*
+ * Accumulating sequence of block multiplies in one call (section "Matrix Multiplication": a worker's
+ * block of C is the sum, over the stages, of products of the A and B blocks it holds at that stage;
+ * section "Memory Management" and figure "cyclic_gemm_cache_fwd": with the blocks cached on the
+ * device the whole sum runs without communication):
+ *
+ *     C[M x N] = alpha * sum_{p < npanels} op(A[p])[M x K] * op(B[p])[K x N] + beta * C
+ *
+ * A and B are HOST arrays of npanels DEVICE pointers, read before the call returns; every panel has
+ * the same shape, orientation and leading dimension (conventions of dmath_gemm).  beta applies once.
+ * When K is a multiple of 16 and the operands qualify for dmath_gemm's fast path (16-byte aligned
+ * panels, leading dimensions multiples of 4) the whole sum is one kernel launch per 32 panels that
+ * keeps the C tile in registers, so C is read and written once per launch instead of once per panel;
+ * otherwise the call is the same as npanels accumulating dmath_gemm calls.  Rounding differs from
+ * that sequence only in summation order.
+ *
+ * npanels == 0, K == 0 or alpha == 0: C = beta*C and no panel pointer is read.
+ * Errors as for dmath_gemm; NULL_PTR also for a NULL entry of A (argument 8) or B (argument 10).
+ */
+dmath_status dmath_gemm_panels(dmath_op transA, dmath_op transB,
+                               int64_t M, int64_t N, int64_t K, int64_t npanels,
+                               float alpha, const float *const *A, int64_t lda,
+                               const float *const *B, int64_t ldb,
+                               float beta, float *C, int64_t ldc,
+                               void *stream);
+
+/*
  * Forward convolution (the DNN primitive of the abstract and of section
  * "Introduction"; the paper delegates its formula to the DNN library it calls,
  * so the usual DNN definition is used: cross-correlation, zero padding):

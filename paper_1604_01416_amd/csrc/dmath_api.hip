@@ -438,6 +438,108 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     return DMATH_OK;
 }
 
+dmath_status dmath_gemm_panels(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, int64_t npanels,
+                               float alpha, const float *const *A, int64_t lda, const float *const *B, int64_t ldb,
+                               float beta, float *C, int64_t ldc, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (transA != DMATH_OP_N && transA != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (transB != DMATH_OP_N && transB != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 2);
+    if (M < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
+    if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
+    if (K < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
+    if (npanels < 0) return fail(DMATH_ERR_INVALID_ARG, 6);
+    const bool a_k = (transA == DMATH_OP_N), b_k = (transB == DMATH_OP_T);
+    const int64_t a_cols = a_k ? K : M, b_cols = b_k ? K : N;
+    if (lda < (a_cols > 1 ? a_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 9);
+    if (ldb < (b_cols > 1 ? b_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 11);
+    if (ldc < (N > 1 ? N : 1)) return fail(DMATH_ERR_INVALID_ARG, 14);
+    if (M == 0 || N == 0) return DMATH_OK;
+    if (C == nullptr) return fail(DMATH_ERR_NULL_PTR, 13);
+    const bool no_product = (K == 0 || npanels == 0 || alpha == 0.0f);
+    bool vec = lda % 4 == 0 && ldb % 4 == 0 && (a_k || M % 4 == 0) && (b_k || N % 4 == 0);
+    if (!no_product) {
+        if (A == nullptr) return fail(DMATH_ERR_NULL_PTR, 8);
+        if (B == nullptr) return fail(DMATH_ERR_NULL_PTR, 10);
+        for (int64_t p = 0; p < npanels; ++p) {
+            if (A[p] == nullptr) return fail(DMATH_ERR_NULL_PTR, 8);
+            if (B[p] == nullptr) return fail(DMATH_ERR_NULL_PTR, 10);
+            vec = vec && aligned16(A[p]) && aligned16(B[p]);
+        }
+    }
+    if (M > (int64_t)1 << 40 || N > (int64_t)1 << 40 || K > (int64_t)1 << 33 || npanels > (int64_t)1 << 24)
+        return fail(DMATH_ERR_UNSUPPORTED, 3);
+
+    if (no_product) {
+        if (beta == 1.0f) return DMATH_OK;
+        const int64_t total = M * N;
+        const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
+        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, C, ldc, M, N, beta);
+        return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
+    }
+    if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, lda > ((int64_t)1 << 22) ? 9 : 11);
+
+    // Every tile configuration uses the same K tile; a panel with a ragged last K tile, or operands
+    // that rule out 16-byte loads, are run as one accumulating dmath_gemm per panel instead.
+    const int bk = desc(0).BK;
+    if (K % bk != 0 || !vec || npanels == 1) {
+        for (int64_t p = 0; p < npanels; ++p) {
+            const dmath_status st = dmath_gemm(transA, transB, M, N, K, alpha, A[p], lda, B[p], ldb, p == 0 ? beta : 1.0f,
+                                               C, ldc, stream_);
+            if (st != DMATH_OK) return st;
+        }
+        return DMATH_OK;
+    }
+
+    for (int64_t p0 = 0; p0 < npanels; p0 += kMaxPanels) {
+        const int np = (int)(npanels - p0 < kMaxPanels ? npanels - p0 : kMaxPanels);
+        const int64_t Ktot = K * np;
+        if (Ktot > (int64_t)1 << 33) return fail(DMATH_ERR_UNSUPPORTED, 5);
+        const Plan plan = resolve_plan(M, N, Ktot, g_state.ws ? g_state.ws_bytes : 0, false);
+        const CfgDesc &d = desc(plan.cfg);
+        const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
+        if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
+        GemmPanelArgs a;
+        GemmArgs &g = a.g;
+        g.A = nullptr;
+        g.B = nullptr;
+        g.C = C;
+        g.lda = lda;
+        g.ldb = ldb;
+        g.ldc = ldc;
+        g.M = M;
+        g.N = N;
+        g.K = Ktot;
+        g.alpha = alpha;
+        g.beta = p0 == 0 ? beta : 1.0f;
+        g.tiles_m = (int)tiles_m;
+        g.tiles_n = (int)tiles_n;
+        g.clock_probe = g_state.clock_probe;
+        g.cvec = (aligned16(C) && ldc % 4 == 0) ? 1 : 0;
+        a.npanels = np;
+        a.tiles_per_panel = (int)(K / d.BK);
+        for (int p = 0; p < kMaxPanels; ++p) {
+            a.A[p] = p < np ? A[p0 + p] : nullptr;
+            a.B[p] = p < np ? B[p0 + p] : nullptr;
+        }
+        if (!prepare_split(plan, tiles_m * tiles_n, M, N, g_state.ws, stream, g.split)) return fail(DMATH_ERR_LAUNCH, 0);
+        if (d.gemm_panels(a, a_k, b_k, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+        if (g.split.plain) {
+            const bool v4 = (N % 4 == 0) && g.cvec;
+            const int64_t items = v4 ? M * (N / 4) : M * N;
+            const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
+            if (v4)
+                hipLaunchKernelGGL(splitk_reduce_kernel_v4, dim3(blocks), dim3(256), 0, stream,
+                                   static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, g.beta);
+            else
+                hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
+                                   static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, g.beta);
+            if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+        }
+    }
+    return DMATH_OK;
+}
+
 // Shared body of the convolution entry points.  The kernel computes  out_mat[rows x cols] =
 // filt_mat[rows x KK] * unfolded(in)[KK x cols]  where, forward: rows = Kout, cols = N*P*Q pixels of y,
 // KK = C*R*S, in = x; backward-data: rows = C, cols = N*H*W pixels of dx, KK = Kout*R*S, in = dy.

@@ -174,6 +174,8 @@ struct LoaderK {
             v[u][it][3] = f[3];
         }
     }
+    // byte distance of k elements along K from a tile origin
+    static __device__ __forceinline__ int64_t k_bytes(int64_t k, int64_t) { return k * 4; }
     __device__ __forceinline__ void advance() { tile += BK * 4; }
     template <int I>
     __device__ __forceinline__ void store_piece(float *S) const
@@ -234,6 +236,8 @@ struct LoaderK0 {
             v[I][3] = f[3];
         }
     }
+    // byte distance of k elements along K from a tile origin
+    static __device__ __forceinline__ int64_t k_bytes(int64_t k, int64_t) { return k * 4; }
     __device__ __forceinline__ void advance() { tile += BK * 4; }
     template <int I>
     __device__ __forceinline__ void store_piece(float *S) const
@@ -311,6 +315,7 @@ struct LoaderMN {
             for (int j = 0; j < 4; ++j) v[I][j] = *reinterpret_cast<const float *>(q + c[j]);
         }
     }
+    static __device__ __forceinline__ int64_t k_bytes(int64_t k, int64_t ld) { return k * ld * 4; }
     __device__ __forceinline__ void advance() { tile += tstride; }
     template <int I>
     __device__ __forceinline__ void store_piece(float *S) const

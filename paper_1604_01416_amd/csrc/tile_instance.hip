@@ -23,6 +23,7 @@ const CfgDesc &cfg_desc<DMATH_CFG_INDEX>()
         ThisCfg::BM, ThisCfg::BN, ThisCfg::BK, ThisCfg::NT, ThisCfg::LDS_BYTES,
         &launch_gemm_cfg<ThisCfg>,
         &launch_conv_cfg<ThisCfg>,
+        &launch_gemm_panels_cfg<ThisCfg>,
         &launch_conv_bwd_filter_cfg<ThisCfg>,
     };
     return d;

@@ -15,7 +15,7 @@ OK, ERR_INVALID_ARG, ERR_NULL_PTR, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_WORKSPACE = 
 OP_N, OP_T = 0, 1
 
 EXPORTS = (
-    "dmath_gemm", "dmath_conv2d_fwd", "dmath_conv2d_bwd_data", "dmath_conv2d_bwd_filter", "dmath_gemm_workspace_bytes", "dmath_set_workspace",
+    "dmath_gemm", "dmath_conv2d_fwd", "dmath_conv2d_bwd_data", "dmath_conv2d_bwd_filter", "dmath_gemm_panels", "dmath_gemm_workspace_bytes", "dmath_set_workspace",
     "dmath_set_override", "dmath_set_clock_probe", "dmath_gemm_plan", "dmath_num_configs", "dmath_config_name", "dmath_last_error_arg",
     "dmath_status_string", "dmath_version",
 )
@@ -34,6 +34,9 @@ _lib.dmath_conv2d_fwd.restype = _int
 _lib.dmath_conv2d_fwd.argtypes = [_i64] * 11 + [_f32, _vp, _vp, _f32, _vp, _vp]
 _lib.dmath_conv2d_bwd_data.restype = _int
 _lib.dmath_conv2d_bwd_data.argtypes = [_i64] * 11 + [_f32, _vp, _vp, _f32, _vp, _vp]
+_lib.dmath_gemm_panels.restype = _int
+_lib.dmath_gemm_panels.argtypes = [_int, _int, _i64, _i64, _i64, _i64, _f32, ctypes.POINTER(_vp), _i64,
+                                   ctypes.POINTER(_vp), _i64, _f32, _vp, _i64, _vp]
 _lib.dmath_conv2d_bwd_filter.restype = _int
 _lib.dmath_conv2d_bwd_filter.argtypes = [_i64] * 11 + [_f32, _vp, _vp, _f32, _vp, _vp]
 _lib.dmath_gemm_workspace_bytes.restype = ctypes.c_size_t
@@ -87,6 +90,21 @@ def dmath_conv2d_bwd_data(N, C, H, W, Kout, R, S, pad_h, pad_w, stride_h, stride
                           stream=None):
     return _lib.dmath_conv2d_bwd_data(N, C, H, W, Kout, R, S, pad_h, pad_w, stride_h, stride_w, alpha, _addr(dy),
                                       _addr(w), beta, _addr(dx), _stream(stream))
+
+
+def dmath_gemm_panels(transA, transB, M, N, K, alpha, A_panels, lda, B_panels, ldb, beta, C, ldc, stream=None):
+    """A_panels, B_panels: equally long sequences of device tensors / addresses (or None for a NULL table)."""
+    def table(panels):
+        if panels is None:
+            return None, 0
+        arr = (_vp * max(1, len(panels)))(*[_addr(p) for p in panels])
+        return arr, len(panels)
+    ta, na = table(A_panels)
+    tb, nb = table(B_panels)
+    if A_panels is not None and B_panels is not None and na != nb:
+        raise ValueError("A_panels and B_panels differ in length")
+    return _lib.dmath_gemm_panels(transA, transB, M, N, K, max(na, nb), alpha, ta, lda, tb, ldb, beta, _addr(C), ldc,
+                                  _stream(stream))
 
 
 def dmath_conv2d_bwd_filter(N, C, H, W, Kout, R, S, pad_h, pad_w, stride_h, stride_w, alpha, x, dy, beta, dw,

@@ -83,6 +83,47 @@ def run_gemm_case(dm, torch, tA, tB, M, N, K, alpha=1.0, beta=0.0, ld_extra=(0, 
     return check_bound(got[:, :N], ref, mag, max(K, 1), "gemm t%d%d %dx%dx%d" % (tA, tB, M, N, K))
 
 
+def run_gemm_panels_case(dm, torch, tA, tB, M, N, K, P, alpha=1.0, beta=0.0, ld_extra=(0, 0, 0), lead=(0, 0, 0),
+                         seed=0, ints=False, exact=False):
+    """One dmath_gemm_panels call over P panels against the oracle's sum of products."""
+    rng = np.random.default_rng(seed)
+    if ints:
+        As = [rng.integers(-3, 4, size=(M, K)).astype(np.float32) for _ in range(P)]
+        Bs = [rng.integers(-3, 4, size=(K, N)).astype(np.float32) for _ in range(P)]
+        C0 = rng.integers(-4, 5, size=(M, N)).astype(np.float32)
+    else:
+        As = [rng.uniform(-1, 1, (M, K)).astype(np.float32) for _ in range(P)]
+        Bs = [rng.uniform(-1, 1, (K, N)).astype(np.float32) for _ in range(P)]
+        C0 = rng.standard_normal((M, N)).astype(np.float32)
+    if beta == 0.0:
+        C0[:] = np.nan
+    sa = [stored(a, tA, ld_extra[0], lead[0]) for a in As]
+    sb = [stored(b, tB, ld_extra[1], lead[1]) for b in Bs]
+    c_flat, c_off, ldc = stored(C0, 0, ld_extra[2], lead[2])
+    lda = sa[0][2] if P else max(1, (M if tA else K) + ld_extra[0])
+    ldb = sb[0][2] if P else max(1, (K if tB else N) + ld_extra[1])
+    dA = [torch.from_numpy(f).cuda() for f, _, _ in sa]
+    dB = [torch.from_numpy(f).cuda() for f, _, _ in sb]
+    dC = torch.from_numpy(c_flat).cuda()
+    st = dm.dmath_gemm_panels(tA, tB, M, N, K, alpha, [t[lead[0]:] for t in dA], lda, [t[lead[1]:] for t in dB], ldb,
+                              beta, dC[c_off:], ldc)
+    assert st == dm.OK, (dm.dmath_status_string(st), dm.dmath_last_error_arg())
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    ref, mag = oracle.gemm_panels(tA, tB, M, N, K, alpha, [f[o:] for f, o, _ in sa], lda, [f[o:] for f, o, _ in sb],
+                                  ldb, beta, c_flat[c_off:] if beta != 0.0 else None, ldc)
+    got = out[c_off:c_off + M * ldc].reshape(M, ldc) if M > 0 else np.zeros((0, ldc), np.float32)
+    if M > 0:
+        assert np.isnan(got[:, N:]).all(), "row padding of C was written"
+    assert np.isnan(out[:c_off]).all() and np.isnan(out[c_off + M * ldc:]).all(), "wrote outside C"
+    if M == 0 or N == 0:
+        return 0.0
+    if exact:
+        assert np.array_equal(got[:, :N].astype(np.float64), ref), "integer case must be bit-exact"
+        return 0.0
+    return check_bound(got[:, :N], ref, mag, max(K * P, 1), "gemm_panels t%d%d %dx%dx%d x%d" % (tA, tB, M, N, K, P))
+
+
 def run_conv_case(dm, torch, N, C, H, W, Kout, R, S, pad, stride, alpha=1.0, beta=0.0, seed=0, ints=False,
                   exact=False, lead=0):
     rng = np.random.default_rng(seed)

@@ -14,7 +14,7 @@ import pytest
 
 import oracle
 from paper_1604_01416_amd import workloads
-from parity_util import check_bound, run_conv_bwd_data_case, run_conv_bwd_filter_case, run_conv_case, run_gemm_case
+from parity_util import check_bound, run_conv_bwd_data_case, run_conv_bwd_filter_case, run_conv_case, run_gemm_case, run_gemm_panels_case
 
 pytestmark = pytest.mark.gpu
 
@@ -527,3 +527,81 @@ def test_config5_shape_bwd_filter_full_size_sampled(dm, torch):
     ref, mag = oracle.conv2d_bwd_filter(wl.x, dy, (Kout, C, 3, 3), pad=wl.pad, stride=wl.stride, idx=idx)
     r = check_bound(got.reshape(-1)[idx], ref, mag, N * P * Q, "config 5 bwd-filter sampled")
     print("config 5 bwd-filter max err/bound %.3g" % r)
+
+
+# ------------------------------------------------------------------ multi-panel update
+
+@pytest.mark.parametrize("tA,tB", TRANS)
+def test_gemm_panels_fused_small(dm, torch, tA, tB):
+    # K multiple of 16, aligned: the single-launch path; 300 x 260 spans several tiles with ragged edges
+    run_gemm_panels_case(dm, torch, tA, tB, 300, 260, 48, 5, seed=1 + 2 * tA + tB, ld_extra=(4, 8, 4))
+    run_gemm_panels_case(dm, torch, tA, tB, 300, 260, 16, 7, alpha=-0.5, beta=2.0, seed=7, ld_extra=(0, 0, 4))
+    run_gemm_panels_case(dm, torch, tA, tB, 128, 512, 64, 3, ints=True, exact=True, beta=1.0, seed=3)
+    run_gemm_panels_case(dm, torch, tA, tB, 64, 64, 32, 40, seed=9)                     # more than one chunk of panels
+
+
+@pytest.mark.parametrize("tA,tB", TRANS)
+def test_gemm_panels_falls_back_to_a_gemm_per_panel(dm, torch, tA, tB):
+    run_gemm_panels_case(dm, torch, tA, tB, 45, 37, 19, 4, beta=0.5, seed=2, ld_extra=(1, 3, 2))   # ragged K, odd ld
+    run_gemm_panels_case(dm, torch, tA, tB, 64, 64, 32, 3, seed=4, lead=(1, 0, 0))                # unaligned panels
+    run_gemm_panels_case(dm, torch, tA, tB, 33, 20, 16, 1, seed=5)
+
+
+def test_gemm_panels_quick_returns(dm, torch):
+    run_gemm_panels_case(dm, torch, 0, 0, 40, 24, 16, 0, beta=0.5, seed=1)      # no panels: C = beta*C
+    run_gemm_panels_case(dm, torch, 0, 0, 40, 24, 0, 3, beta=-1.0, seed=2)      # K == 0
+    run_gemm_panels_case(dm, torch, 0, 0, 40, 24, 16, 3, alpha=0.0, beta=2.0, seed=3)
+    run_gemm_panels_case(dm, torch, 0, 0, 0, 24, 16, 3, seed=4)
+    c = torch.zeros(16, device="cuda")
+    assert dm.dmath_gemm_panels(0, 0, 4, 4, 16, 1.0, [c, None], 16, [c, c], 4, 0.0, c, 4) == dm.ERR_NULL_PTR
+    assert dm.dmath_last_error_arg() == 8
+    assert dm.dmath_gemm_panels(0, 0, 4, 4, 16, 1.0, [c], 15, [c], 4, 0.0, c, 4) == dm.ERR_INVALID_ARG
+    assert dm.dmath_last_error_arg() == 9
+
+
+@pytest.mark.parametrize("cfg", range(6))
+@pytest.mark.parametrize("split", [1, 3])
+def test_gemm_panels_every_config(dm, torch, cfg, split):
+    if cfg >= dm.dmath_num_configs():
+        pytest.skip("no such configuration")
+    dm.dmath_set_override(cfg, split)
+    run_gemm_panels_case(dm, torch, 0, 0, 270, 520, 32, 6, ints=True, exact=True, beta=1.0, seed=cfg)
+    run_gemm_panels_case(dm, torch, 1, 1, 516, 130, 16, 9, alpha=1.5, beta=-1.0, seed=cfg + 10, ld_extra=(4, 4, 0))
+
+
+def test_gemm_panels_tail_split_and_order_invariance(dm, torch):
+    # 17 x 16 = 272 tiles of the 256 x 256 configuration: one full round plus a split tail
+    dm.dmath_set_override(2, -1)
+    M, N, K, P = 17 * 256, 16 * 256, 64, 4
+    rng = np.random.default_rng(12)
+    As = [torch.from_numpy(rng.integers(-2, 3, size=(M, K)).astype(np.float32)).cuda() for _ in range(P)]
+    Bs = [torch.from_numpy(rng.integers(-2, 3, size=(K, N)).astype(np.float32)).cuda() for _ in range(P)]
+    C1 = torch.zeros((M, N), device="cuda")
+    C2 = torch.zeros((M, N), device="cuda")
+    dm.check(dm.dmath_gemm_panels(0, 0, M, N, K, 1.0, As, K, Bs, N, 0.0, C1, N))
+    for p in range(P):
+        dm.check(dm.dmath_gemm(0, 0, M, N, K, 1.0, As[p], K, Bs[p], N, 1.0 if p else 0.0, C2, N))
+    torch.cuda.synchronize()
+    assert torch.equal(C1, C2)          # integer data: exact in any order
+    want = sum(a.double() @ b.double() for a, b in zip(As, Bs))
+    assert torch.equal(C1.double(), want)
+
+
+def test_config3_panels_full_size_sampled(dm, torch):
+    """Config 3 as one fused call: C(8192 x 8192) += sum of 16 products of 8192 x 512 by 512 x 8192 panels."""
+    wl = workloads.config3()
+    dev = {k: torch.from_numpy(v).cuda() for k, v in wl.arrays.items()}
+    c = wl.calls[0]
+    As = [dev[x.A] for x in wl.calls]
+    Bs = [dev[x.B] for x in wl.calls]
+    dm.check(dm.dmath_gemm_panels(0, 0, c.M, c.N, c.K, 1.0, As, c.lda, Bs, c.ldb, 1.0, dev["C"], c.ldc))
+    torch.cuda.synchronize()
+    got = dev["C"].cpu().numpy()
+    rng = np.random.default_rng(3)
+    pi = rng.integers(0, c.M, size=4000)
+    pj = rng.integers(0, c.N, size=4000)
+    pi[:4], pj[:4] = [0, 0, c.M - 1, c.M - 1], [0, c.N - 1, 0, c.N - 1]
+    ref, mag = oracle.gemm_panels(0, 0, c.M, c.N, c.K, 1.0, [wl.arrays[x.A] for x in wl.calls], c.lda,
+                                  [wl.arrays[x.B] for x in wl.calls], c.ldb, 1.0, wl.arrays["C"], c.ldc, pi=pi, pj=pj)
+    r = check_bound(got[pi, pj], ref, mag, c.K * len(wl.calls), "config 3 fused, sampled")
+    print("config 3 fused max err/bound %.3g" % r)
