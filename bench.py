@@ -43,7 +43,8 @@ MEASURED_HBM_TRAFFIC_BYTES = {
     "conv_bwd_filter": int(((156909.8 + 32272.7) * 2.0 + 64512.0 + 2304.0) * 1024),  # profiles/conv3x3_..._bwd_filter_kernels.md
 }
 
-WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv", "conv_bwd_data", "conv_bwd_filter", "summa_fused")
+WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv", "conv_bwd_data", "conv_bwd_filter", "summa_fused",
+             "fc_nn", "fc_nt", "fc_tn")
 
 
 def _device_arrays(torch, arrays):
@@ -191,7 +192,11 @@ def main():
         wl_name = conv.name + ("_bwd_data" if bwd else "_bwd_filter" if bwd_filter else "")
     else:
         wl = {"gemm4096": workloads.config2, "gemm256": workloads.config1, "summa": workloads.config3,
-              "summa_fused": workloads.config3, "fc": workloads.config4}[args.workload]()
+              "summa_fused": workloads.config3, "fc": workloads.config4, "fc_nn": workloads.config4,
+              "fc_nt": workloads.config4, "fc_tn": workloads.config4}[args.workload]()
+        if args.workload in ("fc_nn", "fc_nt", "fc_tn"):   # one of the three products of the layer alone
+            wl.calls = [wl.calls[("fc_nn", "fc_nt", "fc_tn").index(args.workload)]]
+            wl.name += "_" + args.workload[3:]
         dev = _device_arrays(torch, wl.arrays)
         calls = [(c, dev[c.A], dev[c.B], dev[c.C]) for c in wl.calls]
         fused = args.workload == "summa_fused"   # the same update sequence as one multi-panel call
