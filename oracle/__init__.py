@@ -23,6 +23,7 @@ _dbl = ctypes.c_double
 _fp = ctypes.POINTER(ctypes.c_float)
 _dp = ctypes.POINTER(ctypes.c_double)
 _ip = ctypes.POINTER(ctypes.c_int64)
+_hp = ctypes.POINTER(ctypes.c_uint16)
 
 
 def _load():
@@ -41,6 +42,11 @@ def _load():
         lib.oracle_gemm_panels.argtypes = [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _i64, _dbl,
                                            ctypes.POINTER(_fp), _i64, ctypes.POINTER(_fp), _i64, _dbl, _fp, _i64,
                                            _i64, _ip, _ip, _dp, _dp]
+        lib.oracle_half_to_double.restype = _dbl
+        lib.oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.oracle_hgemm.restype = ctypes.c_int
+        lib.oracle_hgemm.argtypes = [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _dbl, _hp, _i64, _hp, _i64, _dbl,
+                                     _hp, _i64, _i64, _ip, _ip, _dp, _dp]
         lib.oracle_conv2d_fwd.restype = ctypes.c_int
         lib.oracle_conv2d_fwd.argtypes = [_i64] * 11 + [_dbl, _fp, _fp, _dbl, _fp, _dp, _dp]
         lib.oracle_conv2d_fwd_points.restype = ctypes.c_int
@@ -162,6 +168,58 @@ def gemm_panels(transA, transB, M, N, K, alpha, A_panels, lda, B_panels, ldb, be
                                     ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
     if rc != 0:
         raise RuntimeError("oracle_gemm_panels rejected its arguments")
+    return ref, mag
+
+
+def half_to_double(bits):
+    """Value of one IEEE binary16 bit pattern (0..65535) as the oracle decodes it."""
+    return _load().oracle_half_to_double(int(bits))
+
+
+def _f16(a, name):
+    if a is None:
+        return None
+    a = np.asarray(a)
+    if a.dtype != np.float16 or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError("%s must be a C-contiguous float16 array" % name)
+    return a
+
+
+def _hptr(a):
+    return ctypes.cast(None, _hp) if a is None else a.ctypes.data_as(_hp)
+
+
+def half_bound(K, mag, ref):
+    """Acceptance bound for a result stored as IEEE half: the FP32-accumulation bound plus one rounding of the
+    result to half (half an ulp: 2^-11 relative for normal numbers, 2^-25 absolute in the subnormal range)."""
+    return bound(K, mag) + np.maximum(np.abs(ref) * 2.0 ** -11, 2.0 ** -25)
+
+
+def hgemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta=0.0, C0=None, ldc=None, pi=None, pj=None):
+    """ref, mag (float64) of alpha*op(A)*op(B) + beta*C0 for float16 arrays; all elements or the points (pi, pj)."""
+    ldc = N if ldc is None else ldc
+    A, B, C0 = _f16(A, "A"), _f16(B, "B"), _f16(C0, "C0")
+    if alpha != 0.0:
+        _need(A, _extent(K, M, lda) if transA else _extent(M, K, lda), "A")
+        _need(B, _extent(N, K, ldb) if transB else _extent(K, N, ldb), "B")
+    if beta != 0.0:
+        _need(C0, _extent(M, N, ldc), "C0")
+    if pi is None:
+        shape, npts = (M, N), 0
+        ip = jp = ctypes.cast(None, _ip)
+    else:
+        pi = np.ascontiguousarray(pi, dtype=np.int64)
+        pj = np.ascontiguousarray(pj, dtype=np.int64)
+        assert pi.shape == pj.shape and pi.ndim == 1
+        shape, npts = pi.shape, pi.size
+        ip, jp = pi.ctypes.data_as(_ip), pj.ctypes.data_as(_ip)
+    ref = np.empty(shape, dtype=np.float64)
+    mag = np.empty(shape, dtype=np.float64)
+    rc = _load().oracle_hgemm(int(bool(transA)), int(bool(transB)), M, N, K, float(alpha), _hptr(A), lda, _hptr(B),
+                              ldb, float(beta), _hptr(C0), ldc, npts, ip, jp,
+                              ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
+    if rc != 0:
+        raise RuntimeError("oracle_hgemm rejected its arguments")
     return ref, mag
 
 

@@ -22,7 +22,10 @@
  *     1, one group, no bias, NCHW input, KCRS filters, NKPQ output:
  *         ref[n][j][p][q] = alpha * sum_{c,r,s} x[n][c][p*sh+r-ph][q*sw+s-pw] * w[j][c][r][s]
  *                           + beta * y0[n][j][p][q]
- *   - For both, the companion magnitude sum (same expression with every factor
+ *   - The two gradients of that convolution (its adjoints), the accumulating
+ *     sum of several block products, and the GEMM on IEEE half-precision storage
+ *     with wide accumulation (section "Precisions"): see the comment at each.
+ *   - For all of them, the companion magnitude sum (same expression with every factor
  *     replaced by its absolute value) that the acceptance bound
  *         |gpu - ref| <= 4*K*2^-24 * mag + 1e-6
  *     needs.
@@ -213,6 +216,85 @@ int oracle_gemm_panels(int transA, int transB, int64_t M, int64_t N, int64_t K, 
         double g = product ? fabs(alpha) * m : 0.0;
         if (beta != 0.0) {
             const double c0 = (double)C0[i * ldc + j];
+            r += beta * c0;
+            g += fabs(beta) * fabs(c0);
+        }
+        ref[t] = r;
+        if (mag) mag[t] = g;
+    }
+    return 0;
+}
+
+/*
+ * IEEE 754 binary16 -> double, from the format: 1 sign bit, 5 exponent bits
+ * (bias 15), 10 fraction bits; exponent 0 is zero / subnormal (fraction * 2^-24),
+ * exponent 31 is infinity (fraction 0) or NaN.
+ */
+double oracle_half_to_double(uint16_t h)
+{
+    const int sign = (h >> 15) & 1, e = (h >> 10) & 31, f = h & 1023;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -24);
+    else if (e == 31)
+        v = f ? NAN : INFINITY;
+    else
+        v = ldexp((double)(1024 + f), e - 25);
+    return sign ? -v : v;
+}
+
+static inline double ha_elem(const uint16_t *A, int64_t lda, int tA, int64_t i, int64_t k)
+{
+    return oracle_half_to_double(tA ? A[k * lda + i] : A[i * lda + k]);
+}
+
+static inline double hb_elem(const uint16_t *B, int64_t ldb, int tB, int64_t k, int64_t j)
+{
+    return oracle_half_to_double(tB ? B[j * ldb + k] : B[k * ldb + j]);
+}
+
+/*
+ * GEMM on half-precision storage (section "Precisions": matrices stored as IEEE
+ * half floats, the arithmetic done in a wider precision):
+ *
+ *     ref[i][j] = alpha * sum_k opA(i,k) * opB(k,j) + beta * C0[i][j]
+ *
+ * with A, B, C0 arrays of binary16 bit patterns, each converted exactly to FP64;
+ * ref and mag are the unrounded FP64 values (the rounding of the stored result
+ * to half is the caller's tolerance, not applied here).  pi == NULL: all M x N
+ * elements (row stride N); else only the npts positions (pi[t], pj[t]).
+ */
+int oracle_hgemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                 double alpha, const uint16_t *A, int64_t lda,
+                 const uint16_t *B, int64_t ldb,
+                 double beta, const uint16_t *C0, int64_t ldc,
+                 int64_t npts, const int64_t *pi, const int64_t *pj,
+                 double *ref, double *mag)
+{
+    if (M < 0 || N < 0 || K < 0 || npts < 0 || !ref) return 1;
+    if (beta != 0.0 && !C0 && M > 0 && N > 0) return 1;
+    const int product = alpha != 0.0 && K > 0 && M > 0 && N > 0;
+    if (product && (!A || !B)) return 1;
+    const int64_t total = pi ? npts : M * N;
+    if (pi)
+        for (int64_t t = 0; t < npts; ++t)
+            if (pi[t] < 0 || pi[t] >= M || pj[t] < 0 || pj[t] >= N) return 1;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t t = 0; t < total; ++t) {
+        const int64_t i = pi ? pi[t] : t / N, j = pi ? pj[t] : t % N;
+        double s = 0.0, m = 0.0;
+        if (product) {
+            for (int64_t k = 0; k < K; ++k) {
+                const double a = ha_elem(A, lda, transA, i, k);
+                const double b = hb_elem(B, ldb, transB, k, j);
+                s += a * b;
+                m += fabs(a) * fabs(b);
+            }
+        }
+        double r = product ? alpha * s : 0.0;
+        double g = product ? fabs(alpha) * m : 0.0;
+        if (beta != 0.0) {
+            const double c0 = oracle_half_to_double(C0[i * ldc + j]);
             r += beta * c0;
             g += fabs(beta) * fabs(c0);
         }

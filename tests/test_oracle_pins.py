@@ -342,6 +342,103 @@ def test_gemm_panels_integer_exact_equals_product_of_concatenations():
     assert np.array_equal(ref, want.astype(np.float64))
 
 
+# ----------------------------------------------------------------------------- half-precision storage
+
+def _half(bits):
+    return np.array(bits, dtype=np.uint16).view(np.float16)
+
+
+def test_half_decoder_agrees_with_numpy_on_every_bit_pattern():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    want = bits.view(np.float16).astype(np.float64)          # numpy's own conversion, not the oracle's
+    got = np.array([oracle.half_to_double(int(b)) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))     # -0.0 keeps its sign
+    # a few values fixed by the format itself
+    assert oracle.half_to_double(0x3C00) == 1.0 and oracle.half_to_double(0xC000) == -2.0
+    assert oracle.half_to_double(0x0001) == 2.0 ** -24 and oracle.half_to_double(0x0400) == 2.0 ** -14
+    assert oracle.half_to_double(0x7BFF) == 65504.0 and oracle.half_to_double(0x7C00) == np.inf
+
+
+def test_hgemm_hand_worked_fixture_all_transposes():
+    raw = {}
+    with open(os.path.join(GOLDEN, "hgemm_hand_worked.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                key, *vals = line.split()
+                raw[key] = vals
+    M, N, K = int(raw["M"][0]), int(raw["N"][0]), int(raw["K"][0])
+    A = _half([int(v, 16) for v in raw["A"]]).reshape(M, K)
+    B = _half([int(v, 16) for v in raw["B"]]).reshape(K, N)
+    C0 = _half([int(v, 16) for v in raw["C0"]]).reshape(M, N)
+    want = np.array([float(v) for v in raw["ref"]]).reshape(M, N)
+    want_mag = np.array([float(v) for v in raw["mag"]]).reshape(M, N)
+    alpha, beta = float(raw["alpha"][0]), float(raw["beta"][0])
+    for tA, tB in itertools.product((0, 1), (0, 1)):
+        a = np.ascontiguousarray(A.T if tA else A)
+        b = np.ascontiguousarray(B.T if tB else B)
+        ref, mag = oracle.hgemm(tA, tB, M, N, K, alpha, a, a.shape[1], b, b.shape[1], beta, C0, N)
+        assert np.array_equal(ref, want), (tA, tB, ref)
+        assert np.array_equal(mag, want_mag), (tA, tB, mag)
+        pts, _ = oracle.hgemm(tA, tB, M, N, K, alpha, a, a.shape[1], b, b.shape[1], beta, C0, N, pi=[1, 0], pj=[1, 0])
+        assert np.array_equal(pts, want[[1, 0], [1, 0]])
+
+
+@pytest.mark.parametrize("tA,tB", list(itertools.product((0, 1), (0, 1))))
+def test_hgemm_matches_numpy_float64_of_the_same_halves(tA, tB):
+    rng = np.random.default_rng(40 + 2 * tA + tB)
+    M, N, K = 7, 9, 33
+    A = rng.standard_normal((M, K)).astype(np.float16)
+    B = rng.standard_normal((K, N)).astype(np.float16)
+    C0 = rng.standard_normal((M, N)).astype(np.float16)
+    lda, ldb, ldc = (M if tA else K) + 3, (K if tB else N) + 1, N + 2
+
+    def store(m, ld):
+        buf = np.full((m.shape[0], ld), np.nan, dtype=np.float16)
+        buf[:, :m.shape[1]] = m
+        return buf
+
+    a, b, c = store(A.T if tA else A, lda), store(B.T if tB else B, ldb), store(C0, ldc)
+    ref, mag = oracle.hgemm(tA, tB, M, N, K, -1.5, a, lda, b, ldb, 0.25, c, ldc)
+    want = -1.5 * (A.astype(np.float64) @ B.astype(np.float64)) + 0.25 * C0.astype(np.float64)
+    want_mag = 1.5 * (np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64)) + 0.25 * np.abs(C0).astype(np.float64)
+    assert np.allclose(ref, want, rtol=0, atol=1e-12)
+    assert np.allclose(mag, want_mag, rtol=0, atol=1e-12)
+    # the same numbers through the FP32 oracle (halves are exactly representable as floats)
+    a32, b32, c32 = (np.nan_to_num(x.astype(np.float32)) for x in (a, b, c))
+    ref32, _ = oracle.gemm(tA, tB, M, N, K, -1.5, a32, lda, b32, ldb, 0.25, c32, ldc)
+    assert np.array_equal(ref, ref32)
+
+
+def test_hgemm_integer_exact_and_conventions():
+    rng = np.random.default_rng(8)
+    M, N, K = 12, 10, 64
+    A = rng.integers(-4, 5, size=(M, K))
+    B = rng.integers(-4, 5, size=(K, N))
+    ref, _ = oracle.hgemm(0, 0, M, N, K, 1.0, A.astype(np.float16), K, B.astype(np.float16), N)
+    assert np.array_equal(ref, (A @ B).astype(np.float64))
+    # beta == 0 never reads C0 (NaN there), alpha == 0 never reads A, B
+    nanC = np.full((M, N), np.nan, dtype=np.float16)
+    ref, _ = oracle.hgemm(0, 0, M, N, K, 1.0, A.astype(np.float16), K, B.astype(np.float16), N, 0.0, nanC, N)
+    assert np.array_equal(ref, (A @ B).astype(np.float64))
+    C0 = rng.integers(-4, 5, size=(M, N)).astype(np.float16)
+    nanA = np.full((M, K), np.nan, dtype=np.float16)
+    ref, _ = oracle.hgemm(0, 0, M, N, K, 0.0, nanA, K, nanA.reshape(K, M)[:, :N].copy(), N, 2.0, C0, N)
+    assert np.array_equal(ref, 2.0 * C0.astype(np.float64))
+
+
+def test_half_bound_formula():
+    ref = np.array([0.0, 1.0, -2048.0, 1e-6])
+    mag = np.array([0.0, 1.0, 4096.0, 1e-6])
+    got = oracle.half_bound(100, mag, ref)
+    base = 4.0 * 100 * 2.0 ** -24 * mag + 1e-6
+    want = base + np.array([2.0 ** -25, 2.0 ** -11, 1.0, 2.0 ** -25])
+    assert np.allclose(got, want, rtol=1e-15, atol=0)
+
+
 def _conv_brute(x, w, pad, stride):
     """Second, independent statement of the definition: python loops in float64."""
     N, C, H, W = x.shape
