@@ -44,7 +44,7 @@ MEASURED_HBM_TRAFFIC_BYTES = {
 }
 
 WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv", "conv_bwd_data", "conv_bwd_filter", "summa_fused",
-             "fc_nn", "fc_nt", "fc_tn")
+             "fc_nn", "fc_nt", "fc_tn", "hgemm4096", "fc_half")
 
 
 def _device_arrays(torch, arrays):
@@ -193,7 +193,12 @@ def main():
     else:
         wl = {"gemm4096": workloads.config2, "gemm256": workloads.config1, "summa": workloads.config3,
               "summa_fused": workloads.config3, "fc": workloads.config4, "fc_nn": workloads.config4,
-              "fc_nt": workloads.config4, "fc_tn": workloads.config4}[args.workload]()
+              "fc_nt": workloads.config4, "fc_tn": workloads.config4, "hgemm4096": workloads.config2,
+              "fc_half": workloads.config4}[args.workload]()
+        half = args.workload in ("hgemm4096", "fc_half")   # the same operands rounded to half-precision storage
+        if half:
+            wl.arrays = {k: v.astype(np.float16) for k, v in wl.arrays.items()}
+            wl.name += "_half_storage"
         if args.workload in ("fc_nn", "fc_nt", "fc_tn"):   # one of the three products of the layer alone
             wl.calls = [wl.calls[("fc_nn", "fc_nt", "fc_tn").index(args.workload)]]
             wl.name += "_" + args.workload[3:]
@@ -207,12 +212,12 @@ def main():
                 dm.check(dm.dmath_gemm_panels(c.transA, c.transB, c.M, c.N, c.K, c.alpha, [x[1] for x in calls], c.lda,
                                               [x[2] for x in calls], c.ldb, c.beta, calls[0][3], c.ldc))
                 return
+            gemm = dm.dmath_hgemm if half else dm.dmath_gemm
             for c, a, b, cc in calls:
-                dm.check(dm.dmath_gemm(c.transA, c.transB, c.M, c.N, c.K, c.alpha, a, c.lda, b, c.ldb, c.beta, cc,
-                                       c.ldc))
+                dm.check(gemm(c.transA, c.transB, c.M, c.N, c.K, c.alpha, a, c.lda, b, c.ldb, c.beta, cc, c.ldc))
 
         flop = wl.flop
-        alg_bytes = sum(c.algorithmic_bytes for c in wl.calls)
+        alg_bytes = sum(c.algorithmic_bytes for c in wl.calls) // (2 if half else 1)
         launches = len(wl.calls)
         wl_name = wl.name
         if fused:   # all panels read once, C read and written once
@@ -240,7 +245,9 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        if conv is not None and args.workload != "conv":
+        if args.workload in ("hgemm4096", "fc_half"):
+            cpu_baseline = None   # the FP32 workloads of the same shapes carry the oracle timing
+        elif conv is not None and args.workload != "conv":
             cpu_baseline = None   # the forward workload carries the oracle timing of this layer
         elif conv is not None:
             cpu_baseline = _cpu_baseline_conv(oracle, conv)

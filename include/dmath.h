@@ -80,6 +80,26 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB,
                         void *stream);
 
 /*
+ * The same multiply for matrices kept in half-precision storage (section "Precisions": IEEE 16-bit
+ * half floats halve the bytes stored and moved, while the arithmetic stays single precision):
+ *
+ *     C = half( alpha * op(A) * op(B) + beta * float(C) )
+ *
+ * A, B and C hold IEEE 754 binary16 bit patterns (uint16_t); every element is converted exactly to
+ * FP32, products and sums are FP32 (MFMA) exactly as in dmath_gemm, and the result is rounded to half
+ * once (to nearest even) when it is stored.  alpha and beta are FP32.  Leading dimensions count
+ * elements.  The fast path needs 8-byte aligned pointers and leading dimensions that are multiples of
+ * 4; anything 2-byte aligned works.  Conventions, errors and split-K workspace as for dmath_gemm (the
+ * split-K slices are FP32); UNSUPPORTED if the rotated-image comparison configuration is forced.
+ */
+dmath_status dmath_hgemm(dmath_op transA, dmath_op transB,
+                         int64_t M, int64_t N, int64_t K,
+                         float alpha, const uint16_t *A, int64_t lda,
+                         const uint16_t *B, int64_t ldb,
+                         float beta, uint16_t *C, int64_t ldc,
+                         void *stream);
+
+/*
  * Accumulating sequence of block multiplies in one call (section "Matrix Multiplication": a worker's
  * block of C is the sum, over the stages, of products of the A and B blocks it holds at that stage;
  * section "Memory Management" and figure "cyclic_gemm_cache_fwd": with the blocks cached on the

@@ -24,6 +24,7 @@ struct CfgDesc {
     int BM, BN, BK, NT, lds_bytes;
     int (*gemm)(const GemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);
     int (*conv)(const ConvArgs &, bool vec, int loader_kind, hipStream_t);
+    int (*hgemm)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);  // fails on the rotated-image entry
     int (*gemm_panels)(const GemmPanelArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);
     int (*conv_bwd_filter)(const ConvFilterGradArgs &, bool quad_in_image, bool quad_in_row, hipStream_t);  // fails on the rotated-image entry
 };

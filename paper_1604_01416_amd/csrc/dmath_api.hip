@@ -57,8 +57,20 @@ __global__ void scale_kernel(float *C, int64_t ldc, int64_t M, int64_t N, float 
     }
 }
 
-// C = alpha * (slice 0 + slice 1 + ... in that order) + beta * C.  Slices are dense M x N.
-__global__ void splitk_reduce_kernel(const float *ws, int splits, int64_t slice_stride, float *C, int64_t ldc,
+__global__ void scale_kernel(_Float16 *C, int64_t ldc, int64_t M, int64_t N, float beta)
+{
+    const int64_t total = M * N;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = e / N, col = e - row * N;
+        _Float16 *dst = C + row * ldc + col;
+        *dst = (beta == 0.0f) ? (_Float16)0.0f : (_Float16)(beta * (float)*dst);
+    }
+}
+
+// C = alpha * (slice 0 + slice 1 + ... in that order) + beta * C.  Slices are dense M x N FP32; C is
+// FP32 or half-precision storage (rounded once, at the store).
+template <class T>
+__global__ void splitk_reduce_kernel(const float *ws, int splits, int64_t slice_stride, T *C, int64_t ldc,
                                      int64_t M, int64_t N, float alpha, float beta)
 {
     const int64_t total = M * N;
@@ -66,27 +78,34 @@ __global__ void splitk_reduce_kernel(const float *ws, int splits, int64_t slice_
         const int64_t row = e / N, col = e - row * N;
         float s = ws[e];
         for (int z = 1; z < splits; ++z) s += ws[e + z * slice_stride];
-        float *dst = C + row * ldc + col;
+        T *dst = C + row * ldc + col;
         float o = alpha * s;
-        if (beta != 0.0f) o += beta * *dst;
-        *dst = o;
+        if (beta != 0.0f) o += beta * (float)*dst;
+        *dst = (T)o;
     }
 }
 
-// Vectorised form for N % 4 == 0, 16-byte aligned C rows.
-__global__ void splitk_reduce_kernel_v4(const float *ws, int splits, int64_t slice_stride, float *C, int64_t ldc,
+// Vectorised form for N % 4 == 0 and C rows that allow aligned 4-element accesses.
+template <class T>
+__global__ void splitk_reduce_kernel_v4(const float *ws, int splits, int64_t slice_stride, T *C, int64_t ldc,
                                         int64_t M, int64_t N, float alpha, float beta)
 {
+    typedef typename Quad<T>::type QT;
     const int64_t nq = N / 4, total = M * nq;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
         const int64_t row = e / nq, col = (e - row * nq) * 4;
         const float *src = ws + row * N + col;
         floatx4 s = *reinterpret_cast<const floatx4 *>(src);
         for (int z = 1; z < splits; ++z) s += *reinterpret_cast<const floatx4 *>(src + z * slice_stride);
-        float *dst = C + row * ldc + col;
+        T *dst = C + row * ldc + col;
         floatx4 o = alpha * s;
-        if (beta != 0.0f) o += beta * *reinterpret_cast<const floatx4 *>(dst);
-        *reinterpret_cast<floatx4 *>(dst) = o;
+        if (beta != 0.0f) o += beta * Quad<T>::widen(*reinterpret_cast<const QT *>(dst));
+        QT q;
+        q[0] = (T)o[0];
+        q[1] = (T)o[1];
+        q[2] = (T)o[2];
+        q[3] = (T)o[3];
+        *reinterpret_cast<QT *>(dst) = q;
     }
 }
 
@@ -288,6 +307,96 @@ bool prepare_split(const Plan &p, int64_t tiles, int64_t M, int64_t N, void *ws,
 
 using namespace dmath;
 
+// Body of dmath_gemm (T = float) and dmath_hgemm (T = _Float16: same kernels, operands widened on the
+// way into LDS, result rounded once on the way out).
+template <class T>
+dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, float alpha, const T *A,
+                        int64_t lda, const T *B, int64_t ldb, float beta, T *C, int64_t ldc, void *stream_)
+{
+    constexpr bool kHalf = !std::is_same<T, float>::value;
+    constexpr uintptr_t kQuadAlign = 4 * sizeof(T) - 1;  // alignment of a 4-element vector access
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (transA != DMATH_OP_N && transA != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (transB != DMATH_OP_N && transB != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 2);
+    if (M < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
+    if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
+    if (K < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
+    const bool a_k = (transA == DMATH_OP_N);  // A contiguous along k
+    const bool b_k = (transB == DMATH_OP_T);  // B contiguous along k
+    const int64_t a_cols = a_k ? K : M, b_cols = b_k ? K : N;
+    if (lda < (a_cols > 1 ? a_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 8);
+    if (ldb < (b_cols > 1 ? b_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 10);
+    if (ldc < (N > 1 ? N : 1)) return fail(DMATH_ERR_INVALID_ARG, 13);
+    if (M == 0 || N == 0) return DMATH_OK;
+    if (C == nullptr) return fail(DMATH_ERR_NULL_PTR, 12);
+    const bool no_product = (K == 0 || alpha == 0.0f);
+    if (!no_product) {
+        if (A == nullptr) return fail(DMATH_ERR_NULL_PTR, 7);
+        if (B == nullptr) return fail(DMATH_ERR_NULL_PTR, 9);
+    }
+    // tile counts and in-kernel K tile counters are 32-bit
+    if (M > (int64_t)1 << 40 || N > (int64_t)1 << 40 || K > (int64_t)1 << 33) return fail(DMATH_ERR_UNSUPPORTED, 3);
+
+    if (no_product) {
+        if (beta == 1.0f) return DMATH_OK;
+        const int64_t total = M * N;
+        const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
+        hipLaunchKernelGGL((void (*)(T *, int64_t, int64_t, int64_t, float))scale_kernel, dim3(blocks), dim3(256), 0,
+                           stream, C, ldc, M, N, beta);
+        return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
+    }
+
+    const Plan plan = resolve_plan(M, N, K, g_state.ws ? g_state.ws_bytes : 0, false);
+    const CfgDesc &d = desc(plan.cfg);
+    const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
+    if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
+    if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, lda > ((int64_t)1 << 22) ? 8 : 10);
+
+    // 16-byte loads need aligned bases and rows; along the operand's own index also a whole number of quads.
+    auto quad_aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & kQuadAlign) == 0; };
+    bool vec = quad_aligned(A) && quad_aligned(B) && lda % 4 == 0 && ldb % 4 == 0;
+    if (!a_k && M % 4 != 0) vec = false;
+    if (!b_k && N % 4 != 0) vec = false;
+
+    GemmArgsT<T> g;
+    g.A = A;
+    g.B = B;
+    g.C = C;
+    g.lda = lda;
+    g.ldb = ldb;
+    g.ldc = ldc;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.alpha = alpha;
+    g.beta = beta;
+    g.tiles_m = (int)tiles_m;
+    g.tiles_n = (int)tiles_n;
+    g.clock_probe = g_state.clock_probe;
+    g.cvec = (quad_aligned(C) && ldc % 4 == 0) ? 1 : 0;
+    if (!prepare_split(plan, tiles_m * tiles_n, M, N, g_state.ws, stream, g.split)) return fail(DMATH_ERR_LAUNCH, 0);
+    int rc;
+    if constexpr (kHalf)
+        rc = d.hgemm(g, a_k, b_k, vec, stream);
+    else
+        rc = d.gemm(g, a_k, b_k, vec, stream);
+    if (rc == (int)hipErrorInvalidValue) return fail(DMATH_ERR_UNSUPPORTED, 0);
+    if (rc != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    if (g.split.plain) {
+        const bool v4 = (N % 4 == 0) && g.cvec;
+        const int64_t items = v4 ? M * (N / 4) : M * N;
+        const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
+        if (v4)
+            hipLaunchKernelGGL(splitk_reduce_kernel_v4<T>, dim3(blocks), dim3(256), 0, stream,
+                               static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
+        else
+            hipLaunchKernelGGL(splitk_reduce_kernel<T>, dim3(blocks), dim3(256), 0, stream,
+                               static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
+        if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    }
+    return DMATH_OK;
+}
+
 extern "C" {
 
 const char *dmath_version(void) { return "dmath-mi355x 0.1 (gfx950, fp32 mfma)"; }
@@ -364,78 +473,16 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
                         const float *A, int64_t lda, const float *B, int64_t ldb, float beta, float *C,
                         int64_t ldc, void *stream_)
 {
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
-    if (transA != DMATH_OP_N && transA != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 1);
-    if (transB != DMATH_OP_N && transB != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 2);
-    if (M < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
-    if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
-    if (K < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
-    const bool a_k = (transA == DMATH_OP_N);  // A contiguous along k
-    const bool b_k = (transB == DMATH_OP_T);  // B contiguous along k
-    const int64_t a_cols = a_k ? K : M, b_cols = b_k ? K : N;
-    if (lda < (a_cols > 1 ? a_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 8);
-    if (ldb < (b_cols > 1 ? b_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 10);
-    if (ldc < (N > 1 ? N : 1)) return fail(DMATH_ERR_INVALID_ARG, 13);
-    if (M == 0 || N == 0) return DMATH_OK;
-    if (C == nullptr) return fail(DMATH_ERR_NULL_PTR, 12);
-    const bool no_product = (K == 0 || alpha == 0.0f);
-    if (!no_product) {
-        if (A == nullptr) return fail(DMATH_ERR_NULL_PTR, 7);
-        if (B == nullptr) return fail(DMATH_ERR_NULL_PTR, 9);
-    }
-    // tile counts and in-kernel K tile counters are 32-bit
-    if (M > (int64_t)1 << 40 || N > (int64_t)1 << 40 || K > (int64_t)1 << 33) return fail(DMATH_ERR_UNSUPPORTED, 3);
+    return gemm_entry<float>(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream_);
+}
 
-    if (no_product) {
-        if (beta == 1.0f) return DMATH_OK;
-        const int64_t total = M * N;
-        const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
-        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, C, ldc, M, N, beta);
-        return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
-    }
-
-    const Plan plan = resolve_plan(M, N, K, g_state.ws ? g_state.ws_bytes : 0, false);
-    const CfgDesc &d = desc(plan.cfg);
-    const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
-    if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
-    if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, lda > ((int64_t)1 << 22) ? 8 : 10);
-
-    // 16-byte loads need aligned bases and rows; along the operand's own index also a whole number of quads.
-    bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
-    if (!a_k && M % 4 != 0) vec = false;
-    if (!b_k && N % 4 != 0) vec = false;
-
-    GemmArgs g;
-    g.A = A;
-    g.B = B;
-    g.C = C;
-    g.lda = lda;
-    g.ldb = ldb;
-    g.ldc = ldc;
-    g.M = M;
-    g.N = N;
-    g.K = K;
-    g.alpha = alpha;
-    g.beta = beta;
-    g.tiles_m = (int)tiles_m;
-    g.tiles_n = (int)tiles_n;
-    g.clock_probe = g_state.clock_probe;
-    g.cvec = (aligned16(C) && ldc % 4 == 0) ? 1 : 0;
-    if (!prepare_split(plan, tiles_m * tiles_n, M, N, g_state.ws, stream, g.split)) return fail(DMATH_ERR_LAUNCH, 0);
-    if (d.gemm(g, a_k, b_k, vec, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
-    if (g.split.plain) {
-        const bool v4 = (N % 4 == 0) && aligned16(C) && ldc % 4 == 0;
-        const int64_t items = v4 ? M * (N / 4) : M * N;
-        const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
-        if (v4)
-            hipLaunchKernelGGL(splitk_reduce_kernel_v4, dim3(blocks), dim3(256), 0, stream,
-                               static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
-        else
-            hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
-                               static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
-        if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
-    }
-    return DMATH_OK;
+dmath_status dmath_hgemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, float alpha,
+                         const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, float beta, uint16_t *C,
+                         int64_t ldc, void *stream_)
+{
+    return gemm_entry<_Float16>(transA, transB, M, N, K, alpha, reinterpret_cast<const _Float16 *>(A), lda,
+                                reinterpret_cast<const _Float16 *>(B), ldb, beta, reinterpret_cast<_Float16 *>(C), ldc,
+                                stream_);
 }
 
 dmath_status dmath_gemm_panels(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, int64_t npanels,
@@ -474,7 +521,7 @@ dmath_status dmath_gemm_panels(dmath_op transA, dmath_op transB, int64_t M, int6
         if (beta == 1.0f) return DMATH_OK;
         const int64_t total = M * N;
         const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
-        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, C, ldc, M, N, beta);
+        hipLaunchKernelGGL((void (*)(float *, int64_t, int64_t, int64_t, float))scale_kernel, dim3(blocks), dim3(256), 0, stream, C, ldc, M, N, beta);
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
     if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, lda > ((int64_t)1 << 22) ? 9 : 11);
@@ -529,10 +576,10 @@ dmath_status dmath_gemm_panels(dmath_op transA, dmath_op transB, int64_t M, int6
             const int64_t items = v4 ? M * (N / 4) : M * N;
             const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
             if (v4)
-                hipLaunchKernelGGL(splitk_reduce_kernel_v4, dim3(blocks), dim3(256), 0, stream,
+                hipLaunchKernelGGL(splitk_reduce_kernel_v4<float>, dim3(blocks), dim3(256), 0, stream,
                                    static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, g.beta);
             else
-                hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
+                hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, stream,
                                    static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, g.beta);
             if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
         }
@@ -587,7 +634,7 @@ static dmath_status run_conv(bool bwd_data, int64_t N, int64_t C, int64_t H, int
         if (beta == 1.0f) return DMATH_OK;
         const int64_t total = cols * rows;
         const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
-        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, out, total, (int64_t)1, total, beta);
+        hipLaunchKernelGGL((void (*)(float *, int64_t, int64_t, int64_t, float))scale_kernel, dim3(blocks), dim3(256), 0, stream, out, total, (int64_t)1, total, beta);
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
 
@@ -706,7 +753,7 @@ dmath_status dmath_conv2d_bwd_filter(int64_t N, int64_t C, int64_t H, int64_t W,
         if (beta == 1.0f) return DMATH_OK;
         const int64_t total = Kout * CRS;
         const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
-        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, stream, dw, total, (int64_t)1, total, beta);
+        hipLaunchKernelGGL((void (*)(float *, int64_t, int64_t, int64_t, float))scale_kernel, dim3(blocks), dim3(256), 0, stream, dw, total, (int64_t)1, total, beta);
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
 
@@ -744,10 +791,10 @@ dmath_status dmath_conv2d_bwd_filter(int64_t N, int64_t C, int64_t H, int64_t W,
         const int64_t items = v4 ? Kout * (CRS / 4) : Kout * CRS;
         const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
         if (v4)
-            hipLaunchKernelGGL(splitk_reduce_kernel_v4, dim3(blocks), dim3(256), 0, stream,
+            hipLaunchKernelGGL(splitk_reduce_kernel_v4<float>, dim3(blocks), dim3(256), 0, stream,
                                static_cast<const float *>(g_state.ws), plan.splits, Kout * CRS, dw, CRS, Kout, CRS, alpha, beta);
         else
-            hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream,
+            hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, stream,
                                static_cast<const float *>(g_state.ws), plan.splits, Kout * CRS, dw, CRS, Kout, CRS, alpha, beta);
         if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
     }

@@ -1,14 +1,19 @@
 // GEMM kernel: C = alpha * op(A) * op(B) + beta * C on one BM x BN tile per workgroup, and its
 // host-side launcher template.  Included by one translation unit per tile configuration.
 #pragma once
+#include <type_traits>
+
 #include "tile_core.h"
 
 namespace dmath {
 
-struct GemmArgs {
-    const float *A;
-    const float *B;
-    float *C;
+// T: stored element type of A, B and C (float, or _Float16 for half-precision storage; the arithmetic
+// is FP32 either way).
+template <class T>
+struct GemmArgsT {
+    const T *A;
+    const T *B;
+    T *C;
     int64_t lda, ldb, ldc;
     int64_t M, N, K;
     float alpha, beta;
@@ -17,22 +22,24 @@ struct GemmArgs {
     SplitPlan split;
     unsigned long long *clock_probe;  // optional: 4 stamps from each of workgroups 0..7 (see dmath_set_clock_probe)
 };
+typedef GemmArgsT<float> GemmArgs;
+typedef GemmArgsT<_Float16> HGemmArgs;
 
-template <class Cfg, bool ROWS_K, bool VEC>
+template <class Cfg, bool ROWS_K, bool VEC, class T = float>
 struct RowLoaderSel {
-    typedef typename LoaderKSel<Cfg::LKV, Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC>::type type;
+    typedef typename LoaderKSel<Cfg::LKV, Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC, T>::type type;
 };
-template <class Cfg, bool VEC>
-struct RowLoaderSel<Cfg, false, VEC> {
-    typedef LoaderMN<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC> type;
+template <class Cfg, bool VEC, class T>
+struct RowLoaderSel<Cfg, false, VEC, T> {
+    typedef LoaderMN<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC, T> type;
 };
-template <class Cfg, bool COLS_K, bool VEC>
+template <class Cfg, bool COLS_K, bool VEC, class T = float>
 struct ColLoaderSel {
-    typedef typename LoaderKSel<Cfg::LKV, Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC>::type type;
+    typedef typename LoaderKSel<Cfg::LKV, Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC, T>::type type;
 };
-template <class Cfg, bool VEC>
-struct ColLoaderSel<Cfg, false, VEC> {
-    typedef LoaderMN<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC> type;
+template <class Cfg, bool VEC, class T>
+struct ColLoaderSel<Cfg, false, VEC, T> {
+    typedef LoaderMN<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC, T> type;
 };
 
 // Epilogue of a product whose result is a row-major matrix: out = alpha*acc + beta*out with edge
@@ -94,10 +101,63 @@ __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::M
     }
 }
 
+// The same epilogue for C kept in half-precision storage: out = half(alpha*acc + beta*float(out)),
+// rounded to nearest even once.  Raw split-K slices stay FP32 and go through the float version.
+template <class Cfg>
+__device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::MB][Cfg::NB], _Float16 *C, int64_t ldc,
+                                                    int64_t M, int64_t N, float alpha, float beta, bool cvec,
+                                                    int64_t m0, int64_t n0, const SplitPlan &split, const WorkItem &w)
+{
+    if (split.plain && w.nslice > 1) {
+        store_tile_rowmajor<Cfg>(acc, static_cast<float *>(nullptr), N, M, N, 1.0f, 0.0f, false, m0, n0, split, w);
+        return;
+    }
+    typedef _Float16 HV __attribute__((ext_vector_type(Cfg::NB)));
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
+    const int64_t col = n0 + wn0 + Cfg::NB * i;
+    const bool full_vec = cvec && Cfg::NB > 1 && (col + Cfg::NB <= N);
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+            if (row >= M) continue;
+            _Float16 *dst = C + row * ldc + col;
+            float out[Cfg::NB];
+#pragma unroll
+            for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] = alpha * acc[bm][bn][r];
+            if constexpr (Cfg::NB > 1) {
+                if (full_vec) {
+                    if (beta != 0.0f) {
+                        const HV old = *reinterpret_cast<const HV *>(dst);
+#pragma unroll
+                        for (int bn = 0; bn < Cfg::NB; ++bn) out[bn] += beta * (float)old[bn];
+                    }
+                    HV o;
+#pragma unroll
+                    for (int bn = 0; bn < Cfg::NB; ++bn) o[bn] = (_Float16)out[bn];
+                    *reinterpret_cast<HV *>(dst) = o;
+                    continue;
+                }
+            }
+#pragma unroll
+            for (int bn = 0; bn < Cfg::NB; ++bn) {
+                if (col + bn < N) {
+                    float o = out[bn];
+                    if (beta != 0.0f) o += beta * (float)dst[bn];
+                    dst[bn] = (_Float16)o;
+                }
+            }
+        }
+    }
+}
+
 // A_KCONTIG: A stored M x K (transA == N).  B_KCONTIG: B stored N x K (transB == T).
 // VEC: every 16-byte global load of A and B is aligned and wholly inside the matrix.
-template <class Cfg, bool A_KCONTIG, bool B_KCONTIG, bool VEC>
-__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(const GemmArgs g)
+template <class Cfg, bool A_KCONTIG, bool B_KCONTIG, bool VEC, class ElemT = float>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(const GemmArgsT<ElemT> g)
 {
     __shared__ __attribute__((aligned(16))) float smem[Cfg::STAGES * Cfg::STAGE_FLOATS];
 
@@ -118,8 +178,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
     slice_range(ktiles_total, (int)(g.K - (int64_t)ktiles_total * Cfg::BK), w.slice, w.nslice, kt0, T, krem);
     const int64_t k0 = (int64_t)kt0 * Cfg::BK;
 
-    typename RowLoaderSel<Cfg, A_KCONTIG, VEC>::type rl;
-    typename ColLoaderSel<Cfg, B_KCONTIG, VEC>::type cl;
+    typename RowLoaderSel<Cfg, A_KCONTIG, VEC, ElemT>::type rl;
+    typename ColLoaderSel<Cfg, B_KCONTIG, VEC, ElemT>::type cl;
     rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x);
     cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x);
 
@@ -143,13 +203,17 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
 
 // Host side: pick the instantiation for the operand orientations and alignment, and launch.
 // Returns the hipError_t of the launch as int.
-template <class Cfg>
-int launch_gemm_cfg(const GemmArgs &g, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t stream)
+template <class Cfg, class T = float>
+int launch_gemm_cfg(const GemmArgsT<T> &g, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t stream)
 {
+    // half-precision storage is offered on the padded LDS image only
+    if constexpr (!std::is_same<T, float>::value && Cfg::LKV != 0) {
+        return (int)hipErrorInvalidValue;
+    } else {
     const int tiles = g.tiles_m * g.tiles_n;
     const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
 #define DMATH_LAUNCH(AK, BK_, V) \
-    hipLaunchKernelGGL((gemm_tile_kernel<Cfg, AK, BK_, V>), grid, block, 0, stream, g)
+    hipLaunchKernelGGL((gemm_tile_kernel<Cfg, AK, BK_, V, T>), grid, block, 0, stream, g)
     if (vec) {
         if (a_kcontig && b_kcontig) DMATH_LAUNCH(true, true, true);
         else if (a_kcontig) DMATH_LAUNCH(true, false, true);
@@ -163,6 +227,7 @@ int launch_gemm_cfg(const GemmArgs &g, bool a_kcontig, bool b_kcontig, bool vec,
     }
 #undef DMATH_LAUNCH
     return (int)hipGetLastError();
+    }
 }
 
 }  // namespace dmath

@@ -40,6 +40,29 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+
+// Four consecutive stored elements of type T as one vector, and their values as floats.  T is float, or
+// _Float16 for matrices kept in half-precision storage (converted exactly on the way to the LDS image).
+template <class T> struct Quad;
+template <> struct Quad<float> {
+    typedef floatx4 type;
+    static __device__ __forceinline__ floatx4 widen(floatx4 q) { return q; }
+};
+template <> struct Quad<_Float16> {
+    typedef halfx4 type;
+    static __device__ __forceinline__ floatx4 widen(halfx4 q)
+    {
+        floatx4 f;
+        f[0] = (float)q[0];
+        f[1] = (float)q[1];
+        f[2] = (float)q[2];
+        f[3] = (float)q[3];
+        return f;
+    }
+};
+
 template <int N> struct VecOf;
 template <> struct VecOf<1> { typedef float type; };
 template <> struct VecOf<2> { typedef floatx2 type; };
@@ -199,18 +222,19 @@ struct LoaderK {
 
 // Comparison variant for the unrotated, padded image (LD = BR + 4): 4 consecutive lanes per row,
 // 4-byte transposing stores (two-way bank conflicts on every store).
-template <int BR, int BK, int NT, int LD, bool VEC>
+template <int BR, int BK, int NT, int LD, bool VEC, class T = float>
 struct LoaderK0 {
     static constexpr int QPR = BK / 4;
     static constexpr int NQ = (BR * QPR) / NT;
     static constexpr int NLOAD = NQ, NSTORE = NQ * 4;
+    static constexpr int ES = (int)sizeof(T);
     static_assert((BR * QPR) % NT == 0 && NQ >= 1, "tile must split evenly over the threads");
     const char *tile;
     uint32_t off[NQ];
     floatx4 v[NQ];
     int row0, kq;
 
-    __device__ __forceinline__ void init(const float *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
+    __device__ __forceinline__ void init(const T *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
     {
         row0 = tid / QPR;
         kq = tid % QPR;
@@ -219,7 +243,7 @@ struct LoaderK0 {
         for (int it = 0; it < NQ; ++it) {
             int64_t lr = row0 + it * (NT / QPR);
             lr = r0 + lr < R ? lr : R - 1 - r0;
-            off[it] = (uint32_t)((lr * ld + kq * 4) * 4);
+            off[it] = (uint32_t)((lr * ld + kq * 4) * ES);
         }
     }
     template <int I>
@@ -227,18 +251,18 @@ struct LoaderK0 {
     {
         const char *q = tile + off[I];
         if (VEC) {
-            v[I] = *reinterpret_cast<const floatx4 *>(q);
+            v[I] = Quad<T>::widen(*reinterpret_cast<const typename Quad<T>::type *>(q));
         } else {
-            const float *f = reinterpret_cast<const float *>(q);
-            v[I][0] = f[0];
-            v[I][1] = f[1];
-            v[I][2] = f[2];
-            v[I][3] = f[3];
+            const T *f = reinterpret_cast<const T *>(q);
+            v[I][0] = (float)f[0];
+            v[I][1] = (float)f[1];
+            v[I][2] = (float)f[2];
+            v[I][3] = (float)f[3];
         }
     }
     // byte distance of k elements along K from a tile origin
-    static __device__ __forceinline__ int64_t k_bytes(int64_t k, int64_t) { return k * 4; }
-    __device__ __forceinline__ void advance() { tile += BK * 4; }
+    static __device__ __forceinline__ int64_t k_bytes(int64_t k, int64_t) { return k * ES; }
+    __device__ __forceinline__ void advance() { tile += BK * ES; }
     template <int I>
     __device__ __forceinline__ void store_piece(float *S) const
     {
@@ -249,58 +273,59 @@ struct LoaderK0 {
     {
 #pragma unroll
         for (int it = 0; it < NQ; ++it) {
-            const float *f = reinterpret_cast<const float *>(tile + off[it]);
+            const T *f = reinterpret_cast<const T *>(tile + off[it]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[it][j] = (kq * 4 + j < krem) ? f[j] : 0.0f;
+            for (int j = 0; j < 4; ++j) v[it][j] = (kq * 4 + j < krem) ? (float)f[j] : 0.0f;
         }
     }
 };
 
-template <int LKV, int BR, int BK, int NT, int LD, int ROT, bool VEC>
+template <int LKV, int BR, int BK, int NT, int LD, int ROT, bool VEC, class T = float>
 struct LoaderKSel {
-    typedef LoaderK<BR, BK, NT, LD, ROT, VEC> type;
+    typedef LoaderK<BR, BK, NT, LD, ROT, VEC> type;  // FP32 storage only
 };
-template <int BR, int BK, int NT, int LD, int ROT, bool VEC>
-struct LoaderKSel<0, BR, BK, NT, LD, ROT, VEC> {
-    typedef LoaderK0<BR, BK, NT, LD, VEC> type;
+template <int BR, int BK, int NT, int LD, int ROT, bool VEC, class T>
+struct LoaderKSel<0, BR, BK, NT, LD, ROT, VEC, T> {
+    typedef LoaderK0<BR, BK, NT, LD, VEC, T> type;
 };
 
 // Loader for an operand stored contiguously along its own index: element (r, k) at base[k*ld + r].
 // Used for A when transA == T and for B when transB == N.  Quads run along r; NT is a multiple of
 // the quads per k row, so a thread keeps one r quad and walks k.  16-byte global loads, 16-byte LDS
 // stores; the lanes served together write one contiguous (rotated) run of an image row.
-template <int BR, int BK, int NT, int LD, int ROT, bool VEC>
+template <int BR, int BK, int NT, int LD, int ROT, bool VEC, class T = float>
 struct LoaderMN {
     static constexpr int QPR = BR / 4;
     static constexpr int NQ = (BK * QPR) / NT;
     static constexpr int KSTEP = NT / QPR;
     static constexpr int NLOAD = NQ, NSTORE = NQ;
+    static constexpr int ES = (int)sizeof(T);
     static_assert((BK * QPR) % NT == 0 && NQ >= 1 && NT % QPR == 0, "tile must split evenly over the threads");
     const char *tile;   // &base[k*ld + r0], uniform over the workgroup
-    int64_t tstride;    // bytes per K tile: BK * ld * 4
+    int64_t tstride;    // bytes per K tile: BK * ld * ES
     uint32_t off[NQ];   // byte offset of k row krow + it*KSTEP, column of the quad (VEC) or 0 (scalar path)
     uint32_t c[4];      // scalar path: byte offsets of the four elements (clamped to the last valid one)
     floatx4 v[NQ];
     int lds[NQ];
     int krow;
 
-    __device__ __forceinline__ void init(const float *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
+    __device__ __forceinline__ void init(const T *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
     {
         krow = tid / QPR;
         const int rq = tid % QPR;
         tile = reinterpret_cast<const char *>(base + k0 * ld + r0);
-        tstride = (int64_t)BK * ld * 4;
+        tstride = (int64_t)BK * ld * ES;
         int64_t quad = rq * 4;  // VEC: R is a multiple of 4, a quad is wholly inside or wholly outside
         if (VEC) quad = r0 + quad + 4 <= R ? quad : R - 4 - r0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t lr = rq * 4 + j;
-            c[j] = (uint32_t)((r0 + lr < R ? lr : R - 1 - r0) * 4);
+            c[j] = (uint32_t)((r0 + lr < R ? lr : R - 1 - r0) * ES);
         }
 #pragma unroll
         for (int it = 0; it < NQ; ++it) {
             const int k = krow + it * KSTEP;
-            off[it] = (uint32_t)((k * ld + (VEC ? quad : 0)) * 4);
+            off[it] = (uint32_t)((k * ld + (VEC ? quad : 0)) * ES);
             lds[it] = k * LD + rot_col<BR, ROT>(rq * 4, k);
         }
     }
@@ -309,13 +334,13 @@ struct LoaderMN {
     {
         const char *q = tile + off[I];
         if (VEC) {
-            v[I] = *reinterpret_cast<const floatx4 *>(q);
+            v[I] = Quad<T>::widen(*reinterpret_cast<const typename Quad<T>::type *>(q));
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[I][j] = *reinterpret_cast<const float *>(q + c[j]);
+            for (int j = 0; j < 4; ++j) v[I][j] = (float)*reinterpret_cast<const T *>(q + c[j]);
         }
     }
-    static __device__ __forceinline__ int64_t k_bytes(int64_t k, int64_t ld) { return k * ld * 4; }
+    static __device__ __forceinline__ int64_t k_bytes(int64_t k, int64_t ld) { return k * ld * ES; }
     __device__ __forceinline__ void advance() { tile += tstride; }
     template <int I>
     __device__ __forceinline__ void store_piece(float *S) const
@@ -330,7 +355,7 @@ struct LoaderMN {
             const bool ok = krow + it * KSTEP < krem;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                v[it][j] = ok ? *reinterpret_cast<const float *>(q + (VEC ? 4 * j : c[j])) : 0.0f;
+                v[it][j] = ok ? (float)*reinterpret_cast<const T *>(q + (VEC ? ES * j : c[j])) : 0.0f;
         }
     }
 };

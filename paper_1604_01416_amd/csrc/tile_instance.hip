@@ -21,8 +21,9 @@ const CfgDesc &cfg_desc<DMATH_CFG_INDEX>()
     static const CfgDesc d = {
         name,
         ThisCfg::BM, ThisCfg::BN, ThisCfg::BK, ThisCfg::NT, ThisCfg::LDS_BYTES,
-        &launch_gemm_cfg<ThisCfg>,
+        &launch_gemm_cfg<ThisCfg, float>,
         &launch_conv_cfg<ThisCfg>,
+        &launch_gemm_cfg<ThisCfg, _Float16>,
         &launch_gemm_panels_cfg<ThisCfg>,
         &launch_conv_bwd_filter_cfg<ThisCfg>,
     };

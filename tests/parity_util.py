@@ -83,6 +83,59 @@ def run_gemm_case(dm, torch, tA, tB, M, N, K, alpha=1.0, beta=0.0, ld_extra=(0, 
     return check_bound(got[:, :N], ref, mag, max(K, 1), "gemm t%d%d %dx%dx%d" % (tA, tB, M, N, K))
 
 
+def stored_half(op_matrix, trans, ld_extra=0, lead=0, tail=8):
+    """Like stored(), for float16 storage."""
+    m = np.ascontiguousarray(op_matrix.T if trans else op_matrix, dtype=np.float16)
+    rows, cols = m.shape
+    ld = max(1, cols + ld_extra)
+    flat = np.full(lead + rows * ld + tail, np.nan, dtype=np.float16)
+    view = flat[lead:lead + rows * ld].reshape(rows, ld)
+    view[:, :cols] = m
+    return flat, lead, ld
+
+
+def run_hgemm_case(dm, torch, tA, tB, M, N, K, alpha=1.0, beta=0.0, ld_extra=(0, 0, 0), lead=(0, 0, 0),
+                   seed=0, ints=False, exact=False):
+    """One dmath_hgemm call (half-precision storage, FP32 arithmetic) against the oracle."""
+    rng = np.random.default_rng(seed)
+    if ints:
+        A = rng.integers(-2, 3, size=(M, K)).astype(np.float16)
+        B = rng.integers(-2, 3, size=(K, N)).astype(np.float16)
+        C0 = rng.integers(-4, 5, size=(M, N)).astype(np.float16)
+    else:
+        A = rng.uniform(-1, 1, (M, K)).astype(np.float16)
+        B = rng.uniform(-1, 1, (K, N)).astype(np.float16)
+        C0 = rng.standard_normal((M, N)).astype(np.float16)
+    if beta == 0.0:
+        C0[:] = np.nan
+    a_flat, a_off, lda = stored_half(A, tA, ld_extra[0], lead[0])
+    b_flat, b_off, ldb = stored_half(B, tB, ld_extra[1], lead[1])
+    c_flat, c_off, ldc = stored_half(C0, 0, ld_extra[2], lead[2])
+    dA, dB, dC = (torch.from_numpy(f).cuda() for f in (a_flat, b_flat, c_flat))
+    st = dm.dmath_hgemm(tA, tB, M, N, K, alpha, dA[a_off:], lda, dB[b_off:], ldb, beta, dC[c_off:], ldc)
+    assert st == dm.OK, (dm.dmath_status_string(st), dm.dmath_last_error_arg())
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    ref, mag = oracle.hgemm(tA, tB, M, N, K, alpha, a_flat[a_off:], lda, b_flat[b_off:], ldb, beta,
+                            c_flat[c_off:] if beta != 0.0 else None, ldc)
+    got = out[c_off:c_off + M * ldc].reshape(M, ldc) if M > 0 else np.zeros((0, ldc), np.float16)
+    if M > 0:
+        assert np.isnan(got[:, N:]).all(), "row padding of C was written"
+    assert np.isnan(out[:c_off]).all() and np.isnan(out[c_off + M * ldc:]).all(), "wrote outside C"
+    if M == 0 or N == 0:
+        return 0.0
+    g = got[:, :N].astype(np.float64)
+    if exact:
+        assert np.array_equal(g, ref), "integer case must be bit-exact"
+        return 0.0
+    err = np.abs(g - ref)
+    bnd = oracle.half_bound(max(K, 1), mag, ref)
+    bad = ~(err <= bnd)
+    assert not bad.any(), "hgemm t%d%d %dx%dx%d: %d elements outside the bound, first %s err %s bound %s" % (
+        tA, tB, M, N, K, int(bad.sum()), np.argwhere(bad)[:3].tolist(), err[bad][:3], bnd[bad][:3])
+    return float((err / bnd).max())
+
+
 def run_gemm_panels_case(dm, torch, tA, tB, M, N, K, P, alpha=1.0, beta=0.0, ld_extra=(0, 0, 0), lead=(0, 0, 0),
                          seed=0, ints=False, exact=False):
     """One dmath_gemm_panels call over P panels against the oracle's sum of products."""

@@ -14,7 +14,7 @@ import pytest
 
 import oracle
 from paper_1604_01416_amd import workloads
-from parity_util import check_bound, run_conv_bwd_data_case, run_conv_bwd_filter_case, run_conv_case, run_gemm_case, run_gemm_panels_case
+from parity_util import check_bound, run_conv_bwd_data_case, run_conv_bwd_filter_case, run_conv_case, run_gemm_case, run_gemm_panels_case, run_hgemm_case
 
 pytestmark = pytest.mark.gpu
 
@@ -605,3 +605,68 @@ def test_config3_panels_full_size_sampled(dm, torch):
                                   [wl.arrays[x.B] for x in wl.calls], c.ldb, 1.0, wl.arrays["C"], c.ldc, pi=pi, pj=pj)
     r = check_bound(got[pi, pj], ref, mag, c.K * len(wl.calls), "config 3 fused, sampled")
     print("config 3 fused max err/bound %.3g" % r)
+
+
+# ------------------------------------------------------------------ half-precision storage
+
+@pytest.mark.parametrize("tA,tB", TRANS)
+def test_hgemm_small(dm, torch, tA, tB):
+    run_hgemm_case(dm, torch, tA, tB, 300, 260, 150, seed=1 + 2 * tA + tB, ld_extra=(4, 8, 4))          # vector path
+    run_hgemm_case(dm, torch, tA, tB, 129, 67, 45, alpha=-0.5, beta=2.0, seed=7, ld_extra=(1, 3, 1))    # scalar path
+    run_hgemm_case(dm, torch, tA, tB, 64, 132, 64, seed=9, lead=(1, 2, 3), beta=1.0)                    # 2-byte aligned
+    run_hgemm_case(dm, torch, tA, tB, 128, 512, 64, ints=True, exact=True, beta=1.0, seed=3)
+    run_hgemm_case(dm, torch, tA, tB, 1, 1, 1, seed=4)
+    run_hgemm_case(dm, torch, tA, tB, 33, 20, 0, beta=0.5, seed=5)                                      # K == 0
+    run_hgemm_case(dm, torch, tA, tB, 33, 20, 16, alpha=0.0, beta=0.0, seed=6)
+
+
+@pytest.mark.parametrize("cfg", range(6))
+@pytest.mark.parametrize("split", [1, 3])
+def test_hgemm_every_config(dm, torch, cfg, split):
+    if cfg >= dm.dmath_num_configs():
+        pytest.skip("no such configuration")
+    dm.dmath_set_override(cfg, split)
+    if "_l2" in dm.dmath_config_name(cfg):
+        t = torch.zeros(4096, dtype=torch.float16, device="cuda")
+        assert dm.dmath_hgemm(0, 0, 16, 16, 16, 1.0, t, 16, t, 16, 0.0, t, 16) == dm.ERR_UNSUPPORTED
+        return
+    run_hgemm_case(dm, torch, 0, 0, 270, 520, 96, ints=True, exact=True, beta=1.0, seed=cfg)
+    run_hgemm_case(dm, torch, 1, 1, 516, 130, 200, alpha=1.5, beta=-1.0, seed=cfg + 10, ld_extra=(4, 4, 0))
+    run_hgemm_case(dm, torch, 0, 1, 100, 90, 77, seed=cfg + 20, ld_extra=(1, 1, 1))
+
+
+def test_hgemm_config4_layer_in_half_storage(dm, torch):
+    """The fully connected layer of config 4 with X, W, dY rounded to half and outputs stored as half."""
+    wl = workloads.config4()
+    half = {k: v.astype(np.float16) for k, v in wl.arrays.items()}
+    dev = {k: torch.from_numpy(v).cuda() for k, v in half.items()}
+    for c in wl.calls:
+        dm.check(dm.dmath_hgemm(c.transA, c.transB, c.M, c.N, c.K, 1.0, dev[c.A], c.lda, dev[c.B], c.ldb, 0.0,
+                                dev[c.C], c.ldc))
+    torch.cuda.synchronize()
+    for c in wl.calls:
+        ref, mag = oracle.hgemm(c.transA, c.transB, c.M, c.N, c.K, 1.0, half[c.A], c.lda, half[c.B], c.ldb)
+        got = dev[c.C].cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref)
+        bnd = oracle.half_bound(c.K, mag, ref)
+        assert (err <= bnd).all(), c.C
+        print("config 4 half storage %s max err/bound %.3g" % (c.C, (err / bnd).max()))
+
+
+def test_hgemm_4096_sampled(dm, torch):
+    wl = workloads.config2()
+    A, B = wl.arrays["A"].astype(np.float16), wl.arrays["B"].astype(np.float16)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dC = torch.full((4096, 4096), float("nan"), dtype=torch.float16, device="cuda")
+    dm.check(dm.dmath_hgemm(0, 0, 4096, 4096, 4096, 1.0, dA, 4096, dB, 4096, 0.0, dC, 4096))
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(2)
+    pi = np.concatenate([rng.integers(0, 4096, 20000), np.full(4096, 4095), np.arange(4096)])
+    pj = np.concatenate([rng.integers(0, 4096, 20000), np.arange(4096), np.zeros(4096, dtype=np.int64)])
+    ref, mag = oracle.hgemm(0, 0, 4096, 4096, 4096, 1.0, A, 4096, B, 4096, pi=pi, pj=pj)
+    err = np.abs(got[pi, pj].astype(np.float64) - ref)
+    bnd = oracle.half_bound(4096, mag, ref)
+    assert (err <= bnd).all()
+    print("hgemm 4096 max err/bound %.3g" % (err / bnd).max())
