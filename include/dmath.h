@@ -91,6 +91,15 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB,
  * elements.  The fast path needs 8-byte aligned pointers and leading dimensions that are multiples of
  * 4; anything 2-byte aligned works.  Conventions, errors and split-K workspace as for dmath_gemm (the
  * split-K slices are FP32); UNSUPPORTED if the rotated-image comparison configuration is forced.
+ *
+ * Two kernels implement it.  When A and B are 16-byte aligned, lda and ldb are multiples of 8, K is a
+ * multiple of 32 and an operand stored along its own index (A for transA == T, B for transB == N) has a
+ * multiple of 8 rows / columns, the FP16-input matrix instruction is used: products of two halves are
+ * exact in FP32 and it accumulates in FP32, so it computes the same sums (in another order) at 16 times
+ * the FP32 matrix rate.  Every other case runs the FP32 matrix instruction on operands widened on the
+ * fly.  dmath_set_hgemm_path forces one of them for this thread's later calls: -1 automatic, 0 the
+ * FP32 instruction, 1 the FP16-input instruction (then UNSUPPORTED when the conditions do not hold);
+ * a tile configuration forced with dmath_set_override also selects the FP32 instruction.
  */
 dmath_status dmath_hgemm(dmath_op transA, dmath_op transB,
                          int64_t M, int64_t N, int64_t K,
@@ -98,6 +107,7 @@ dmath_status dmath_hgemm(dmath_op transA, dmath_op transB,
                          const uint16_t *B, int64_t ldb,
                          float beta, uint16_t *C, int64_t ldc,
                          void *stream);
+dmath_status dmath_set_hgemm_path(int path);
 
 /*
  * Accumulating sequence of block multiplies in one call (section "Matrix Multiplication": a worker's

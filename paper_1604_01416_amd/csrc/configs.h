@@ -5,6 +5,7 @@
 #include "conv_kernel.h"
 #include "gemm_kernel.h"
 #include "gemm_panels_kernel.h"
+#include "hgemm_kernel.h"
 
 namespace dmath {
 

@@ -20,6 +20,7 @@ struct ThreadState {
     size_t ws_bytes = 0;
     int force_cfg = -1;
     int force_split = -1;
+    int hgemm_path = -1;  // -1 automatic, 0 FP32 matrix instruction on widened operands, 1 FP16-input instruction
     int last_error_arg = 0;
     unsigned long long *clock_probe = nullptr;
 };
@@ -346,11 +347,73 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
 
+    if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, lda > ((int64_t)1 << 22) ? 8 : 10);
+    if constexpr (kHalf) {
+        // The FP16-input matrix instruction computes the same FP32 sums of exact products 16 times
+        // faster; its kernel needs whole K tiles and 16-byte chunks everywhere.
+        const HCfgDesc &h = hcfg_desc();
+        const bool fits = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0 && K % h.BK == 0 &&
+                          (a_k || M % 8 == 0) && (b_k || N % 8 == 0);
+        if (g_state.hgemm_path == 1 && !fits) return fail(DMATH_ERR_UNSUPPORTED, 0);
+        if (fits && g_state.hgemm_path != 0 && g_state.force_cfg < 0) {
+            const int64_t tiles_m = ceil_div(M, h.BM), tiles_n = ceil_div(N, h.BN), tiles = tiles_m * tiles_n;
+            const int64_t ktiles = K / h.BK;
+            if (tiles * 64 > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
+            // few tiles: cut K so that the slices fill the compute units (plain split-K, FP32 slices)
+            int64_t s = 1;
+            if (g_state.force_split >= 1)
+                s = g_state.force_split;
+            else if (tiles < kNumCU / 2)
+                s = kNumCU / tiles;
+            if (s > kMaxSplits) s = kMaxSplits;
+            if (s > ktiles / 2) s = ktiles / 2;
+            const size_t avail = g_state.ws ? g_state.ws_bytes : 0;
+            const size_t slice_bytes = (size_t)M * (size_t)N * sizeof(float);
+            if (s > 1 && s * slice_bytes > avail) s = (int64_t)(avail / slice_bytes);
+            if (s < 2) s = 1;
+            HGemmArgs g;
+            g.A = A;
+            g.B = B;
+            g.C = C;
+            g.lda = lda;
+            g.ldb = ldb;
+            g.ldc = ldc;
+            g.M = M;
+            g.N = N;
+            g.K = K;
+            g.alpha = alpha;
+            g.beta = beta;
+            g.tiles_m = (int)tiles_m;
+            g.tiles_n = (int)tiles_n;
+            g.clock_probe = nullptr;
+            g.cvec = ((reinterpret_cast<uintptr_t>(C) & 7u) == 0 && ldc % 4 == 0) ? 1 : 0;
+            g.split.dp_tiles = s > 1 ? 0 : (int)tiles;
+            g.split.splits = (int)s;
+            g.split.partials = s > 1 ? static_cast<float *>(g_state.ws) : nullptr;
+            g.split.counters = nullptr;
+            g.split.plain = s > 1 ? 1 : 0;
+            g.split.slice_stride = M * N;
+            if (h.launch(g, a_k, b_k, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+            if (s > 1) {
+                const bool v4 = (N % 4 == 0) && g.cvec;
+                const int64_t items = v4 ? M * (N / 4) : M * N;
+                const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
+                if (v4)
+                    hipLaunchKernelGGL(splitk_reduce_kernel_v4<_Float16>, dim3(blocks), dim3(256), 0, stream,
+                                       static_cast<const float *>(g_state.ws), (int)s, M * N, C, ldc, M, N, alpha, beta);
+                else
+                    hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, stream,
+                                       static_cast<const float *>(g_state.ws), (int)s, M * N, C, ldc, M, N, alpha, beta);
+                if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+            }
+            return DMATH_OK;
+        }
+    }
+
     const Plan plan = resolve_plan(M, N, K, g_state.ws ? g_state.ws_bytes : 0, false);
     const CfgDesc &d = desc(plan.cfg);
     const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
     if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
-    if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, lda > ((int64_t)1 << 22) ? 8 : 10);
 
     // 16-byte loads need aligned bases and rows; along the operand's own index also a whole number of quads.
     auto quad_aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & kQuadAlign) == 0; };
@@ -426,6 +489,13 @@ dmath_status dmath_set_override(int tile_config, int split_k)
     if (split_k == 0 || split_k > 64) return fail(DMATH_ERR_INVALID_ARG, 2);
     g_state.force_cfg = tile_config < 0 ? -1 : tile_config;
     g_state.force_split = split_k < 0 ? -1 : split_k;
+    return DMATH_OK;
+}
+
+dmath_status dmath_set_hgemm_path(int path)
+{
+    if (path < -1 || path > 1) return fail(DMATH_ERR_INVALID_ARG, 1);
+    g_state.hgemm_path = path;
     return DMATH_OK;
 }
 

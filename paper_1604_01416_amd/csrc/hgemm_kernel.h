@@ -1,0 +1,403 @@
+// GEMM on half-precision storage computed on the FP16-input matrix instruction
+// (v_mfma_f32_32x32x16_f16): the product of two halves is exact in FP32 and the instruction accumulates
+// in FP32, so the arithmetic is the single-precision arithmetic on converted operands that section
+// "Precisions" of the paper describes, at the rate of the 16-bit matrix pipe.
+//
+// Operand layout of the instruction (checked on the device with one-hot operands): lane l holds, for
+// A, row l%32 and the 8 consecutive k = 8*(l/32) .. +7; for B, column l%32 and the same k; the 32x32
+// FP32 result is laid out like that of the FP32 instruction.  Both operands therefore want 8
+// consecutive k per lane, and the LDS image of a K tile is k-contiguous for both:
+//
+//     As[BM][LDK], Bs[BN][LDK] halves, LDK = BK + 8 (80-byte rows: the 16 lanes served together by a
+//     16-byte LDS read hit 16 different 16-byte bank groups when they read 16 consecutive rows).
+//
+// An operand stored contiguously along k (A for transA == N, B for transB == T) is copied with 16-byte
+// loads and 16-byte LDS stores.  An operand stored along its own index (A^T, B) is transposed on the
+// way: a thread loads the same 8 columns of two consecutive k rows, pairs them up in registers and
+// writes eight 4-byte (k, k+1) pairs.
+//
+// A wave owns MB x NB blocks of 32x32; block (bm, bn) covers tile rows wm0 + 32*bm .. +31 and tile
+// columns wn0 + 32*bn .. +31 (contiguous blocks, unlike the FP32 kernel's interleaved ones, because
+// consecutive lanes must read consecutive image rows to stay conflict-free).
+#pragma once
+#include "gemm_kernel.h"
+
+namespace dmath {
+
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int STAGES_>
+struct HTileCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = 32;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
+    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int MB = WM / 32, NB = WN / 32;
+    static constexpr int LDK = BK + 8;
+    static constexpr int A_HALVES = BM * LDK, B_HALVES = BN * LDK, STAGE_HALVES = A_HALVES + B_HALVES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_HALVES * 2;
+    static constexpr int KSTEPS = BK / 16;
+    static constexpr int MIN_WAVES = (NT / 64 + 3) / 4;
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && STAGES >= 3, "wave tile is made of 32x32 blocks; 3+ stages");
+};
+
+// Operand contiguous along k: element (r, k) at base[r*ld + k].  Thread (row, 8-element chunk).
+// SLOTS register sets hold tiles in flight between the global load and the LDS store.
+template <int BR, int BK, int NT, int LDK, int SLOTS>
+struct HLoaderK {
+    static constexpr int CPR = BK / 8;             // 16-byte chunks per row
+    static constexpr int NP = (BR * CPR) / NT;     // chunks per thread
+    static constexpr int NLOAD = NP, NSTORE = NP;
+    static_assert((BR * CPR) % NT == 0 && NP >= 1, "tile must split evenly over the threads");
+    const char *tile;
+    uint32_t off[NP];
+    halfx8 v[SLOTS][NP];
+    int lds0;
+
+    __device__ __forceinline__ void init(const _Float16 *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
+    {
+        const int row0 = tid / CPR, ch = tid % CPR;
+        tile = reinterpret_cast<const char *>(base + r0 * ld + k0);
+        lds0 = row0 * LDK + ch * 8;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            int64_t lr = row0 + p * (NT / CPR);
+            lr = r0 + lr < R ? lr : R - 1 - r0;  // rows past the end re-read the last one; never stored
+            off[p] = (uint32_t)((lr * ld + ch * 8) * 2);
+        }
+    }
+    template <int SLOT, int I>
+    __device__ __forceinline__ void load_piece()
+    {
+        v[SLOT][I] = *reinterpret_cast<const halfx8 *>(tile + off[I]);
+    }
+    __device__ __forceinline__ void advance() { tile += BK * 2; }
+    template <int SLOT, int I>
+    __device__ __forceinline__ void store_piece(_Float16 *S) const
+    {
+        *reinterpret_cast<halfx8 *>(S + lds0 + I * (NT / CPR) * LDK) = v[SLOT][I];
+    }
+};
+
+// Operand contiguous along its own index: element (r, k) at base[k*ld + r].  A thread owns the 8
+// consecutive r of one chunk for the k pair (2*kp, 2*kp + 1): lanes 0..15 of a 16-lane group take the
+// 16 k pairs of one chunk, so that their 4-byte LDS stores fall into 16 consecutive dwords of a row.
+template <int BR, int BK, int NT, int LDK, int SLOTS>
+struct HLoaderN {
+    static constexpr int KP = BK / 2;                     // k pairs per tile
+    static constexpr int ITEMS = KP * (BR / 8);           // (k pair, chunk) items
+    static constexpr int NP = ITEMS / NT;
+    static constexpr int NLOAD = 2 * NP, NSTORE = 8 * NP;
+    static_assert(ITEMS % NT == 0 && NP >= 1 && NT % KP == 0, "tile must split evenly over the threads");
+    const char *tile;
+    int64_t tstride, row_bytes;
+    uint32_t off[NP];
+    halfx8 v[SLOTS][NP][2];
+    int lds0;
+
+    __device__ __forceinline__ void init(const _Float16 *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
+    {
+        const int kp = tid % KP, c0 = tid / KP;
+        tile = reinterpret_cast<const char *>(base + k0 * ld + r0);
+        tstride = (int64_t)BK * ld * 2;
+        row_bytes = ld * 2;
+        lds0 = c0 * 8 * LDK + 2 * kp;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            int64_t col = (c0 + p * (NT / KP)) * 8;
+            col = r0 + col + 8 <= R ? col : R - 8 - r0;  // R is a multiple of 8: the last whole chunk
+            off[p] = (uint32_t)(((int64_t)2 * kp * ld + col) * 2);
+        }
+    }
+    template <int SLOT, int I>
+    __device__ __forceinline__ void load_piece()
+    {
+        constexpr int p = I / 2, which = I % 2;
+        v[SLOT][p][which] = *reinterpret_cast<const halfx8 *>(tile + off[p] + (which ? row_bytes : 0));
+    }
+    __device__ __forceinline__ void advance() { tile += tstride; }
+    template <int SLOT, int I>
+    __device__ __forceinline__ void store_piece(_Float16 *S) const
+    {
+        constexpr int p = I / 8, j = I % 8;
+        halfx2 pr;
+        pr[0] = v[SLOT][p][0][j];
+        pr[1] = v[SLOT][p][1][j];
+        *reinterpret_cast<halfx2 *>(S + lds0 + (p * (NT / KP) * 8 + j) * LDK) = pr;
+    }
+};
+
+template <class Cfg, bool KCONTIG, int BR, int SLOTS>
+struct HLoaderSel {
+    typedef HLoaderK<BR, Cfg::BK, Cfg::NT, Cfg::LDK, SLOTS> type;
+};
+template <class Cfg, int BR, int SLOTS>
+struct HLoaderSel<Cfg, false, BR, SLOTS> {
+    typedef HLoaderN<BR, Cfg::BK, Cfg::NT, Cfg::LDK, SLOTS> type;
+};
+
+template <class Cfg>
+struct HFrag {
+    halfx8 a[Cfg::MB], b[Cfg::NB];
+};
+
+// Fragment piece P of k step KS: P < MB is block row P of A, else block column P - MB of B.
+template <class Cfg, int KS, int P>
+__device__ __forceinline__ void hload_frag_piece(HFrag<Cfg> &f, const _Float16 *As, const _Float16 *Bs, int a_off, int b_off)
+{
+    if constexpr (P < Cfg::MB)
+        f.a[P] = *reinterpret_cast<const halfx8 *>(As + a_off + P * 32 * Cfg::LDK + KS * 16);
+    else
+        f.b[P - Cfg::MB] = *reinterpret_cast<const halfx8 *>(Bs + b_off + (P - Cfg::MB) * 32 * Cfg::LDK + KS * 16);
+}
+
+template <class Cfg, int Q>
+__device__ __forceinline__ void hmma_one(const HFrag<Cfg> &f, floatx16 (&acc)[Cfg::MB][Cfg::NB])
+{
+    constexpr int bm = Q / Cfg::NB, bn = Q % Cfg::NB;
+    acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.a[bm], f.b[bn], acc[bm][bn], 0, 0, 0);
+}
+
+// One K tile: MB*NB matrix instructions per k step.  Between them, one at a time: the fragment reads
+// of the next k step (or of the next tile's first step), the LDS stores of the staged tile (DO_STORE)
+// and the global loads of a later tile (DO_LOAD).  SLOT is the register set both use: the tile stored
+// now was loaded SLOTS iterations ago.
+//
+// STEADY: everything happens, no conditions.  Otherwise (first and last tiles of a K range) the
+// workgroup-uniform flags say whether there is a tile to store, one to load and a next one to read;
+// the conditions guard the memory operations only, the matrix instructions are common code.
+template <class Cfg, int SLOT, bool STEADY, class RL, class CL>
+__device__ __forceinline__ void htile_iter(RL &rl, CL &cl, HFrag<Cfg> (&fr)[2], floatx16 (&acc)[Cfg::MB][Cfg::NB],
+                                           const _Float16 *cur, const _Float16 *nxt, _Float16 *fill, int a_off, int b_off,
+                                           bool DO_STORE = true, bool DO_LOAD = true, bool NEXT = true)
+{
+    if constexpr (STEADY) {
+        DO_STORE = true;
+        DO_LOAD = true;
+        NEXT = true;
+    }
+    constexpr int NMMA = Cfg::MB * Cfg::NB, NFRAG = Cfg::MB + Cfg::NB;
+    constexpr int NST = RL::NSTORE + CL::NSTORE, NLD = RL::NLOAD + CL::NLOAD;
+    static_for<Cfg::KSTEPS>([&](auto ksc) {
+        constexpr int ks = decltype(ksc)::value;
+        constexpr bool last = ks == Cfg::KSTEPS - 1;
+        static_for<NMMA>([&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            hmma_one<Cfg, q>(fr[ks % 2], acc);
+            __builtin_amdgcn_sched_barrier(0);
+            // fragments for the next k step (same tile) or the first step of the next tile
+            if constexpr (q < NFRAG) {
+                if constexpr (!last)
+                    hload_frag_piece<Cfg, ks + 1, q>(fr[(ks + 1) % 2], cur, cur + Cfg::A_HALVES, a_off, b_off);
+                else if (NEXT)
+                    hload_frag_piece<Cfg, 0, q>(fr[0], nxt, nxt + Cfg::A_HALVES, a_off, b_off);
+            }
+            // staged tile -> LDS, spread over the matrix instructions of all k steps
+            constexpr int slot_idx = ks * NMMA + q;
+            constexpr int per = (NST + Cfg::KSTEPS * NMMA - 1) / (Cfg::KSTEPS * NMMA);
+            if (DO_STORE) {
+                static_for<per>([&](auto ec) {
+                    constexpr int s = slot_idx * per + decltype(ec)::value;
+                    if constexpr (s < RL::NSTORE)
+                        rl.template store_piece<SLOT, s>(fill);
+                    else if constexpr (s < NST)
+                        cl.template store_piece<SLOT, s - RL::NSTORE>(fill + Cfg::A_HALVES);
+                });
+            }
+            // global loads of a later tile go out once this slot's registers have been stored
+            if (DO_LOAD) {
+                constexpr int first_free = (NST + per - 1) / per;  // matrix instruction after the last store
+                constexpr int l = slot_idx - first_free;
+                if constexpr (l >= 0 && l < NLD) {
+                    if constexpr (l < RL::NLOAD)
+                        rl.template load_piece<SLOT, l>();
+                    else
+                        cl.template load_piece<SLOT, l - RL::NLOAD>();
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    });
+    if (DO_LOAD) {
+        // loads that found no matrix instruction to follow (many stores, few instructions)
+        constexpr int per = (NST + Cfg::KSTEPS * NMMA - 1) / (Cfg::KSTEPS * NMMA);
+        constexpr int first_free = (NST + per - 1) / per;
+        constexpr int placed = Cfg::KSTEPS * NMMA - first_free > 0 ? Cfg::KSTEPS * NMMA - first_free : 0;
+        static_for<NLD>([&](auto lc) {
+            constexpr int l = decltype(lc)::value;
+            if constexpr (l >= placed) {
+                if constexpr (l < RL::NLOAD)
+                    rl.template load_piece<SLOT, l>();
+                else
+                    cl.template load_piece<SLOT, l - RL::NLOAD>();
+            }
+        });
+        rl.advance();
+        cl.advance();
+    }
+}
+
+// Epilogue: lane (i, h) holds, for block (bm, bn) and register r, the element in tile row
+// wm0 + 32*bm + 8*(r/4) + 4*h + r%4, tile column wn0 + 32*bn + i.  out = half(alpha*acc + beta*out);
+// a slice of a plain split-K launch writes raw FP32 sums to its M x N array in the workspace.
+template <class Cfg>
+__device__ __forceinline__ void hstore_tile(const floatx16 (&acc)[Cfg::MB][Cfg::NB], _Float16 *C, int64_t ldc, int64_t M,
+                                            int64_t N, float alpha, float beta, int64_t m0, int64_t n0,
+                                            const SplitPlan &split, const WorkItem &w)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
+    const bool raw = split.plain && w.nslice > 1;
+    float *Z = raw ? split.partials + (int64_t)w.slice * split.slice_stride : nullptr;
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + wm0 + 32 * bm + 8 * (r / 4) + 4 * h + (r % 4);
+            if (row >= M) continue;
+#pragma unroll
+            for (int bn = 0; bn < Cfg::NB; ++bn) {
+                const int64_t col = n0 + wn0 + 32 * bn + i;
+                if (col >= N) continue;
+                if (raw) {
+                    Z[row * N + col] = acc[bm][bn][r];
+                } else {
+                    _Float16 *dst = C + row * ldc + col;
+                    float o = alpha * acc[bm][bn][r];
+                    if (beta != 0.0f) o += beta * (float)*dst;
+                    *dst = (_Float16)o;
+                }
+            }
+        }
+}
+
+// Needs: K a multiple of BK, 16-byte aligned A and B with leading dimensions that are multiples of 8,
+// and an operand stored along its own index to have a multiple of 8 rows/columns (the host checks).
+template <class Cfg, bool A_KCONTIG, bool B_KCONTIG>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(const HGemmArgs g)
+{
+    constexpr int S = Cfg::STAGES, SLOTS = 2;
+    __shared__ __attribute__((aligned(16))) _Float16 smem[S * Cfg::STAGE_HALVES];
+
+    const int tiles = g.tiles_m * g.tiles_n;
+    const WorkItem w = work_item(blockIdx.x, tiles, g.split);
+    int tm, tn;
+    tile_coords<8>(w.tile, g.tiles_m, g.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
+    int kt0, T, krem;
+    slice_range((int)(g.K / Cfg::BK), 0, w.slice, w.nslice, kt0, T, krem);
+    const int64_t k0 = (int64_t)kt0 * Cfg::BK;
+
+    typename HLoaderSel<Cfg, A_KCONTIG, Cfg::BM, SLOTS>::type rl;
+    typename HLoaderSel<Cfg, B_KCONTIG, Cfg::BN, SLOTS>::type cl;
+    rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x);
+    cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int a_off = ((wave / Cfg::WAVES_N) * Cfg::WM + (lane & 31)) * Cfg::LDK + 8 * (lane >> 5);
+    const int b_off = ((wave % Cfg::WAVES_N) * Cfg::WN + (lane & 31)) * Cfg::LDK + 8 * (lane >> 5);
+
+    floatx16 acc[Cfg::MB][Cfg::NB];
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < Cfg::NB; ++bn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
+
+    // Prologue: tiles 0 .. S-2 go to LDS stages 0 .. S-2 through register set 0; then tiles S-1 and S
+    // are loaded into register sets 0 and 1 and stay in flight.  Tile t lives in stage t % S; iteration
+    // t stores tile t + S - 1 (register set t % 2) and then loads tile t + S + 1 into the same set.
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s) {
+        if (s < T) {
+            static_for<decltype(rl)::NLOAD>([&](auto ic) { rl.template load_piece<0, decltype(ic)::value>(); });
+            static_for<decltype(cl)::NLOAD>([&](auto ic) { cl.template load_piece<0, decltype(ic)::value>(); });
+            rl.advance();
+            cl.advance();
+            _Float16 *st = smem + s * Cfg::STAGE_HALVES;
+            static_for<decltype(rl)::NSTORE>([&](auto ic) { rl.template store_piece<0, decltype(ic)::value>(st); });
+            static_for<decltype(cl)::NSTORE>([&](auto ic) { cl.template store_piece<0, decltype(ic)::value>(st + Cfg::A_HALVES); });
+        }
+    }
+    if (S - 1 < T) {
+        static_for<decltype(rl)::NLOAD>([&](auto ic) { rl.template load_piece<0, decltype(ic)::value>(); });
+        static_for<decltype(cl)::NLOAD>([&](auto ic) { cl.template load_piece<0, decltype(ic)::value>(); });
+        rl.advance();
+        cl.advance();
+    }
+    if (S < T) {
+        static_for<decltype(rl)::NLOAD>([&](auto ic) { rl.template load_piece<1, decltype(ic)::value>(); });
+        static_for<decltype(cl)::NLOAD>([&](auto ic) { cl.template load_piece<1, decltype(ic)::value>(); });
+        rl.advance();
+        cl.advance();
+    }
+    __syncthreads();
+
+    HFrag<Cfg> fr[2];
+    if (T > 0)
+        static_for<Cfg::MB + Cfg::NB>([&](auto pc) {
+            hload_frag_piece<Cfg, 0, decltype(pc)::value>(fr[0], smem, smem + Cfg::A_HALVES, a_off, b_off);
+        });
+
+    // Two tiles per trip (register sets 0 and 1); LDS stages by pointer.
+    int cs = 0, fill = S - 1;
+    auto stage = [&](int s) { return smem + s * Cfg::STAGE_HALVES; };
+    auto next_of = [](int s) { return s + 1 == S ? 0 : s + 1; };
+    int t = 0;
+    // steady state: stores, loads and a next tile exist for both halves of the trip
+    while (t + S + 2 < T) {
+        htile_iter<Cfg, 0, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off);
+        cs = next_of(cs);
+        fill = next_of(fill);
+        __syncthreads();
+        htile_iter<Cfg, 1, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off);
+        cs = next_of(cs);
+        fill = next_of(fill);
+        __syncthreads();
+        t += 2;
+    }
+    // first and last tiles of the range: the same iterations with their conditions
+    for (; t < T; t += 2) {
+        htile_iter<Cfg, 0, false>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off,
+                                  t + S - 1 < T, t + S + 1 < T, t + 1 < T);
+        cs = next_of(cs);
+        fill = next_of(fill);
+        __syncthreads();
+        if (t + 1 < T) {
+            htile_iter<Cfg, 1, false>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off,
+                                      t + S < T, t + S + 2 < T, t + 2 < T);
+            cs = next_of(cs);
+            fill = next_of(fill);
+            __syncthreads();
+        }
+    }
+    if (!combine_slices<Cfg>(acc, g.split, w)) return;
+    hstore_tile<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
+}
+
+template <class Cfg>
+int launch_hgemm_mfma16(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
+{
+    const int tiles = g.tiles_m * g.tiles_n;
+    const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
+    if (a_kcontig && b_kcontig)
+        hipLaunchKernelGGL((hgemm_mfma16_kernel<Cfg, true, true>), grid, block, 0, stream, g);
+    else if (a_kcontig)
+        hipLaunchKernelGGL((hgemm_mfma16_kernel<Cfg, true, false>), grid, block, 0, stream, g);
+    else if (b_kcontig)
+        hipLaunchKernelGGL((hgemm_mfma16_kernel<Cfg, false, true>), grid, block, 0, stream, g);
+    else
+        hipLaunchKernelGGL((hgemm_mfma16_kernel<Cfg, false, false>), grid, block, 0, stream, g);
+    return (int)hipGetLastError();
+}
+
+struct HCfgDesc {
+    const char *name;
+    int BM, BN, BK, NT, lds_bytes;
+    int (*launch)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);
+};
+const HCfgDesc &hcfg_desc();  // defined in hgemm_instance.hip
+
+}  // namespace dmath
