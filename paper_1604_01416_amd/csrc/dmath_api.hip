@@ -351,10 +351,10 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     if constexpr (kHalf) {
         // The FP16-input matrix instruction computes the same FP32 sums of exact products 16 times
         // faster; its kernel needs whole K tiles and 16-byte chunks everywhere.
-        const HCfgDesc &h = hcfg_desc();
+        const HCfgDesc &h = hcfg_desc(g_state.hgemm_path >= 1 ? g_state.hgemm_path - 1 : 0);
         const bool fits = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0 && K % h.BK == 0 &&
                           (a_k || M % 8 == 0) && (b_k || N % 8 == 0);
-        if (g_state.hgemm_path == 1 && !fits) return fail(DMATH_ERR_UNSUPPORTED, 0);
+        if (g_state.hgemm_path >= 1 && !fits) return fail(DMATH_ERR_UNSUPPORTED, 0);
         if (fits && g_state.hgemm_path != 0 && g_state.force_cfg < 0) {
             const int64_t tiles_m = ceil_div(M, h.BM), tiles_n = ceil_div(N, h.BN), tiles = tiles_m * tiles_n;
             const int64_t ktiles = K / h.BK;
@@ -385,7 +385,7 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
             g.beta = beta;
             g.tiles_m = (int)tiles_m;
             g.tiles_n = (int)tiles_n;
-            g.clock_probe = nullptr;
+            g.clock_probe = g_state.clock_probe;
             g.cvec = ((reinterpret_cast<uintptr_t>(C) & 7u) == 0 && ldc % 4 == 0) ? 1 : 0;
             g.split.dp_tiles = s > 1 ? 0 : (int)tiles;
             g.split.splits = (int)s;
@@ -494,7 +494,7 @@ dmath_status dmath_set_override(int tile_config, int split_k)
 
 dmath_status dmath_set_hgemm_path(int path)
 {
-    if (path < -1 || path > 1) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (path < -1 || path > kNumHCfg) return fail(DMATH_ERR_INVALID_ARG, 1);
     g_state.hgemm_path = path;
     return DMATH_OK;
 }

@@ -1,16 +1,18 @@
-// The FP16-input matrix-instruction GEMM kernels (one tile configuration), in a translation unit of
-// their own.
+// The FP16-input matrix-instruction GEMM kernels, in a translation unit of their own.
 #include "hgemm_kernel.h"
 
 namespace dmath {
 
-typedef HTileCfg<256, 256, 4, 2, 3> HCfg0;
+typedef HTileCfg<256, 256, 4, 2, 3> HCfg0;  // 8 waves, wave tile 64 x 128, two waves per SIMD
+typedef HTileCfg<256, 256, 2, 2, 3> HCfg1;  // 4 waves, wave tile 128 x 128, one wave per SIMD
 
-const HCfgDesc &hcfg_desc()
+const HCfgDesc &hcfg_desc(int i)
 {
-    static const HCfgDesc d = {"h256x256x32_w4x2_s3", HCfg0::BM, HCfg0::BN, HCfg0::BK, HCfg0::NT, HCfg0::LDS_BYTES,
-                               &launch_hgemm_mfma16<HCfg0>};
-    return d;
+    static const HCfgDesc d[kNumHCfg] = {
+        {"h256x256x32_w4x2_s3", HCfg0::BM, HCfg0::BN, HCfg0::BK, HCfg0::NT, HCfg0::LDS_BYTES, &launch_hgemm_mfma16<HCfg0>},
+        {"h256x256x32_w2x2_s3", HCfg1::BM, HCfg1::BN, HCfg1::BK, HCfg1::NT, HCfg1::LDS_BYTES, &launch_hgemm_mfma16<HCfg1>},
+    };
+    return d[i < 0 || i >= kNumHCfg ? 0 : i];
 }
 
 }  // namespace dmath

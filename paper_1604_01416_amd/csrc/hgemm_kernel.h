@@ -82,6 +82,10 @@ struct HLoaderK {
 // Operand contiguous along its own index: element (r, k) at base[k*ld + r].  A thread owns the 8
 // consecutive r of one chunk for the k pair (2*kp, 2*kp + 1): lanes 0..15 of a 16-lane group take the
 // 16 k pairs of one chunk, so that their 4-byte LDS stores fall into 16 consecutive dwords of a row.
+// (Image rows 8 apart share their banks, so the four 16-lane groups of a wave collide two by two:
+// 4 conflict cycles per store by the counters.  Exchanging the halves of every other chunk, fetched as
+// two 8-byte loads, halved the conflicts but doubled the vector-memory instructions and was 20-35 %
+// slower; the 16-byte loads stay.)
 template <int BR, int BK, int NT, int LDK, int SLOTS>
 struct HLoaderN {
     static constexpr int KP = BK / 2;                     // k pairs per tile
@@ -280,6 +284,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
     constexpr int S = Cfg::STAGES, SLOTS = 2;
     __shared__ __attribute__((aligned(16))) _Float16 smem[S * Cfg::STAGE_HALVES];
 
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();
+        g.clock_probe[blockIdx.x * 4 + 1] = __builtin_amdgcn_s_memrealtime();
+    }
     const int tiles = g.tiles_m * g.tiles_n;
     const WorkItem w = work_item(blockIdx.x, tiles, g.split);
     int tm, tn;
@@ -309,54 +317,69 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
     // Prologue: tiles 0 .. S-2 go to LDS stages 0 .. S-2 through register set 0; then tiles S-1 and S
     // are loaded into register sets 0 and 1 and stay in flight.  Tile t lives in stage t % S; iteration
     // t stores tile t + S - 1 (register set t % 2) and then loads tile t + S + 1 into the same set.
-#pragma unroll
-    for (int s = 0; s < S - 1; ++s) {
-        if (s < T) {
-            static_for<decltype(rl)::NLOAD>([&](auto ic) { rl.template load_piece<0, decltype(ic)::value>(); });
-            static_for<decltype(cl)::NLOAD>([&](auto ic) { cl.template load_piece<0, decltype(ic)::value>(); });
-            rl.advance();
-            cl.advance();
-            _Float16 *st = smem + s * Cfg::STAGE_HALVES;
-            static_for<decltype(rl)::NSTORE>([&](auto ic) { rl.template store_piece<0, decltype(ic)::value>(st); });
-            static_for<decltype(cl)::NSTORE>([&](auto ic) { cl.template store_piece<0, decltype(ic)::value>(st + Cfg::A_HALVES); });
-        }
-    }
-    if (S - 1 < T) {
-        static_for<decltype(rl)::NLOAD>([&](auto ic) { rl.template load_piece<0, decltype(ic)::value>(); });
-        static_for<decltype(cl)::NLOAD>([&](auto ic) { cl.template load_piece<0, decltype(ic)::value>(); });
+    auto load_all = [&](auto slotc) {
+        constexpr int SL = decltype(slotc)::value;
+        static_for<decltype(rl)::NLOAD>([&](auto ic) { rl.template load_piece<SL, decltype(ic)::value>(); });
+        static_for<decltype(cl)::NLOAD>([&](auto ic) { cl.template load_piece<SL, decltype(ic)::value>(); });
         rl.advance();
         cl.advance();
-    }
-    if (S < T) {
-        static_for<decltype(rl)::NLOAD>([&](auto ic) { rl.template load_piece<1, decltype(ic)::value>(); });
-        static_for<decltype(cl)::NLOAD>([&](auto ic) { cl.template load_piece<1, decltype(ic)::value>(); });
-        rl.advance();
-        cl.advance();
-    }
-    __syncthreads();
-
+    };
+    auto store_all = [&](_Float16 *st) {
+        static_for<decltype(rl)::NSTORE>([&](auto ic) { rl.template store_piece<0, decltype(ic)::value>(st); });
+        static_for<decltype(cl)::NSTORE>([&](auto ic) { cl.template store_piece<0, decltype(ic)::value>(st + Cfg::A_HALVES); });
+    };
+    typedef std::integral_constant<int, 0> Slot0;
+    typedef std::integral_constant<int, 1> Slot1;
     HFrag<Cfg> fr[2];
-    if (T > 0)
+    auto first_frags = [&]() {
         static_for<Cfg::MB + Cfg::NB>([&](auto pc) {
             hload_frag_piece<Cfg, 0, decltype(pc)::value>(fr[0], smem, smem + Cfg::A_HALVES, a_off, b_off);
         });
-
-    // Two tiles per trip (register sets 0 and 1); LDS stages by pointer.
+    };
     int cs = 0, fill = S - 1;
     auto stage = [&](int s) { return smem + s * Cfg::STAGE_HALVES; };
     auto next_of = [](int s) { return s + 1 == S ? 0 : s + 1; };
     int t = 0;
-    // steady state: stores, loads and a next tile exist for both halves of the trip
-    while (t + S + 2 < T) {
-        htile_iter<Cfg, 0, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off);
-        cs = next_of(cs);
-        fill = next_of(fill);
+    if (T > S + 2) {
+        // Long K range.  Everything in the prologue is unconditional, so that on every path into the
+        // steady loop the loads in flight are the same two groups in the same order and the waits
+        // before the LDS stores can leave the younger group in flight.
+#pragma unroll
+        for (int s = 0; s < S - 1; ++s) {
+            load_all(Slot0());
+            store_all(smem + s * Cfg::STAGE_HALVES);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        load_all(Slot0());
+        __builtin_amdgcn_sched_barrier(0);  // keep the two groups in issue order
+        load_all(Slot1());
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        htile_iter<Cfg, 1, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off);
-        cs = next_of(cs);
-        fill = next_of(fill);
+        first_frags();
+        // Two tiles per trip (register sets 0 and 1); LDS stages by pointer.
+        while (t + S + 2 < T) {
+            htile_iter<Cfg, 0, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off);
+            cs = next_of(cs);
+            fill = next_of(fill);
+            __syncthreads();
+            htile_iter<Cfg, 1, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off);
+            cs = next_of(cs);
+            fill = next_of(fill);
+            __syncthreads();
+            t += 2;
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < S - 1; ++s) {
+            if (s < T) {
+                load_all(Slot0());
+                store_all(smem + s * Cfg::STAGE_HALVES);
+            }
+        }
+        if (S - 1 < T) load_all(Slot0());
+        if (S < T) load_all(Slot1());
         __syncthreads();
-        t += 2;
+        if (T > 0) first_frags();
     }
     // first and last tiles of the range: the same iterations with their conditions
     for (; t < T; t += 2) {
@@ -375,6 +398,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
     }
     if (!combine_slices<Cfg>(acc, g.split, w)) return;
     hstore_tile<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
+        g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
+    }
 }
 
 template <class Cfg>
@@ -398,6 +425,7 @@ struct HCfgDesc {
     int BM, BN, BK, NT, lds_bytes;
     int (*launch)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);
 };
-const HCfgDesc &hcfg_desc();  // defined in hgemm_instance.hip
+constexpr int kNumHCfg = 2;
+const HCfgDesc &hcfg_desc(int i);  // defined in hgemm_instance.hip
 
 }  // namespace dmath
