@@ -47,6 +47,10 @@ def _load():
         lib.oracle_hgemm.restype = ctypes.c_int
         lib.oracle_hgemm.argtypes = [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _dbl, _hp, _i64, _hp, _i64, _dbl,
                                      _hp, _i64, _i64, _ip, _ip, _dp, _dp]
+        lib.oracle_dgemm.restype = ctypes.c_int
+        lib.oracle_dgemm.argtypes = [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _dbl, _dp, _i64, _dp, _i64, _dbl,
+                                     _dp, _i64, _i64, _ip, _ip, _dp, _dp]
+        lib.oracle_long_double_digits.restype = ctypes.c_int
         lib.oracle_conv2d_fwd.restype = ctypes.c_int
         lib.oracle_conv2d_fwd.argtypes = [_i64] * 11 + [_dbl, _fp, _fp, _dbl, _fp, _dp, _dp]
         lib.oracle_conv2d_fwd_points.restype = ctypes.c_int
@@ -220,6 +224,58 @@ def hgemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta=0.0, C0=None, ldc
                               ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
     if rc != 0:
         raise RuntimeError("oracle_hgemm rejected its arguments")
+    return ref, mag
+
+
+def _f64(a, name):
+    if a is None:
+        return None
+    a = np.asarray(a)
+    if a.dtype != np.float64 or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError("%s must be a C-contiguous float64 array" % name)
+    return a
+
+
+def _dptr(a):
+    return ctypes.cast(None, _dp) if a is None else a.ctypes.data_as(_dp)
+
+
+def long_double_digits():
+    """Significand bits of the type the FP64 oracle accumulates in (64 on x86-64)."""
+    return _load().oracle_long_double_digits()
+
+
+def double_bound(K, mag):
+    """Acceptance bound for FP64 results: the FP32 contract with the FP64 unit roundoff,
+    4*K*2^-53*mag + 2^-49."""
+    return 4.0 * K * 2.0 ** -53 * mag + 2.0 ** -49
+
+
+def dgemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta=0.0, C0=None, ldc=None, pi=None, pj=None):
+    """ref, mag (float64, accumulated in long double) of alpha*op(A)*op(B) + beta*C0 for float64 arrays."""
+    ldc = N if ldc is None else ldc
+    A, B, C0 = _f64(A, "A"), _f64(B, "B"), _f64(C0, "C0")
+    if alpha != 0.0:
+        _need(A, _extent(K, M, lda) if transA else _extent(M, K, lda), "A")
+        _need(B, _extent(N, K, ldb) if transB else _extent(K, N, ldb), "B")
+    if beta != 0.0:
+        _need(C0, _extent(M, N, ldc), "C0")
+    if pi is None:
+        shape, npts = (M, N), 0
+        ip = jp = ctypes.cast(None, _ip)
+    else:
+        pi = np.ascontiguousarray(pi, dtype=np.int64)
+        pj = np.ascontiguousarray(pj, dtype=np.int64)
+        assert pi.shape == pj.shape and pi.ndim == 1
+        shape, npts = pi.shape, pi.size
+        ip, jp = pi.ctypes.data_as(_ip), pj.ctypes.data_as(_ip)
+    ref = np.empty(shape, dtype=np.float64)
+    mag = np.empty(shape, dtype=np.float64)
+    rc = _load().oracle_dgemm(int(bool(transA)), int(bool(transB)), M, N, K, float(alpha), _dptr(A), lda, _dptr(B),
+                              ldb, float(beta), _dptr(C0), ldc, npts, ip, jp,
+                              ref.ctypes.data_as(_dp), mag.ctypes.data_as(_dp))
+    if rc != 0:
+        raise RuntimeError("oracle_dgemm rejected its arguments")
     return ref, mag
 
 

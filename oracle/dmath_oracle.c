@@ -304,6 +304,60 @@ int oracle_hgemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
     return 0;
 }
 
+/*
+ * Double-precision GEMM (section "Precisions": single and double precision are
+ * the library's nominal precisions).  Inputs are FP64; to stand above the
+ * arithmetic it checks, every product and sum is carried in long double (the
+ * x87 80-bit format here: 64-bit significand, so the accumulated rounding error
+ * is 2^-11 of what FP64 accumulation of the same terms may commit), and rounded
+ * to double once at the end.  mag is the same sum over absolute values.
+ *
+ *     ref[i][j] = alpha * sum_k opA(i,k) * opB(k,j) + beta * C0[i][j]
+ *
+ * pi == NULL: all M x N elements (row stride N); else the npts positions.
+ */
+int oracle_dgemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                 double alpha, const double *A, int64_t lda,
+                 const double *B, int64_t ldb,
+                 double beta, const double *C0, int64_t ldc,
+                 int64_t npts, const int64_t *pi, const int64_t *pj,
+                 double *ref, double *mag)
+{
+    if (M < 0 || N < 0 || K < 0 || npts < 0 || !ref) return 1;
+    if (beta != 0.0 && !C0 && M > 0 && N > 0) return 1;
+    const int product = alpha != 0.0 && K > 0 && M > 0 && N > 0;
+    if (product && (!A || !B)) return 1;
+    const int64_t total = pi ? npts : M * N;
+    if (pi)
+        for (int64_t t = 0; t < npts; ++t)
+            if (pi[t] < 0 || pi[t] >= M || pj[t] < 0 || pj[t] >= N) return 1;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t t = 0; t < total; ++t) {
+        const int64_t i = pi ? pi[t] : t / N, j = pi ? pj[t] : t % N;
+        long double s = 0.0L, m = 0.0L;
+        if (product) {
+            for (int64_t k = 0; k < K; ++k) {
+                const long double a = transA ? A[k * lda + i] : A[i * lda + k];
+                const long double b = transB ? B[j * ldb + k] : B[k * ldb + j];
+                s += a * b;
+                m += fabsl(a) * fabsl(b);
+            }
+        }
+        long double r = product ? (long double)alpha * s : 0.0L;
+        long double g = product ? fabsl((long double)alpha) * m : 0.0L;
+        if (beta != 0.0) {
+            const long double c0 = C0[i * ldc + j];
+            r += (long double)beta * c0;
+            g += fabsl((long double)beta) * fabsl(c0);
+        }
+        ref[t] = (double)r;
+        if (mag) mag[t] = (double)g;
+    }
+    return 0;
+}
+
+int oracle_long_double_digits(void) { return __LDBL_MANT_DIG__; }
+
 static inline int64_t conv_out_dim(int64_t in, int64_t pad, int64_t filt, int64_t stride)
 {
     const int64_t span = in + 2 * pad - filt;

@@ -439,6 +439,79 @@ def test_half_bound_formula():
     assert np.allclose(got, want, rtol=1e-15, atol=0)
 
 
+# ----------------------------------------------------------------------------- double precision
+
+def test_dgemm_accumulates_wider_than_double():
+    assert oracle.long_double_digits() >= 64
+    # 2^60 + 1 - 2^60 summed left to right: FP64 accumulation loses the 1, the oracle must not
+    A = np.array([[2.0 ** 60, 1.0, -2.0 ** 60]])
+    B = np.ones((3, 1))
+    ref, mag = oracle.dgemm(0, 0, 1, 1, 3, 1.0, A, 3, B, 1)
+    assert ref[0, 0] == 1.0
+    assert mag[0, 0] == 2.0 ** 61      # 2^61 + 1 rounded to double
+    # products are exact too: (1 + 2^-30)^2 - 1 - 2^-29 = 2^-60, lost by FP64 products
+    x = 1.0 + 2.0 ** -30
+    A = np.array([[x, -1.0, -2.0 ** -29]])
+    B = np.array([[x], [1.0], [1.0]])
+    ref, _ = oracle.dgemm(0, 0, 1, 1, 3, 1.0, A, 3, B, 1)
+    assert ref[0, 0] == 2.0 ** -60
+
+
+@pytest.mark.parametrize("tA,tB", list(itertools.product((0, 1), (0, 1))))
+def test_dgemm_matches_exact_rational_arithmetic(tA, tB):
+    from fractions import Fraction
+    rng = np.random.default_rng(60 + 2 * tA + tB)
+    M, N, K = 4, 5, 9
+    A = rng.standard_normal((M, K))
+    B = rng.standard_normal((K, N))
+    C0 = rng.standard_normal((M, N))
+    alpha, beta = -1.25, 0.5
+    a, lda = np.ascontiguousarray(A.T if tA else A), (M if tA else K)
+    b, ldb = np.ascontiguousarray(B.T if tB else B), (K if tB else N)
+    ref, mag = oracle.dgemm(tA, tB, M, N, K, alpha, a, lda, b, ldb, beta, C0, N)
+    for i in range(M):
+        for j in range(N):
+            exact = Fraction(alpha) * sum(Fraction(A[i, k]) * Fraction(B[k, j]) for k in range(K)) \
+                + Fraction(beta) * Fraction(C0[i, j])
+            emag = abs(Fraction(alpha)) * sum(abs(Fraction(A[i, k])) * abs(Fraction(B[k, j])) for k in range(K)) \
+                + abs(Fraction(beta)) * abs(Fraction(C0[i, j]))
+            # long-double accumulation of 9 terms, then one rounding to double
+            tol = float(emag) * (2.0 ** -53 + 12 * 2.0 ** -64)
+            assert abs(Fraction(ref[i, j]) - exact) <= Fraction(tol), (i, j)
+            assert abs(Fraction(mag[i, j]) - emag) <= Fraction(tol), (i, j)
+
+
+def test_dgemm_integer_exact_leading_dimensions_and_conventions():
+    rng = np.random.default_rng(9)
+    M, N, K = 11, 7, 40
+    A = rng.integers(-1000, 1001, size=(M, K))
+    B = rng.integers(-1000, 1001, size=(K, N))
+    want = (A @ B).astype(np.float64)
+    a = np.full((M, K + 3), np.nan)
+    a[:, :K] = A
+    b = np.full((K, N + 2), np.nan)
+    b[:, :N] = B
+    ref, _ = oracle.dgemm(0, 0, M, N, K, 1.0, a, K + 3, b, N + 2)
+    assert np.array_equal(ref, want)
+    at = np.ascontiguousarray(A.T.astype(np.float64))
+    bt = np.ascontiguousarray(B.T.astype(np.float64))
+    ref, _ = oracle.dgemm(1, 1, M, N, K, 2.0, at, M, bt, K, -1.0, want.copy(), N)
+    assert np.array_equal(ref, want)                       # 2*AB - AB
+    pts, _ = oracle.dgemm(1, 1, M, N, K, 2.0, at, M, bt, K, -1.0, want.copy(), N, pi=[10, 0], pj=[6, 3])
+    assert np.array_equal(pts, want[[10, 0], [6, 3]])
+    nanC = np.full((M, N), np.nan)
+    ref, _ = oracle.dgemm(0, 0, M, N, K, 1.0, A.astype(np.float64), K, B.astype(np.float64), N, 0.0, nanC, N)
+    assert np.array_equal(ref, want)
+    ref, _ = oracle.dgemm(0, 0, M, N, K, 0.0, np.full((M, K), np.nan), K, np.full((K, N), np.nan), N, 3.0, want, N)
+    assert np.array_equal(ref, 3.0 * want)
+
+
+def test_double_bound_formula():
+    mag = np.array([0.0, 1.0, 1e6])
+    got = oracle.double_bound(1000, mag)
+    assert np.allclose(got, 4000 * 2.0 ** -53 * mag + 2.0 ** -49, rtol=1e-15, atol=0)
+
+
 def _conv_brute(x, w, pad, stride):
     """Second, independent statement of the definition: python loops in float64."""
     N, C, H, W = x.shape
