@@ -25,6 +25,8 @@ if ROOT not in sys.path:
 
 # Published MI355X peaks used as roofline denominators.
 PEAK_FP32_MFMA_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 64 flop/clk x 2.4 GHz
+PEAK_FP16_MFMA_TFLOPS = 2500.0  # dense FP16-input matrix instruction, FP32 accumulate
+PEAK_FP64_MFMA_TFLOPS = 78.6
 PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by
@@ -44,7 +46,7 @@ MEASURED_HBM_TRAFFIC_BYTES = {
 }
 
 WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv", "conv_bwd_data", "conv_bwd_filter", "summa_fused",
-             "fc_nn", "fc_nt", "fc_tn", "hgemm4096", "fc_half")
+             "fc_nn", "fc_nt", "fc_tn", "hgemm4096", "fc_half", "dgemm4096")
 
 
 def _device_arrays(torch, arrays):
@@ -194,7 +196,7 @@ def main():
         wl = {"gemm4096": workloads.config2, "gemm256": workloads.config1, "summa": workloads.config3,
               "summa_fused": workloads.config3, "fc": workloads.config4, "fc_nn": workloads.config4,
               "fc_nt": workloads.config4, "fc_tn": workloads.config4, "hgemm4096": workloads.config2,
-              "fc_half": workloads.config4}[args.workload]()
+              "fc_half": workloads.config4, "dgemm4096": workloads.config2}[args.workload]()
         half = args.workload in ("hgemm4096", "fc_half")   # the same operands rounded to half-precision storage
         if half:
             wl.arrays = {k: v.astype(np.float16) for k, v in wl.arrays.items()}
@@ -202,6 +204,10 @@ def main():
         if args.workload in ("fc_nn", "fc_nt", "fc_tn"):   # one of the three products of the layer alone
             wl.calls = [wl.calls[("fc_nn", "fc_nt", "fc_tn").index(args.workload)]]
             wl.name += "_" + args.workload[3:]
+        double = args.workload == "dgemm4096"          # the same operands widened to FP64
+        if double:
+            wl.arrays = {k: v.astype(np.float64) for k, v in wl.arrays.items()}
+            wl.name += "_fp64"
         dev = _device_arrays(torch, wl.arrays)
         calls = [(c, dev[c.A], dev[c.B], dev[c.C]) for c in wl.calls]
         fused = args.workload == "summa_fused"   # the same update sequence as one multi-panel call
@@ -212,12 +218,12 @@ def main():
                 dm.check(dm.dmath_gemm_panels(c.transA, c.transB, c.M, c.N, c.K, c.alpha, [x[1] for x in calls], c.lda,
                                               [x[2] for x in calls], c.ldb, c.beta, calls[0][3], c.ldc))
                 return
-            gemm = dm.dmath_hgemm if half else dm.dmath_gemm
+            gemm = dm.dmath_hgemm if half else dm.dmath_dgemm if double else dm.dmath_gemm
             for c, a, b, cc in calls:
                 dm.check(gemm(c.transA, c.transB, c.M, c.N, c.K, c.alpha, a, c.lda, b, c.ldb, c.beta, cc, c.ldc))
 
         flop = wl.flop
-        alg_bytes = sum(c.algorithmic_bytes for c in wl.calls) // (2 if half else 1)
+        alg_bytes = sum(c.algorithmic_bytes for c in wl.calls) // (2 if half else 1) * (2 if double else 1)
         launches = len(wl.calls)
         wl_name = wl.name
         if fused:   # all panels read once, C read and written once
@@ -245,7 +251,7 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        if args.workload in ("hgemm4096", "fc_half"):
+        if args.workload in ("hgemm4096", "fc_half", "dgemm4096"):
             cpu_baseline = None   # the FP32 workloads of the same shapes carry the oracle timing
         elif conv is not None and args.workload != "conv":
             cpu_baseline = None   # the forward workload carries the oracle timing of this layer
@@ -257,9 +263,15 @@ def main():
     # Dominant kernel: the MFMA tile kernel.  The headline workload is one launch of it per step, so its
     # mean duration is the event time per step; for multi-call workloads this is the aggregate rate.
     achieved = tflops
+    # each contraction is priced against the matrix peak of its own input type
+    peak, dtype = PEAK_FP32_MFMA_TFLOPS, "f32"
+    if args.workload in ("hgemm4096", "fc_half"):
+        peak, dtype = PEAK_FP16_MFMA_TFLOPS, "f16"     # half storage, exact products, FP32 accumulation
+    elif args.workload == "dgemm4096":
+        peak, dtype = PEAK_FP64_MFMA_TFLOPS, "f64"
     roofline = {
-        "bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-        "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+        "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+        "frac": achieved / peak,
         "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(args.workload),
         "algorithmic_bytes_per_step": alg_bytes,
         "algorithmic_GBps": alg_bytes / ms_ev / 1e6,
@@ -267,18 +279,20 @@ def main():
     }
     line = {
         "metric": "FP32 GEMM TFLOP/s at 4096^3 on 1 MI355X; % of FP32 MFMA peak" if args.workload == "gemm4096"
-                  else "FP32 TFLOP/s on workload %s on 1 MI355X" % wl_name,
+                  else "%s TFLOP/s on workload %s on 1 MI355X" % ({"f32": "FP32", "f16": "FP16-storage / FP32-accumulate",
+                                                                   "f64": "FP64"}[dtype], wl_name),
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_ev, "ms_per_step_host_clock": ms_wall, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": wl_name, "launches_per_step": launches, "flop_per_step": flop,
                    "tile_config": dm.dmath_config_name(args.tile_config) if args.tile_config >= 0 else "auto",
                    "library": dm.dmath_version()},
-        "pct_of_fp32_mfma_peak": 100.0 * tflops / PEAK_FP32_MFMA_TFLOPS,
+        "pct_of_fp32_mfma_peak": 100.0 * tflops / peak if dtype == "f32" else None,
+        "pct_of_mfma_peak": 100.0 * tflops / peak,
         "measured_shader_clock_ghz": measured_clock_ghz,
-        "pct_of_fp32_mfma_peak_at_measured_clock":
+        "pct_of_mfma_peak_at_measured_clock":
             None if not measured_clock_ghz
-            else 100.0 * tflops / (PEAK_FP32_MFMA_TFLOPS * measured_clock_ghz["mean"] / 2.4),
+            else 100.0 * tflops / (peak * measured_clock_ghz["mean"] / 2.4),
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "paper_context": "dMath paper, table 'Matrix Multiplication Performance': N=4096 on one K80 GPU with "

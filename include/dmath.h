@@ -111,6 +111,22 @@ dmath_status dmath_hgemm(dmath_op transA, dmath_op transB,
 dmath_status dmath_set_hgemm_path(int path);
 
 /*
+ * The same multiply in double precision (section "Precisions": single and double precision are the
+ * library's two nominal precisions): A, B, C, alpha and beta are FP64, products and sums are FP64 on
+ * the double-precision matrix instruction.  Layout conventions, quick returns and error codes as for
+ * dmath_gemm; any 8-byte aligned pointers and any legal leading dimensions are accepted.  There is no
+ * split-K: a product with few output tiles runs on few compute units.  dmath_set_dgemm_config forces
+ * one of the two tile configurations (0: 256 x 128, 1: 128 x 128; -1 automatic) for this thread.
+ */
+dmath_status dmath_dgemm(dmath_op transA, dmath_op transB,
+                         int64_t M, int64_t N, int64_t K,
+                         double alpha, const double *A, int64_t lda,
+                         const double *B, int64_t ldb,
+                         double beta, double *C, int64_t ldc,
+                         void *stream);
+dmath_status dmath_set_dgemm_config(int tile_config);
+
+/*
  * Accumulating sequence of block multiplies in one call (section "Matrix Multiplication": a worker's
  * block of C is the sum, over the stages, of products of the A and B blocks it holds at that stage;
  * section "Memory Management" and figure "cyclic_gemm_cache_fwd": with the blocks cached on the

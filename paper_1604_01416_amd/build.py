@@ -1,6 +1,6 @@
 """Build libdmath.so (the C-ABI library of include/dmath.h) for gfx950 with hipcc.
 
-One object per tile configuration, one for the FP16-input kernels, plus the API object, compiled in parallel, linked in-tree
+One object per tile configuration, one each for the FP16-input and the FP64 kernels, plus the API object, compiled in parallel, linked in-tree
 into ``paper_1604_01416_amd/libdmath.so``.  hipcc cross-compiles without a GPU.
 Run as ``python -m paper_1604_01416_amd.build``.
 """
@@ -49,7 +49,8 @@ def build(force: bool = True, jobs: int = 8, verbose: bool = False) -> str:
         return LIB
     os.makedirs(OBJ, exist_ok=True)
     work = [(os.path.join(CSRC, "dmath_api.hip"), os.path.join(OBJ, "dmath_api.o"), []),
-            (os.path.join(CSRC, "hgemm_instance.hip"), os.path.join(OBJ, "hgemm_instance.o"), [])]
+            (os.path.join(CSRC, "hgemm_instance.hip"), os.path.join(OBJ, "hgemm_instance.o"), []),
+            (os.path.join(CSRC, "dgemm_instance.hip"), os.path.join(OBJ, "dgemm_instance.o"), [])]
     for i in range(num_configs()):
         work.append((os.path.join(CSRC, "tile_instance.hip"), os.path.join(OBJ, "tile_%d.o" % i),
                      ["-DDMATH_CFG_INDEX=%d" % i]))

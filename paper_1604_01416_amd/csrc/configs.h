@@ -6,6 +6,7 @@
 #include "gemm_kernel.h"
 #include "gemm_panels_kernel.h"
 #include "hgemm_kernel.h"
+#include "dgemm_kernel.h"
 
 namespace dmath {
 

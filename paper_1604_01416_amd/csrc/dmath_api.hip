@@ -20,7 +20,8 @@ struct ThreadState {
     size_t ws_bytes = 0;
     int force_cfg = -1;
     int force_split = -1;
-    int hgemm_path = -1;  // -1 automatic, 0 FP32 matrix instruction on widened operands, 1 FP16-input instruction
+    int hgemm_path = -1;
+    int dgemm_cfg = -1;   // -1 automatic, else index of the FP64 tile configuration  // -1 automatic, 0 FP32 matrix instruction on widened operands, 1 FP16-input instruction
     int last_error_arg = 0;
     unsigned long long *clock_probe = nullptr;
 };
@@ -55,6 +56,16 @@ __global__ void scale_kernel(float *C, int64_t ldc, int64_t M, int64_t N, float 
         const int64_t row = e / N, col = e - row * N;
         float *dst = C + row * ldc + col;
         *dst = (beta == 0.0f) ? 0.0f : beta * *dst;
+    }
+}
+
+__global__ void scale_kernel_f64(double *C, int64_t ldc, int64_t M, int64_t N, double beta)
+{
+    const int64_t total = M * N;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = e / N, col = e - row * N;
+        double *dst = C + row * ldc + col;
+        *dst = (beta == 0.0) ? 0.0 : beta * *dst;
     }
 }
 
@@ -553,6 +564,75 @@ dmath_status dmath_hgemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N,
     return gemm_entry<_Float16>(transA, transB, M, N, K, alpha, reinterpret_cast<const _Float16 *>(A), lda,
                                 reinterpret_cast<const _Float16 *>(B), ldb, beta, reinterpret_cast<_Float16 *>(C), ldc,
                                 stream_);
+}
+
+dmath_status dmath_dgemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, double alpha,
+                         const double *A, int64_t lda, const double *B, int64_t ldb, double beta, double *C,
+                         int64_t ldc, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (transA != DMATH_OP_N && transA != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (transB != DMATH_OP_N && transB != DMATH_OP_T) return fail(DMATH_ERR_INVALID_ARG, 2);
+    if (M < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
+    if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
+    if (K < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
+    const bool a_k = (transA == DMATH_OP_N), b_k = (transB == DMATH_OP_T);
+    const int64_t a_cols = a_k ? K : M, b_cols = b_k ? K : N;
+    if (lda < (a_cols > 1 ? a_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 8);
+    if (ldb < (b_cols > 1 ? b_cols : 1)) return fail(DMATH_ERR_INVALID_ARG, 10);
+    if (ldc < (N > 1 ? N : 1)) return fail(DMATH_ERR_INVALID_ARG, 13);
+    if (M == 0 || N == 0) return DMATH_OK;
+    if (C == nullptr) return fail(DMATH_ERR_NULL_PTR, 12);
+    const bool no_product = (K == 0 || alpha == 0.0);
+    if (!no_product) {
+        if (A == nullptr) return fail(DMATH_ERR_NULL_PTR, 7);
+        if (B == nullptr) return fail(DMATH_ERR_NULL_PTR, 9);
+    }
+    if (M > (int64_t)1 << 40 || N > (int64_t)1 << 40 || K > (int64_t)1 << 33) return fail(DMATH_ERR_UNSUPPORTED, 3);
+    if (no_product) {
+        if (beta == 1.0) return DMATH_OK;
+        const int64_t total = M * N;
+        const int blocks = (int)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
+        hipLaunchKernelGGL(scale_kernel_f64, dim3(blocks), dim3(256), 0, stream, C, ldc, M, N, beta);
+        return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
+    }
+    // the large tile once it fills the compute units most of a round, else the small one
+    int cfg = g_state.dgemm_cfg;
+    if (cfg < 0) cfg = ceil_div(M, dcfg_desc(0).BM) * ceil_div(N, dcfg_desc(0).BN) >= (kNumCU * 3) / 4 ? 0 : 1;
+    const DCfgDesc &d = dcfg_desc(cfg);
+    const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
+    if (tiles_m * tiles_n > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
+    DGemmArgs g;
+    g.A = A;
+    g.B = B;
+    g.C = C;
+    g.lda = lda;
+    g.ldb = ldb;
+    g.ldc = ldc;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.alpha = 0.0f;  // the FP64 scalars travel in their own argument
+    g.beta = 0.0f;
+    g.tiles_m = (int)tiles_m;
+    g.tiles_n = (int)tiles_n;
+    g.cvec = 0;
+    g.split.dp_tiles = (int)(tiles_m * tiles_n);
+    g.split.splits = 1;
+    g.split.partials = nullptr;
+    g.split.counters = nullptr;
+    g.split.plain = 0;
+    g.split.slice_stride = 0;
+    g.clock_probe = nullptr;
+    if (d.launch(g, alpha, beta, a_k, b_k, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    return DMATH_OK;
+}
+
+dmath_status dmath_set_dgemm_config(int tile_config)
+{
+    if (tile_config < -1 || tile_config >= kNumDCfg) return fail(DMATH_ERR_INVALID_ARG, 1);
+    g_state.dgemm_cfg = tile_config;
+    return DMATH_OK;
 }
 
 dmath_status dmath_gemm_panels(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, int64_t npanels,

@@ -15,7 +15,7 @@ OK, ERR_INVALID_ARG, ERR_NULL_PTR, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_WORKSPACE = 
 OP_N, OP_T = 0, 1
 
 EXPORTS = (
-    "dmath_gemm", "dmath_conv2d_fwd", "dmath_conv2d_bwd_data", "dmath_conv2d_bwd_filter", "dmath_gemm_panels", "dmath_hgemm", "dmath_set_hgemm_path", "dmath_gemm_workspace_bytes", "dmath_set_workspace",
+    "dmath_gemm", "dmath_conv2d_fwd", "dmath_conv2d_bwd_data", "dmath_conv2d_bwd_filter", "dmath_gemm_panels", "dmath_hgemm", "dmath_set_hgemm_path", "dmath_dgemm", "dmath_set_dgemm_config", "dmath_gemm_workspace_bytes", "dmath_set_workspace",
     "dmath_set_override", "dmath_set_clock_probe", "dmath_gemm_plan", "dmath_num_configs", "dmath_config_name", "dmath_last_error_arg",
     "dmath_status_string", "dmath_version",
 )
@@ -36,6 +36,11 @@ _lib.dmath_conv2d_bwd_data.restype = _int
 _lib.dmath_conv2d_bwd_data.argtypes = [_i64] * 11 + [_f32, _vp, _vp, _f32, _vp, _vp]
 _lib.dmath_hgemm.restype = _int
 _lib.dmath_hgemm.argtypes = [_int, _int, _i64, _i64, _i64, _f32, _vp, _i64, _vp, _i64, _f32, _vp, _i64, _vp]
+_lib.dmath_dgemm.restype = _int
+_lib.dmath_dgemm.argtypes = [_int, _int, _i64, _i64, _i64, ctypes.c_double, _vp, _i64, _vp, _i64, ctypes.c_double, _vp,
+                             _i64, _vp]
+_lib.dmath_set_dgemm_config.restype = _int
+_lib.dmath_set_dgemm_config.argtypes = [_int]
 _lib.dmath_set_hgemm_path.restype = _int
 _lib.dmath_set_hgemm_path.argtypes = [_int]
 _lib.dmath_gemm_panels.restype = _int
@@ -100,6 +105,16 @@ def dmath_hgemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, st
     """A, B, C: float16 device tensors (or addresses of binary16 data)."""
     return _lib.dmath_hgemm(transA, transB, M, N, K, alpha, _addr(A), lda, _addr(B), ldb, beta, _addr(C), ldc,
                             _stream(stream))
+
+
+def dmath_dgemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=None):
+    """A, B, C: float64 device tensors."""
+    return _lib.dmath_dgemm(transA, transB, M, N, K, alpha, _addr(A), lda, _addr(B), ldb, beta, _addr(C), ldc,
+                            _stream(stream))
+
+
+def dmath_set_dgemm_config(tile_config):
+    return _lib.dmath_set_dgemm_config(tile_config)
 
 
 def dmath_set_hgemm_path(path):

@@ -136,6 +136,58 @@ def run_hgemm_case(dm, torch, tA, tB, M, N, K, alpha=1.0, beta=0.0, ld_extra=(0,
     return float((err / bnd).max())
 
 
+def run_dgemm_case(dm, torch, tA, tB, M, N, K, alpha=1.0, beta=0.0, ld_extra=(0, 0, 0), lead=(0, 0, 0), seed=0,
+                   ints=False, exact=False):
+    """One dmath_dgemm call against the long-double oracle, NaN guard frames around every operand."""
+    rng = np.random.default_rng(seed)
+    if ints:
+        A = rng.integers(-1000, 1001, size=(M, K)).astype(np.float64)
+        B = rng.integers(-1000, 1001, size=(K, N)).astype(np.float64)
+        C0 = rng.integers(-1000, 1001, size=(M, N)).astype(np.float64)
+    else:
+        A = rng.uniform(-1, 1, (M, K))
+        B = rng.uniform(-1, 1, (K, N))
+        C0 = rng.standard_normal((M, N))
+    if beta == 0.0:
+        C0[:] = np.nan
+
+    def put(op_matrix, trans, extra, ld0):
+        m = np.ascontiguousarray(op_matrix.T if trans else op_matrix)
+        rows, cols = m.shape
+        ld = max(1, cols + extra)
+        flat = np.full(ld0 + rows * ld + 8, np.nan)
+        flat[ld0:ld0 + rows * ld].reshape(rows, ld)[:, :cols] = m
+        return flat, ld
+
+    a_flat, lda = put(A, tA, ld_extra[0], lead[0])
+    b_flat, ldb = put(B, tB, ld_extra[1], lead[1])
+    c_flat, ldc = put(C0, 0, ld_extra[2], lead[2])
+    dA, dB, dC = (torch.from_numpy(f).cuda() for f in (a_flat, b_flat, c_flat))
+    st = dm.dmath_dgemm(tA, tB, M, N, K, alpha, dA[lead[0]:], lda, dB[lead[1]:], ldb, beta, dC[lead[2]:], ldc)
+    assert st == dm.OK, (dm.dmath_status_string(st), dm.dmath_last_error_arg())
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    ref, mag = oracle.dgemm(tA, tB, M, N, K, alpha, a_flat[lead[0]:], lda, b_flat[lead[1]:], ldb, beta,
+                            c_flat[lead[2]:] if beta != 0.0 else None, ldc)
+    c_off = lead[2]
+    got = out[c_off:c_off + M * ldc].reshape(M, ldc) if M > 0 else np.zeros((0, ldc))
+    if M > 0:
+        assert np.isnan(got[:, N:]).all(), "row padding of C was written"
+    assert np.isnan(out[:c_off]).all() and np.isnan(out[c_off + M * ldc:]).all(), "wrote outside C"
+    if M == 0 or N == 0:
+        return 0.0
+    g = got[:, :N]
+    if exact:
+        assert np.array_equal(g, ref), "integer case must be bit-exact"
+        return 0.0
+    err = np.abs(g - ref)
+    bnd = oracle.double_bound(max(K, 1), mag)
+    bad = ~(err <= bnd)
+    assert not bad.any(), "dgemm t%d%d %dx%dx%d: %d elements outside the bound, first %s err %s bound %s" % (
+        tA, tB, M, N, K, int(bad.sum()), np.argwhere(bad)[:3].tolist(), err[bad][:3], bnd[bad][:3])
+    return float((err / bnd).max())
+
+
 def run_gemm_panels_case(dm, torch, tA, tB, M, N, K, P, alpha=1.0, beta=0.0, ld_extra=(0, 0, 0), lead=(0, 0, 0),
                          seed=0, ints=False, exact=False):
     """One dmath_gemm_panels call over P panels against the oracle's sum of products."""

@@ -14,7 +14,7 @@ import pytest
 
 import oracle
 from paper_1604_01416_amd import workloads
-from parity_util import check_bound, run_conv_bwd_data_case, run_conv_bwd_filter_case, run_conv_case, run_gemm_case, run_gemm_panels_case, run_hgemm_case
+from parity_util import check_bound, run_conv_bwd_data_case, run_conv_bwd_filter_case, run_conv_case, run_dgemm_case, run_gemm_case, run_gemm_panels_case, run_hgemm_case
 
 pytestmark = pytest.mark.gpu
 
@@ -41,9 +41,11 @@ def dm(torch):
 def _auto_plan(dm):
     dm.dmath_set_override(-1, -1)
     dm.dmath_set_hgemm_path(-1)
+    dm.dmath_set_dgemm_config(-1)
     yield
     dm.dmath_set_override(-1, -1)
     dm.dmath_set_hgemm_path(-1)
+    dm.dmath_set_dgemm_config(-1)
 
 
 TRANS = list(itertools.product((0, 1), (0, 1)))
@@ -730,3 +732,52 @@ def test_hgemm_paths_agree_on_integers(dm, torch):
     torch.cuda.synchronize()
     assert torch.equal(out[0], out[1]) and torch.equal(out[0], out[2])
     assert torch.equal(out[0].double(), A.double() @ B.double())
+
+
+# ------------------------------------------------------------------ double precision
+
+@pytest.mark.parametrize("tA,tB", TRANS)
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_dgemm_small(dm, torch, tA, tB, cfg):
+    dm.dmath_set_dgemm_config(cfg)
+    run_dgemm_case(dm, torch, tA, tB, 300, 260, 150, seed=1 + 2 * tA + tB, ld_extra=(3, 1, 2))      # ragged everything
+    run_dgemm_case(dm, torch, tA, tB, 129, 67, 45, alpha=-0.5, beta=2.0, seed=7, lead=(1, 1, 1))      # 8-byte aligned only
+    run_dgemm_case(dm, torch, tA, tB, 260, 515, 64, ints=True, exact=True, beta=1.0, seed=3)
+    run_dgemm_case(dm, torch, tA, tB, 1, 1, 1, seed=4)
+    run_dgemm_case(dm, torch, tA, tB, 17, 9, 5, seed=8)                                             # K below one tile
+    run_dgemm_case(dm, torch, tA, tB, 33, 20, 0, beta=0.5, seed=5)                                  # K == 0
+    run_dgemm_case(dm, torch, tA, tB, 33, 20, 16, alpha=0.0, beta=0.0, seed=6)
+    run_dgemm_case(dm, torch, tA, tB, 0, 20, 16, seed=6)
+
+
+@pytest.mark.parametrize("K", [16, 32, 48, 64, 80, 100])
+def test_dgemm_k_ranges(dm, torch, K):
+    run_dgemm_case(dm, torch, 0, 0, 256, 256, K, ints=True, exact=True, seed=K)
+    run_dgemm_case(dm, torch, 1, 1, 256, 256, K, beta=-1.0, seed=K + 1)
+
+
+def test_dgemm_validation(dm, torch):
+    t = torch.zeros(64, dtype=torch.float64, device="cuda")
+    assert dm.dmath_dgemm(0, 0, 4, 4, 4, 1.0, t, 3, t, 4, 0.0, t, 4) == dm.ERR_INVALID_ARG and dm.dmath_last_error_arg() == 8
+    assert dm.dmath_dgemm(0, 0, 4, 4, 4, 1.0, None, 4, t, 4, 0.0, t, 4) == dm.ERR_NULL_PTR and dm.dmath_last_error_arg() == 7
+    assert dm.dmath_dgemm(2, 0, 4, 4, 4, 1.0, t, 4, t, 4, 0.0, t, 4) == dm.ERR_INVALID_ARG
+    assert dm.dmath_set_dgemm_config(2) == dm.ERR_INVALID_ARG
+
+
+def test_dgemm_2048_sampled(dm, torch):
+    n = 2048
+    rng = np.random.default_rng(31)
+    A, B = rng.uniform(-1, 1, (n, n)), rng.uniform(-1, 1, (n, n))
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dC = torch.full((n, n), float("nan"), dtype=torch.float64, device="cuda")
+    dm.check(dm.dmath_dgemm(0, 0, n, n, n, 1.0, dA, n, dB, n, 0.0, dC, n))
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    assert np.isfinite(got).all()
+    pi = np.concatenate([rng.integers(0, n, 20000), np.full(n, n - 1), np.arange(n)])
+    pj = np.concatenate([rng.integers(0, n, 20000), np.arange(n), np.zeros(n, dtype=np.int64)])
+    ref, mag = oracle.dgemm(0, 0, n, n, n, 1.0, A, n, B, n, pi=pi, pj=pj)
+    err = np.abs(got[pi, pj] - ref)
+    bnd = oracle.double_bound(n, mag)
+    assert (err <= bnd).all()
+    print("dgemm 2048 max err/bound %.3g" % (err / bnd).max())
