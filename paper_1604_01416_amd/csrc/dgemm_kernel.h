@@ -39,11 +39,11 @@ struct DTileCfg {
 
 // Operand contiguous along k: element (r, k) at base[r*ld + k].  Thread (row, k pair); the pair is
 // transposed into the image by two 8-byte LDS stores.
-template <int BR, int BK, int NT, int LD>
+template <int BR, int BK, int NT, int LD, bool VEC>
 struct DLoaderK {
     static constexpr int PPR = BK / 2;            // pairs per row
     static constexpr int NQ = (BR * PPR) / NT;    // pairs per thread
-    static constexpr int NLOAD = 2 * NQ, NSTORE = 2 * NQ;
+    static constexpr int NLOAD = VEC ? NQ : 2 * NQ, NSTORE = 2 * NQ;
     static_assert((BR * PPR) % NT == 0 && NQ >= 1, "tile must split evenly over the threads");
     const double *tile;   // &base[r0*ld + k of the tile]
     int64_t off[NQ];      // element offset of (row, first k of the pair)
@@ -65,7 +65,13 @@ struct DLoaderK {
     template <int I>
     __device__ __forceinline__ void load_piece()
     {
-        v[I / 2][I % 2] = tile[off[I / 2] + (I % 2)];
+        if constexpr (VEC) {  // 16-byte aligned pairs: one load
+            const doublex2 p = *reinterpret_cast<const doublex2 *>(tile + off[I]);
+            v[I][0] = p[0];
+            v[I][1] = p[1];
+        } else {
+            v[I / 2][I % 2] = tile[off[I / 2] + (I % 2)];
+        }
     }
     __device__ __forceinline__ void advance() { tile += BK; }
     // last, partial tile: k >= krem does not exist
@@ -85,12 +91,12 @@ struct DLoaderK {
 
 // Operand contiguous along its own index: element (r, k) at base[k*ld + r].  Thread (k row, r pair);
 // one 16-byte LDS store per pair.
-template <int BR, int BK, int NT, int LD>
+template <int BR, int BK, int NT, int LD, bool VEC>
 struct DLoaderN {
     static constexpr int PPR = BR / 2;            // pairs per k row
     static constexpr int NQ = (BK * PPR) / NT;
     static constexpr int KSTEP = NT / PPR;
-    static constexpr int NLOAD = 2 * NQ, NSTORE = NQ;
+    static constexpr int NLOAD = VEC ? NQ : 2 * NQ, NSTORE = NQ;
     static_assert((BK * PPR) % NT == 0 && NQ >= 1 && NT % PPR == 0, "tile must split evenly over the threads");
     const double *tile;   // &base[k of the tile * ld + r0]
     int64_t tstride;
@@ -109,14 +115,23 @@ struct DLoaderN {
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 int64_t lr = 2 * rq + e;
-                lr = r0 + lr < R ? lr : R - 1 - r0;
+                if (VEC)
+                    lr = r0 + 2 * rq + 2 <= R ? lr : R - 2 - r0 + e;  // R even: the last whole pair
+                else
+                    lr = r0 + lr < R ? lr : R - 1 - r0;
                 off[q][e] = (int64_t)(krow + q * KSTEP) * ld + lr;
             }
     }
     template <int I>
     __device__ __forceinline__ void load_piece()
     {
-        v[I / 2][I % 2] = tile[off[I / 2][I % 2]];
+        if constexpr (VEC) {  // R even and 16-byte aligned rows: the pair is one load, wholly inside or clamped
+            const doublex2 p = *reinterpret_cast<const doublex2 *>(tile + off[I][0]);
+            v[I][0] = p[0];
+            v[I][1] = p[1];
+        } else {
+            v[I / 2][I % 2] = tile[off[I / 2][I % 2]];
+        }
     }
     __device__ __forceinline__ void advance() { tile += tstride; }
     __device__ __forceinline__ void load_tail(int krem)
@@ -136,13 +151,15 @@ struct DLoaderN {
     }
 };
 
-template <class Cfg, bool KCONTIG, int BR, int LD>
+// (The k-contiguous loader always uses its 8-byte form: the compiler joins the two loads of a pair
+// where it can, and the explicit 16-byte form measured 20-40 % slower.)
+template <class Cfg, bool KCONTIG, int BR, int LD, bool VEC>
 struct DLoaderSel {
-    typedef DLoaderK<BR, Cfg::BK, Cfg::NT, LD> type;
+    typedef DLoaderK<BR, Cfg::BK, Cfg::NT, LD, false> type;
 };
-template <class Cfg, int BR, int LD>
-struct DLoaderSel<Cfg, false, BR, LD> {
-    typedef DLoaderN<BR, Cfg::BK, Cfg::NT, LD> type;
+template <class Cfg, int BR, int LD, bool VEC>
+struct DLoaderSel<Cfg, false, BR, LD, VEC> {
+    typedef DLoaderN<BR, Cfg::BK, Cfg::NT, LD, VEC> type;
 };
 
 template <class Cfg>
@@ -170,11 +187,17 @@ __device__ __forceinline__ void dmma_one(const DFrag<Cfg> &f, doublex4 (&acc)[Cf
 // One K tile: MB*NB matrix instructions per k step; after each, at most one fragment read, LDS store
 // of the staged tile or global load of the tile after it.  The flags (workgroup-uniform) say whether
 // there is a tile to store, one to load and a next one to read; they guard the memory operations only.
-template <class Cfg, class RL, class CL>
+// STEADY: all three hold and nothing is tested.
+template <class Cfg, bool STEADY, class RL, class CL>
 __device__ __forceinline__ void dtile_iter(RL &rl, CL &cl, DFrag<Cfg> (&fr)[2], doublex4 (&acc)[Cfg::MB][Cfg::NB],
                                            const double *cur, const double *nxt, double *fill, int a_off, int b_off,
-                                           bool do_store, bool do_load, bool has_next)
+                                           bool do_store = true, bool do_load = true, bool has_next = true)
 {
+    if constexpr (STEADY) {
+        do_store = true;
+        do_load = true;
+        has_next = true;
+    }
     constexpr int NMMA = Cfg::MB * Cfg::NB, NFRAG = Cfg::MB / 2 + Cfg::NB / 2, TOTAL = Cfg::KSTEPS * NMMA;
     constexpr int NST = RL::NSTORE + CL::NSTORE, NLD = RL::NLOAD + CL::NLOAD;
     static_assert(NST + NLD <= TOTAL, "one memory operation per matrix instruction");
@@ -249,7 +272,9 @@ struct DGemmScalars {
     double alpha, beta;
 };
 
-template <class Cfg, bool A_KCONTIG, bool B_KCONTIG>
+// VEC: A and B are 16-byte aligned with even leading dimensions, and an operand stored along its own
+// index has an even number of rows / columns: every pair is one 16-byte load.
+template <class Cfg, bool A_KCONTIG, bool B_KCONTIG, bool VEC>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void dgemm_tile_kernel(const DGemmArgs g, const DGemmScalars sc)
 {
     constexpr int S = Cfg::STAGES;
@@ -262,8 +287,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void dgemm_tile_kernel(con
     const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
     const int T = (int)(g.K / Cfg::BK), krem = (int)(g.K - (int64_t)T * Cfg::BK);
 
-    typename DLoaderSel<Cfg, A_KCONTIG, Cfg::BM, Cfg::LDA>::type rl;
-    typename DLoaderSel<Cfg, B_KCONTIG, Cfg::BN, Cfg::LDB>::type cl;
+    typename DLoaderSel<Cfg, A_KCONTIG, Cfg::BM, Cfg::LDA, VEC>::type rl;
+    typename DLoaderSel<Cfg, B_KCONTIG, Cfg::BN, Cfg::LDB, VEC>::type cl;
     rl.init(g.A, g.lda, m0, g.M, 0, threadIdx.x);
     cl.init(g.B, g.ldb, n0, g.N, 0, threadIdx.x);
 
@@ -312,10 +337,16 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void dgemm_tile_kernel(con
     };
     if (T > 0) first_frags(smem);
 
-    int cs = 0, fill = S - 1;
-    for (int t = 0; t < T; ++t) {
-        dtile_iter<Cfg>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off, t + S - 1 < T, t + S < T,
-                        t + 1 < T);
+    int cs = 0, fill = S - 1, t = 0;
+    for (; t + S < T; ++t) {  // steady state: a tile to store, one to load and a next one to read
+        dtile_iter<Cfg, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off);
+        cs = next_of(cs);
+        fill = next_of(fill);
+        __syncthreads();
+    }
+    for (; t < T; ++t) {
+        dtile_iter<Cfg, false>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off, t + S - 1 < T,
+                               t + S < T, t + 1 < T);
         cs = next_of(cs);
         fill = next_of(fill);
         __syncthreads();
@@ -327,31 +358,36 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void dgemm_tile_kernel(con
         store_all(smem);
         __syncthreads();
         first_frags(smem);
-        dtile_iter<Cfg>(rl, cl, fr, acc, smem, smem, smem, a_off, b_off, false, false, false);
+        dtile_iter<Cfg, false>(rl, cl, fr, acc, smem, smem, smem, a_off, b_off, false, false, false);
     }
     dstore_tile<Cfg>(acc, g.C, g.ldc, g.M, g.N, sc.alpha, sc.beta, m0, n0);
 }
 
 template <class Cfg>
-int launch_dgemm(const DGemmArgs &g, double alpha, double beta, bool a_kcontig, bool b_kcontig, hipStream_t stream)
+int launch_dgemm(const DGemmArgs &g, double alpha, double beta, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t stream)
 {
     const dim3 grid((unsigned)(g.tiles_m * g.tiles_n)), block(Cfg::NT);
     const DGemmScalars sc = {alpha, beta};
-    if (a_kcontig && b_kcontig)
-        hipLaunchKernelGGL((dgemm_tile_kernel<Cfg, true, true>), grid, block, 0, stream, g, sc);
-    else if (a_kcontig)
-        hipLaunchKernelGGL((dgemm_tile_kernel<Cfg, true, false>), grid, block, 0, stream, g, sc);
-    else if (b_kcontig)
-        hipLaunchKernelGGL((dgemm_tile_kernel<Cfg, false, true>), grid, block, 0, stream, g, sc);
-    else
-        hipLaunchKernelGGL((dgemm_tile_kernel<Cfg, false, false>), grid, block, 0, stream, g, sc);
+#define DMATH_DLAUNCH(AK, BK_, V) hipLaunchKernelGGL((dgemm_tile_kernel<Cfg, AK, BK_, V>), grid, block, 0, stream, g, sc)
+    if (vec) {
+        if (a_kcontig && b_kcontig) DMATH_DLAUNCH(true, true, true);
+        else if (a_kcontig) DMATH_DLAUNCH(true, false, true);
+        else if (b_kcontig) DMATH_DLAUNCH(false, true, true);
+        else DMATH_DLAUNCH(false, false, true);
+    } else {
+        if (a_kcontig && b_kcontig) DMATH_DLAUNCH(true, true, false);
+        else if (a_kcontig) DMATH_DLAUNCH(true, false, false);
+        else if (b_kcontig) DMATH_DLAUNCH(false, true, false);
+        else DMATH_DLAUNCH(false, false, false);
+    }
+#undef DMATH_DLAUNCH
     return (int)hipGetLastError();
 }
 
 struct DCfgDesc {
     const char *name;
     int BM, BN, BK, NT, lds_bytes;
-    int (*launch)(const DGemmArgs &, double alpha, double beta, bool a_kcontig, bool b_kcontig, hipStream_t);
+    int (*launch)(const DGemmArgs &, double alpha, double beta, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);
 };
 constexpr int kNumDCfg = 2;
 const DCfgDesc &dcfg_desc(int i);  // defined in dgemm_instance.hip

@@ -624,7 +624,8 @@ dmath_status dmath_dgemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N,
     g.split.plain = 0;
     g.split.slice_stride = 0;
     g.clock_probe = nullptr;
-    if (d.launch(g, alpha, beta, a_k, b_k, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    const bool vec = aligned16(A) && aligned16(B) && lda % 2 == 0 && ldb % 2 == 0 && (a_k || M % 2 == 0) && (b_k || N % 2 == 0);
+    if (d.launch(g, alpha, beta, a_k, b_k, vec, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
     return DMATH_OK;
 }
 
