@@ -8,8 +8,13 @@
 // FP32 result is laid out like that of the FP32 instruction.  Both operands therefore want 8
 // consecutive k per lane, and the LDS image of a K tile is k-contiguous for both:
 //
-//     As[BM][LDK], Bs[BN][LDK] halves, LDK = BK + 8 (80-byte rows: the 16 lanes served together by a
-//     16-byte LDS read hit 16 different 16-byte bank groups when they read 16 consecutive rows).
+//     As[BM][LD], Bs[BN][LD] halves.  For an operand that is transposed on the way in, LD = BK + 8
+//     (80-byte rows: the 16 lanes served together by a 16-byte LDS read hit 16 different 16-byte bank
+//     groups when they read 16 consecutive rows).  For an operand copied with 16-byte stores that
+//     padding makes the stores collide (4 rows x 4 chunks of a 16-lane group overlap by 48 bytes: 8
+//     conflict cycles per store by the counters), so its rows are unpadded (64 bytes) and the four
+//     16-byte chunks of row r are stored in the order c ^ ((r >> 2) & 3): stores of 4 rows x 4 chunks
+//     and reads of 16 consecutive rows at one logical chunk both cover all banks exactly once.
 //
 // An operand stored contiguously along k (A for transA == N, B for transB == T) is copied with 16-byte
 // loads and 16-byte LDS stores.  An operand stored along its own index (A^T, B) is transposed on the
@@ -48,7 +53,8 @@ struct HLoaderK {
     static constexpr int CPR = BK / 8;             // 16-byte chunks per row
     static constexpr int NP = (BR * CPR) / NT;     // chunks per thread
     static constexpr int NLOAD = NP, NSTORE = NP;
-    static_assert((BR * CPR) % NT == 0 && NP >= 1, "tile must split evenly over the threads");
+    static constexpr int LD = BK;                  // unpadded image rows, chunks swizzled
+    static_assert((BR * CPR) % NT == 0 && NP >= 1 && CPR == 4 && (NT / CPR) % 16 == 0, "tile must split evenly over the threads");
     const char *tile;
     uint32_t off[NP];
     halfx8 v[SLOTS][NP];
@@ -58,13 +64,19 @@ struct HLoaderK {
     {
         const int row0 = tid / CPR, ch = tid % CPR;
         tile = reinterpret_cast<const char *>(base + r0 * ld + k0);
-        lds0 = row0 * LDK + ch * 8;
+        lds0 = row0 * LD + ((ch ^ ((row0 >> 2) & 3)) * 8);
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             int64_t lr = row0 + p * (NT / CPR);
             lr = r0 + lr < R ? lr : R - 1 - r0;  // rows past the end re-read the last one; never stored
             off[p] = (uint32_t)((lr * ld + ch * 8) * 2);
         }
+    }
+    // image offset (halves) of the fragment of k step ks for the lane reading tile row `row` (a
+    // multiple of 32 plus lane % 32) with k half h = lane / 32
+    static __device__ __forceinline__ int frag_off(int row, int ks, int h)
+    {
+        return row * LD + (((2 * ks + h) ^ ((row >> 2) & 3)) * 8);
     }
     template <int SLOT, int I>
     __device__ __forceinline__ void load_piece()
@@ -75,7 +87,7 @@ struct HLoaderK {
     template <int SLOT, int I>
     __device__ __forceinline__ void store_piece(_Float16 *S) const
     {
-        *reinterpret_cast<halfx8 *>(S + lds0 + I * (NT / CPR) * LDK) = v[SLOT][I];
+        *reinterpret_cast<halfx8 *>(S + lds0 + I * (NT / CPR) * LD) = v[SLOT][I];
     }
 };
 
@@ -92,7 +104,9 @@ struct HLoaderN {
     static constexpr int ITEMS = KP * (BR / 8);           // (k pair, chunk) items
     static constexpr int NP = ITEMS / NT;
     static constexpr int NLOAD = 2 * NP, NSTORE = 8 * NP;
+    static constexpr int LD = LDK;                        // padded image rows
     static_assert(ITEMS % NT == 0 && NP >= 1 && NT % KP == 0, "tile must split evenly over the threads");
+    static __device__ __forceinline__ int frag_off(int row, int ks, int h) { return row * LD + ks * 16 + 8 * h; }
     const char *tile;
     int64_t tstride, row_bytes;
     uint32_t off[NP];
@@ -146,13 +160,16 @@ struct HFrag {
 };
 
 // Fragment piece P of k step KS: P < MB is block row P of A, else block column P - MB of B.
-template <class Cfg, int KS, int P>
-__device__ __forceinline__ void hload_frag_piece(HFrag<Cfg> &f, const _Float16 *As, const _Float16 *Bs, int a_off, int b_off)
+// a_off / b_off: the lane's image offsets for k steps 0 and 1 (see frag_off of the loaders); LDA / LDB:
+// row strides of the two images.
+template <class Cfg, int LDA, int LDB, int KS, int P>
+__device__ __forceinline__ void hload_frag_piece(HFrag<Cfg> &f, const _Float16 *As, const _Float16 *Bs,
+                                                 const int (&a_off)[2], const int (&b_off)[2])
 {
     if constexpr (P < Cfg::MB)
-        f.a[P] = *reinterpret_cast<const halfx8 *>(As + a_off + P * 32 * Cfg::LDK + KS * 16);
+        f.a[P] = *reinterpret_cast<const halfx8 *>(As + a_off[KS] + P * 32 * LDA);
     else
-        f.b[P - Cfg::MB] = *reinterpret_cast<const halfx8 *>(Bs + b_off + (P - Cfg::MB) * 32 * Cfg::LDK + KS * 16);
+        f.b[P - Cfg::MB] = *reinterpret_cast<const halfx8 *>(Bs + b_off[KS] + (P - Cfg::MB) * 32 * LDB);
 }
 
 template <class Cfg, int Q>
@@ -162,17 +179,18 @@ __device__ __forceinline__ void hmma_one(const HFrag<Cfg> &f, floatx16 (&acc)[Cf
     acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.a[bm], f.b[bn], acc[bm][bn], 0, 0, 0);
 }
 
-// One K tile: MB*NB matrix instructions per k step.  Between them, one at a time: the fragment reads
-// of the next k step (or of the next tile's first step), the LDS stores of the staged tile (DO_STORE)
-// and the global loads of a later tile (DO_LOAD).  SLOT is the register set both use: the tile stored
-// now was loaded SLOTS iterations ago.
+// One K tile (including its barrier): MB*NB matrix instructions per k step.  Between them: the fragment
+// reads of the next k step (or of the next tile's first step), the LDS stores of the staged tile
+// (DO_STORE) and the global loads of a later tile (DO_LOAD).  SLOT is the register set both use: the
+// tile stored now was loaded SLOTS iterations ago.
 //
 // STEADY: everything happens, no conditions.  Otherwise (first and last tiles of a K range) the
 // workgroup-uniform flags say whether there is a tile to store, one to load and a next one to read;
 // the conditions guard the memory operations only, the matrix instructions are common code.
 template <class Cfg, int SLOT, bool STEADY, class RL, class CL>
 __device__ __forceinline__ void htile_iter(RL &rl, CL &cl, HFrag<Cfg> (&fr)[2], floatx16 (&acc)[Cfg::MB][Cfg::NB],
-                                           const _Float16 *cur, const _Float16 *nxt, _Float16 *fill, int a_off, int b_off,
+                                           const _Float16 *cur, const _Float16 *nxt, _Float16 *fill, const int (&a_off)[2],
+                                           const int (&b_off)[2],
                                            bool DO_STORE = true, bool DO_LOAD = true, bool NEXT = true)
 {
     if constexpr (STEADY) {
@@ -182,60 +200,52 @@ __device__ __forceinline__ void htile_iter(RL &rl, CL &cl, HFrag<Cfg> (&fr)[2], 
     }
     constexpr int NMMA = Cfg::MB * Cfg::NB, NFRAG = Cfg::MB + Cfg::NB;
     constexpr int NST = RL::NSTORE + CL::NSTORE, NLD = RL::NLOAD + CL::NLOAD;
-    static_for<Cfg::KSTEPS>([&](auto ksc) {
-        constexpr int ks = decltype(ksc)::value;
-        constexpr bool last = ks == Cfg::KSTEPS - 1;
-        static_for<NMMA>([&](auto qc) {
-            constexpr int q = decltype(qc)::value;
-            hmma_one<Cfg, q>(fr[ks % 2], acc);
-            __builtin_amdgcn_sched_barrier(0);
-            // fragments for the next k step (same tile) or the first step of the next tile
-            if constexpr (q < NFRAG) {
-                if constexpr (!last)
-                    hload_frag_piece<Cfg, ks + 1, q>(fr[(ks + 1) % 2], cur, cur + Cfg::A_HALVES, a_off, b_off);
-                else if (NEXT)
-                    hload_frag_piece<Cfg, 0, q>(fr[0], nxt, nxt + Cfg::A_HALVES, a_off, b_off);
-            }
-            // staged tile -> LDS, spread over the matrix instructions of all k steps
-            constexpr int slot_idx = ks * NMMA + q;
-            constexpr int per = (NST + Cfg::KSTEPS * NMMA - 1) / (Cfg::KSTEPS * NMMA);
-            if (DO_STORE) {
-                static_for<per>([&](auto ec) {
-                    constexpr int s = slot_idx * per + decltype(ec)::value;
-                    if constexpr (s < RL::NSTORE)
-                        rl.template store_piece<SLOT, s>(fill);
-                    else if constexpr (s < NST)
-                        cl.template store_piece<SLOT, s - RL::NSTORE>(fill + Cfg::A_HALVES);
-                });
-            }
-            // global loads of a later tile go out once this slot's registers have been stored
+    constexpr int PER = (NST + NMMA - 1) / NMMA;  // LDS stores after each matrix instruction of k step 0
+    static_assert(Cfg::KSTEPS == 2 && NFRAG <= NMMA && NLD <= NMMA, "two k steps: stores in the first, loads in the second");
+    // k step 0: fragments of k step 1, and the staged tile goes to LDS
+    static_for<NMMA>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        hmma_one<Cfg, q>(fr[0], acc);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (q < NFRAG) hload_frag_piece<Cfg, RL::LD, CL::LD, 1, q>(fr[1], cur, cur + Cfg::A_HALVES, a_off, b_off);
+        if (DO_STORE) {
+            static_for<PER>([&](auto ec) {
+                constexpr int st = q * PER + decltype(ec)::value;
+                if constexpr (st < RL::NSTORE)
+                    rl.template store_piece<SLOT, st>(fill);
+                else if constexpr (st < NST)
+                    cl.template store_piece<SLOT, st - RL::NSTORE>(fill + Cfg::A_HALVES);
+            });
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    // The one barrier of the iteration sits here, between the k steps: what it has to wait for (the
+    // LDS stores above, the fragment reads the next instructions need anyway) was issued at the start
+    // of k step 0, so the wait is short; at the end of the iteration it would expose the latency of
+    // the next tile's fragment reads on every K tile.  Hazards: the stage written above was last read
+    // by fragment reads issued before the previous iteration's barrier; the tile written above is
+    // first read after the next iteration's barrier.
+    __syncthreads();
+    // k step 1: fragments of the next tile's k step 0, and the global loads of a later tile into the
+    // register set that was just stored
+    static_for<NMMA>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        hmma_one<Cfg, q>(fr[1], acc);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (q < NFRAG) {
+            if (NEXT) hload_frag_piece<Cfg, RL::LD, CL::LD, 0, q>(fr[0], nxt, nxt + Cfg::A_HALVES, a_off, b_off);
+        }
+        if constexpr (q < NLD) {
             if (DO_LOAD) {
-                constexpr int first_free = (NST + per - 1) / per;  // matrix instruction after the last store
-                constexpr int l = slot_idx - first_free;
-                if constexpr (l >= 0 && l < NLD) {
-                    if constexpr (l < RL::NLOAD)
-                        rl.template load_piece<SLOT, l>();
-                    else
-                        cl.template load_piece<SLOT, l - RL::NLOAD>();
-                }
+                if constexpr (q < RL::NLOAD)
+                    rl.template load_piece<SLOT, q>();
+                else
+                    cl.template load_piece<SLOT, q - RL::NLOAD>();
             }
-            __builtin_amdgcn_sched_barrier(0);
-        });
+        }
+        __builtin_amdgcn_sched_barrier(0);
     });
     if (DO_LOAD) {
-        // loads that found no matrix instruction to follow (many stores, few instructions)
-        constexpr int per = (NST + Cfg::KSTEPS * NMMA - 1) / (Cfg::KSTEPS * NMMA);
-        constexpr int first_free = (NST + per - 1) / per;
-        constexpr int placed = Cfg::KSTEPS * NMMA - first_free > 0 ? Cfg::KSTEPS * NMMA - first_free : 0;
-        static_for<NLD>([&](auto lc) {
-            constexpr int l = decltype(lc)::value;
-            if constexpr (l >= placed) {
-                if constexpr (l < RL::NLOAD)
-                    rl.template load_piece<SLOT, l>();
-                else
-                    cl.template load_piece<SLOT, l - RL::NLOAD>();
-            }
-        });
         rl.advance();
         cl.advance();
     }
@@ -303,8 +313,11 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
     cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int a_off = ((wave / Cfg::WAVES_N) * Cfg::WM + (lane & 31)) * Cfg::LDK + 8 * (lane >> 5);
-    const int b_off = ((wave % Cfg::WAVES_N) * Cfg::WN + (lane & 31)) * Cfg::LDK + 8 * (lane >> 5);
+    typedef decltype(rl) RLT;
+    typedef decltype(cl) CLT;
+    const int a_row = (wave / Cfg::WAVES_N) * Cfg::WM + (lane & 31), b_row = (wave % Cfg::WAVES_N) * Cfg::WN + (lane & 31);
+    const int a_off[2] = {RLT::frag_off(a_row, 0, lane >> 5), RLT::frag_off(a_row, 1, lane >> 5)};
+    const int b_off[2] = {CLT::frag_off(b_row, 0, lane >> 5), CLT::frag_off(b_row, 1, lane >> 5)};
 
     floatx16 acc[Cfg::MB][Cfg::NB];
 #pragma unroll
@@ -333,7 +346,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
     HFrag<Cfg> fr[2];
     auto first_frags = [&]() {
         static_for<Cfg::MB + Cfg::NB>([&](auto pc) {
-            hload_frag_piece<Cfg, 0, decltype(pc)::value>(fr[0], smem, smem + Cfg::A_HALVES, a_off, b_off);
+            hload_frag_piece<Cfg, RLT::LD, CLT::LD, 0, decltype(pc)::value>(fr[0], smem, smem + Cfg::A_HALVES, a_off, b_off);
         });
     };
     int cs = 0, fill = S - 1;
@@ -361,11 +374,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
             htile_iter<Cfg, 0, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off);
             cs = next_of(cs);
             fill = next_of(fill);
-            __syncthreads();
             htile_iter<Cfg, 1, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off);
             cs = next_of(cs);
             fill = next_of(fill);
-            __syncthreads();
             t += 2;
         }
     } else {
@@ -387,13 +398,11 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
                                   t + S - 1 < T, t + S + 1 < T, t + 1 < T);
         cs = next_of(cs);
         fill = next_of(fill);
-        __syncthreads();
         if (t + 1 < T) {
             htile_iter<Cfg, 1, false>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), a_off, b_off,
                                       t + S < T, t + S + 2 < T, t + 2 < T);
             cs = next_of(cs);
             fill = next_of(fill);
-            __syncthreads();
         }
     }
     if (!combine_slices<Cfg>(acc, g.split, w)) return;
