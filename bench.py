@@ -135,6 +135,7 @@ def main():
     ap.add_argument("--workload", choices=WORKLOADS, default="gemm4096")
     ap.add_argument("--tile-config", type=int, default=-1, help="force a tile configuration (tuning only)")
     ap.add_argument("--split-k", type=int, default=-1, help="force a split-K factor (tuning only)")
+    ap.add_argument("--hgemm-path", type=int, default=-1, help="force the dmath_hgemm kernel (see dmath_set_hgemm_path)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the workload, run `steps` device copies of 256 MiB (for scaling HBM counters)")
@@ -167,6 +168,8 @@ def main():
     dm.check(dm.dmath_set_workspace(ws, ws_bytes))
     if args.tile_config >= 0 or args.split_k >= 1:
         dm.check(dm.dmath_set_override(args.tile_config, args.split_k))
+    if args.hgemm_path >= 0:
+        dm.check(dm.dmath_set_hgemm_path(args.hgemm_path))
 
     cpu_baseline = None
     conv = None

@@ -98,9 +98,10 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB,
  * exact in FP32 and it accumulates in FP32, so it computes the same sums (in another order) at 16 times
  * the FP32 matrix rate.  Every other case runs the FP32 matrix instruction on operands widened on the
  * fly.  dmath_set_hgemm_path forces one of them for this thread's later calls: -1 automatic, 0 the
- * FP32 instruction, 1 the FP16-input instruction with the 8-wave tile (the automatic choice), 2 the
- * same with the 4-wave tile (1 and 2: UNSUPPORTED when the conditions do not hold); a tile
- * configuration forced with dmath_set_override also selects the FP32 instruction.
+ * FP32 instruction; 1, 2, 3 the FP16-input instruction with the 256 x 256 tile of 8 waves, the 256 x 256
+ * tile of 4 waves, the 128 x 128 tile (automatic: 1 for large outputs, 3 for small ones; forced:
+ * UNSUPPORTED when the conditions do not hold); a tile configuration forced with dmath_set_override
+ * also selects the FP32 instruction.
  */
 dmath_status dmath_hgemm(dmath_op transA, dmath_op transB,
                          int64_t M, int64_t N, int64_t K,

@@ -362,7 +362,10 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     if constexpr (kHalf) {
         // The FP16-input matrix instruction computes the same FP32 sums of exact products 16 times
         // faster; its kernel needs whole K tiles and 16-byte chunks everywhere.
-        const HCfgDesc &h = hcfg_desc(g_state.hgemm_path >= 1 ? g_state.hgemm_path - 1 : 0);
+        // automatic: the 256 x 256 tile once it fills a good part of the device, else the 128 x 128 tile
+        int hidx = g_state.hgemm_path >= 1 ? g_state.hgemm_path - 1 : 0;
+        if (g_state.hgemm_path < 1 && ceil_div(M, 256) * ceil_div(N, 256) < 96) hidx = 2;
+        const HCfgDesc &h = hcfg_desc(hidx);
         const bool fits = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0 && K % h.BK == 0 &&
                           (a_k || M % 8 == 0) && (b_k || N % 8 == 0);
         if (g_state.hgemm_path >= 1 && !fits) return fail(DMATH_ERR_UNSUPPORTED, 0);
@@ -376,6 +379,8 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
                 s = g_state.force_split;
             else if (tiles < kNumCU / 2)
                 s = kNumCU / tiles;
+            else if (hidx == 2 && tiles < kNumCU)
+                s = 2 * kNumCU / tiles;  // two of the small workgroups fit a compute unit
             if (s > kMaxSplits) s = kMaxSplits;
             if (s > ktiles / 2) s = ktiles / 2;
             const size_t avail = g_state.ws ? g_state.ws_bytes : 0;

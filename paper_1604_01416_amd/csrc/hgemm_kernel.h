@@ -434,7 +434,7 @@ struct HCfgDesc {
     int BM, BN, BK, NT, lds_bytes;
     int (*launch)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);
 };
-constexpr int kNumHCfg = 2;
+constexpr int kNumHCfg = 3;
 const HCfgDesc &hcfg_desc(int i);  // defined in hgemm_instance.hip
 
 }  // namespace dmath
