@@ -781,3 +781,74 @@ def test_dgemm_2048_sampled(dm, torch):
     bnd = oracle.double_bound(n, mag)
     assert (err <= bnd).all()
     print("dgemm 2048 max err/bound %.3g" % (err / bnd).max())
+
+
+# ------------------------------------------------------------------ reproducibility and streams, every entry point
+
+def _twice(torch, fn, out):
+    """Run fn twice on a NaN-filled output and return both results."""
+    res = []
+    for _ in range(2):
+        out.fill_(float("nan"))
+        fn()
+        torch.cuda.synchronize()
+        res.append(out.clone())
+    return res
+
+
+def test_every_entry_point_is_bit_reproducible(dm, torch):
+    """Same call, same data: same bits (no atomics in any reduction; split slices are added in slice order)."""
+    g = torch.Generator(device="cuda").manual_seed(5)
+    r = lambda *shape, dtype=torch.float32: (torch.rand(shape, device="cuda", generator=g) - 0.5).to(dtype)
+    # split-K GEMM (skinny), tail-split GEMM (17 x 16 tiles of 256 x 256)
+    A, B, C = r(256, 4096), r(4096, 1024), torch.empty((256, 1024), device="cuda")
+    a, b = _twice(torch, lambda: dm.check(dm.dmath_gemm(0, 0, 256, 1024, 4096, 1.0, A, 4096, B, 1024, 0.0, C, 1024)), C)
+    assert torch.equal(a, b)
+    # multi-panel
+    As, Bs, C = [r(512, 64) for _ in range(5)], [r(64, 384) for _ in range(5)], torch.empty((512, 384), device="cuda")
+    a, b = _twice(torch, lambda: dm.check(dm.dmath_gemm_panels(0, 0, 512, 384, 64, 1.0, As, 64, Bs, 384, 0.0, C, 384)), C)
+    assert torch.equal(a, b)
+    # convolution forward (tail split), backward-data, backward-filter (28 slices)
+    x, w = r(16, 64, 28, 28), r(64, 64, 3, 3)
+    y = torch.empty((16, 64, 28, 28), device="cuda")
+    a, b = _twice(torch, lambda: dm.check(dm.dmath_conv2d_fwd(16, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1, 1.0, x, w, 0.0, y)), y)
+    assert torch.equal(a, b)
+    dx = torch.empty_like(x)
+    a, b = _twice(torch, lambda: dm.check(dm.dmath_conv2d_bwd_data(16, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1, 1.0, y, w, 0.0, dx)), dx)
+    assert torch.equal(a, b)
+    dw = torch.empty_like(w)
+    a, b = _twice(torch, lambda: dm.check(dm.dmath_conv2d_bwd_filter(16, 64, 28, 28, 64, 3, 3, 1, 1, 1, 1, 1.0, x, y, 0.0, dw)), dw)
+    assert torch.equal(a, b)
+    # half storage (FP16-input instruction with split-K) and FP64
+    Ah, Bh = r(256, 2048, dtype=torch.float16), r(2048, 512, dtype=torch.float16)
+    Ch = torch.empty((256, 512), device="cuda", dtype=torch.float16)
+    a, b = _twice(torch, lambda: dm.check(dm.dmath_hgemm(0, 0, 256, 512, 2048, 1.0, Ah, 2048, Bh, 512, 0.0, Ch, 512)), Ch)
+    assert torch.equal(a, b)
+    Ad, Bd = r(300, 200, dtype=torch.float64), r(200, 260, dtype=torch.float64)
+    Cd = torch.empty((300, 260), device="cuda", dtype=torch.float64)
+    a, b = _twice(torch, lambda: dm.check(dm.dmath_dgemm(0, 0, 300, 260, 200, 1.0, Ad, 200, Bd, 260, 0.0, Cd, 260)), Cd)
+    assert torch.equal(a, b)
+
+
+def test_other_entry_points_on_a_side_stream(dm, torch):
+    """Work goes to the stream that is passed: results are complete after that stream alone is synchronised."""
+    s = torch.cuda.Stream()
+    rng = np.random.default_rng(77)
+    M, N, K = 264, 136, 96
+    A, B = rng.integers(-2, 3, size=(M, K)), rng.integers(-2, 3, size=(K, N))
+    want = (A @ B).astype(np.float64)
+    A16, B16 = (torch.from_numpy(t.astype(np.float16)).cuda() for t in (A, B))
+    A64, B64 = (torch.from_numpy(t.astype(np.float64)).cuda() for t in (A, B))
+    A32, B32 = (torch.from_numpy(t.astype(np.float32)).cuda() for t in (A, B))
+    C16 = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    C64 = torch.zeros((M, N), dtype=torch.float64, device="cuda")
+    C32 = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    dm.check(dm.dmath_hgemm(0, 0, M, N, K, 1.0, A16, K, B16, N, 0.0, C16, N, stream=s))
+    dm.check(dm.dmath_dgemm(0, 0, M, N, K, 1.0, A64, K, B64, N, 0.0, C64, N, stream=s))
+    dm.check(dm.dmath_gemm_panels(0, 0, M, N, K // 2, 1.0, [A32[:, :K // 2], A32[:, K // 2:]], K,
+                                  [B32[:K // 2], B32[K // 2:]], N, 0.0, C32, N, stream=s))
+    s.synchronize()
+    assert np.array_equal(C16.cpu().numpy().astype(np.float64), want)
+    assert np.array_equal(C64.cpu().numpy(), want)
+    assert np.array_equal(C32.cpu().numpy().astype(np.float64), want)
