@@ -100,8 +100,10 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB,
  * fly.  dmath_set_hgemm_path forces one of them for this thread's later calls: -1 automatic, 0 the
  * FP32 instruction; 1, 2, 3 the FP16-input instruction with the 256 x 256 tile of 8 waves, the 256 x 256
  * tile of 4 waves, the 128 x 128 tile (automatic: 1 for large outputs, 3 for small ones; forced:
- * UNSUPPORTED when the conditions do not hold); a tile configuration forced with dmath_set_override
- * also selects the FP32 instruction.
+ * UNSUPPORTED when the conditions do not hold); adding 16 to 1, 2 or 3 selects the variant of that
+ * kernel that stages every operand through registers (by default a product with both operands stored
+ * along k, transA == N and transB == T, loads them global -> LDS directly); a tile configuration forced
+ * with dmath_set_override also selects the FP32 instruction.
  */
 dmath_status dmath_hgemm(dmath_op transA, dmath_op transB,
                          int64_t M, int64_t N, int64_t K,

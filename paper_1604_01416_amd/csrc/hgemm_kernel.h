@@ -145,6 +145,93 @@ struct HLoaderN {
     }
 };
 
+// The same operand (contiguous along k) brought in by global -> LDS loads that bypass the registers:
+// global_load_lds_dwordx4 writes the 16 bytes of lane l at (wave-uniform LDS address) + 16*l (checked on
+// the device), so one instruction fills 16 consecutive 64-byte rows of the swizzled image and each lane
+// fetches the chunk that belongs at its position.  No staging registers, no LDS store instructions.
+template <int BR, int BK, int NT, int LDK_UNUSED, int SLOTS_UNUSED>
+struct HLoaderKDma {
+    static constexpr bool DMA = true;
+    static constexpr int NW = NT / 64;
+    static constexpr int NP = BR / (16 * NW);      // instructions per thread and tile
+    static constexpr int NFILL = NP, NFETCH = 0;
+    static constexpr int LD = BK;
+    static_assert(BK == 32 && BR % (16 * NW) == 0 && NP >= 1, "16 rows of 64 bytes per wave instruction");
+    const char *tile;
+    uint32_t off[NP];
+    int lds0;  // image offset (halves) of this wave's first row group
+
+    __device__ __forceinline__ void init(const _Float16 *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
+    {
+        const int wave = tid / 64, lane = tid % 64;
+        const int ch = (lane & 3) ^ ((lane >> 4) & 3);  // logical chunk stored at this lane's position
+        tile = reinterpret_cast<const char *>(base + r0 * ld + k0);
+        lds0 = __builtin_amdgcn_readfirstlane(wave * 16 * LD);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            int64_t lr = (wave + p * NW) * 16 + lane / 4;
+            lr = r0 + lr < R ? lr : R - 1 - r0;
+            off[p] = (uint32_t)((lr * ld + ch * 8) * 2);
+        }
+    }
+    static __device__ __forceinline__ int frag_off(int row, int ks, int h)
+    {
+        return row * LD + (((2 * ks + h) ^ ((row >> 2) & 3)) * 8);
+    }
+    template <int SLOT, int I>
+    __device__ __forceinline__ void fill_piece(_Float16 *S) const
+    {
+        // Written as assembly on purpose: for the builtin form the compiler, which cannot tell which LDS
+        // bytes a global -> LDS load writes, waits for all of them (vmcnt(0)) before every later LDS
+        // read, which serialises the very loads this path is meant to keep in flight.  The waits are
+        // placed by hand instead (htile_iter_dma).  m0 = LDS byte address of lane 0's 16 bytes.
+#if defined(__HIP_DEVICE_COMPILE__)
+        typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
+        const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr)(S + lds0 + I * NW * 16 * LD);
+        const char *src = tile + off[I];
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                     :
+                     : "v"(src), "s"(__builtin_amdgcn_readfirstlane(dst))
+                     : "memory");
+#else
+        (void)S;
+#endif
+    }
+    template <int SLOT, int I>
+    __device__ __forceinline__ void fetch_piece() {}
+    __device__ __forceinline__ void advance_fill() { tile += BK * 2; }
+    __device__ __forceinline__ void advance_fetch() {}
+};
+
+// The register-path loader for an operand stored along its own index, under the fill / fetch names.
+template <int BR, int BK, int NT, int LDK, int SLOTS>
+struct HLoaderNReg : HLoaderN<BR, BK, NT, LDK, SLOTS> {
+    typedef HLoaderN<BR, BK, NT, LDK, SLOTS> Base;
+    static constexpr bool DMA = false;
+    static constexpr int NFILL = Base::NSTORE, NFETCH = Base::NLOAD;
+    template <int SLOT, int I>
+    __device__ __forceinline__ void fill_piece(_Float16 *S) const
+    {
+        Base::template store_piece<SLOT, I>(S);
+    }
+    template <int SLOT, int I>
+    __device__ __forceinline__ void fetch_piece()
+    {
+        Base::template load_piece<SLOT, I>();
+    }
+    __device__ __forceinline__ void advance_fill() {}
+    __device__ __forceinline__ void advance_fetch() { Base::advance(); }
+};
+
+template <class Cfg, bool KCONTIG, int BR>
+struct HDmaLoaderSel {
+    typedef HLoaderKDma<BR, Cfg::BK, Cfg::NT, Cfg::LDK, 2> type;
+};
+template <class Cfg, int BR>
+struct HDmaLoaderSel<Cfg, false, BR> {
+    typedef HLoaderNReg<BR, Cfg::BK, Cfg::NT, Cfg::LDK, 2> type;
+};
+
 template <class Cfg, bool KCONTIG, int BR, int SLOTS>
 struct HLoaderSel {
     typedef HLoaderK<BR, Cfg::BK, Cfg::NT, Cfg::LDK, SLOTS> type;
@@ -413,6 +500,219 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
     }
 }
 
+// s_waitcnt immediate that waits for the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0
+// and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "no wait") or for vector memory and LDS both.
+constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+constexpr int waitcnt_vm_lds0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
+
+// One K tile of the kernel with global -> LDS loads.  k step 0: fragments of k step 1, and stage `fill`
+// receives tile t + S - 1 (LDS-DMA loads for a copied operand, LDS stores from register set SLOT for a
+// transposed one).  Then the barrier, before which every wave waits until its own loads of tile t + 1
+// have landed (they were issued S - 2 iterations ago; WAIT_YOUNGER vector-memory operations issued
+// since may stay in flight).  k step 1: the next tile's first fragments, and the register-path loads
+// of tile t + S + 1.
+template <class Cfg, int SLOT, bool STEADY, class RL, class CL>
+__device__ __forceinline__ void htile_iter_dma(RL &rl, CL &cl, HFrag<Cfg> (&fr)[2], floatx16 (&acc)[Cfg::MB][Cfg::NB],
+                                               const _Float16 *cur, const _Float16 *nxt, _Float16 *fill, int a_halves,
+                                               const int (&a_off)[2], const int (&b_off)[2], bool do_fill = true,
+                                               bool do_fetch = true, bool has_next = true)
+{
+    if constexpr (STEADY) {
+        do_fill = true;
+        do_fetch = true;
+        has_next = true;
+    }
+    constexpr int NMMA = Cfg::MB * Cfg::NB, NFRAG = Cfg::MB + Cfg::NB;
+    constexpr int NFILL = RL::NFILL + CL::NFILL, NFETCH = RL::NFETCH + CL::NFETCH;
+    constexpr int PER = (NFILL + NMMA - 1) / NMMA;
+    constexpr int NDMA = (RL::DMA ? RL::NFILL : 0) + (CL::DMA ? CL::NFILL : 0);
+    constexpr int WAIT_YOUNGER = (Cfg::STAGES - 2) * (NDMA + NFETCH);
+    static_assert(Cfg::KSTEPS == 2 && NFRAG <= NMMA && NFETCH <= NMMA && WAIT_YOUNGER < 64, "slots and counter range");
+    static_for<NMMA>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        hmma_one<Cfg, q>(fr[0], acc);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (q < NFRAG) hload_frag_piece<Cfg, RL::LD, CL::LD, 1, q>(fr[1], cur, cur + a_halves, a_off, b_off);
+        if (do_fill) {
+            static_for<PER>([&](auto ec) {
+                constexpr int st = q * PER + decltype(ec)::value;
+                if constexpr (st < RL::NFILL)
+                    rl.template fill_piece<SLOT, st>(fill);
+                else if constexpr (st < NFILL)
+                    cl.template fill_piece<SLOT, st - RL::NFILL>(fill + a_halves);
+            });
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    if (do_fill) {
+        rl.advance_fill();
+        cl.advance_fill();
+    }
+    // LDS stores of this iteration done; own loads of the tile read next have landed
+    if constexpr (STEADY)
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(WAIT_YOUNGER));
+    else
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<NMMA>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        hmma_one<Cfg, q>(fr[1], acc);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (q < NFRAG) {
+            if (has_next) hload_frag_piece<Cfg, RL::LD, CL::LD, 0, q>(fr[0], nxt, nxt + a_halves, a_off, b_off);
+        }
+        if constexpr (q < NFETCH) {
+            if (do_fetch) {
+                if constexpr (q < RL::NFETCH)
+                    rl.template fetch_piece<SLOT, q>();
+                else
+                    cl.template fetch_piece<SLOT, q - RL::NFETCH>();
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    if (do_fetch) {
+        rl.advance_fetch();
+        cl.advance_fetch();
+    }
+}
+
+// The kernel for products with operands stored along k: such an operand goes global -> LDS directly,
+// the other (if stored along its own index) through registers as in hgemm_mfma16_kernel.
+// Cfg::STAGES LDS stages (4: a load has two iterations to land).  Same requirements as above.
+// Measured at 8192^3: both operands direct (NT) 1167 TFLOP/s against 1121 for the register kernel;
+// one direct, one through registers (NN) 891 against 1101 (the compiler's own waits for the register
+// loads count the direct loads too and drain them early), so the host uses it for NT only.
+template <class Cfg, bool A_KCONTIG, bool B_KCONTIG>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma_kernel(const HGemmArgs g)
+{
+    static_assert(A_KCONTIG || B_KCONTIG, "at least one operand takes the direct path");
+    typedef typename HDmaLoaderSel<Cfg, A_KCONTIG, Cfg::BM>::type RLT;
+    typedef typename HDmaLoaderSel<Cfg, B_KCONTIG, Cfg::BN>::type CLT;
+    constexpr int S = Cfg::STAGES;
+    constexpr int A_H = Cfg::BM * RLT::LD, B_H = Cfg::BN * CLT::LD, STAGE_H = A_H + B_H;
+    __shared__ __attribute__((aligned(1024))) _Float16 smem[S * STAGE_H];
+
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();
+        g.clock_probe[blockIdx.x * 4 + 1] = __builtin_amdgcn_s_memrealtime();
+    }
+    const int tiles = g.tiles_m * g.tiles_n;
+    const WorkItem w = work_item(blockIdx.x, tiles, g.split);
+    int tm, tn;
+    tile_coords<8>(w.tile, g.tiles_m, g.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
+    int kt0, T, krem;
+    slice_range((int)(g.K / Cfg::BK), 0, w.slice, w.nslice, kt0, T, krem);
+    const int64_t k0 = (int64_t)kt0 * Cfg::BK;
+
+    RLT rl;
+    CLT cl;
+    rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x);
+    cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int a_row = (wave / Cfg::WAVES_N) * Cfg::WM + (lane & 31), b_row = (wave % Cfg::WAVES_N) * Cfg::WN + (lane & 31);
+    const int a_off[2] = {RLT::frag_off(a_row, 0, lane >> 5), RLT::frag_off(a_row, 1, lane >> 5)};
+    const int b_off[2] = {CLT::frag_off(b_row, 0, lane >> 5), CLT::frag_off(b_row, 1, lane >> 5)};
+
+    floatx16 acc[Cfg::MB][Cfg::NB];
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < Cfg::NB; ++bn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
+
+    auto stage = [&](int s) { return smem + s * STAGE_H; };
+    auto next_of = [](int s) { return s + 1 == S ? 0 : s + 1; };
+    auto fetch_all = [&](auto slotc) {
+        constexpr int SL = decltype(slotc)::value;
+        static_for<RLT::NFETCH>([&](auto ic) { rl.template fetch_piece<SL, decltype(ic)::value>(); });
+        static_for<CLT::NFETCH>([&](auto ic) { cl.template fetch_piece<SL, decltype(ic)::value>(); });
+        rl.advance_fetch();
+        cl.advance_fetch();
+    };
+    auto fill_all = [&](_Float16 *st) {  // from register set 0 / by direct loads
+        static_for<RLT::NFILL>([&](auto ic) { rl.template fill_piece<0, decltype(ic)::value>(st); });
+        static_for<CLT::NFILL>([&](auto ic) { cl.template fill_piece<0, decltype(ic)::value>(st + A_H); });
+        rl.advance_fill();
+        cl.advance_fill();
+    };
+    typedef std::integral_constant<int, 0> Slot0;
+    typedef std::integral_constant<int, 1> Slot1;
+
+    // Prologue: tiles 0 .. S-2 into stages 0 .. S-2; the register path then holds tiles S-1 and S in
+    // its two register sets.  Everything has landed before the first barrier.
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s) {
+        if (s < T) {
+            fetch_all(Slot0());
+            fill_all(stage(s));
+        }
+    }
+    if (S - 1 < T) fetch_all(Slot0());
+    if (S < T) fetch_all(Slot1());
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+
+    HFrag<Cfg> fr[2];
+    if (T > 0)
+        static_for<Cfg::MB + Cfg::NB>([&](auto pc) {
+            hload_frag_piece<Cfg, RLT::LD, CLT::LD, 0, decltype(pc)::value>(fr[0], smem, smem + A_H, a_off, b_off);
+        });
+
+    int cs = 0, fill = S - 1, t = 0;
+    // steady state: a tile to fill, one to fetch (register path: tile t + S + 1) and a next one, for both
+    // halves of the trip
+    while (t + S + 2 < T) {
+        htile_iter_dma<Cfg, 0, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), A_H, a_off, b_off);
+        cs = next_of(cs);
+        fill = next_of(fill);
+        htile_iter_dma<Cfg, 1, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), A_H, a_off, b_off);
+        cs = next_of(cs);
+        fill = next_of(fill);
+        t += 2;
+    }
+    for (; t < T; t += 2) {
+        htile_iter_dma<Cfg, 0, false>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), A_H, a_off, b_off,
+                                      t + S - 1 < T, t + S + 1 < T, t + 1 < T);
+        cs = next_of(cs);
+        fill = next_of(fill);
+        if (t + 1 < T) {
+            htile_iter_dma<Cfg, 1, false>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), A_H, a_off, b_off,
+                                          t + S < T, t + S + 2 < T, t + 2 < T);
+            cs = next_of(cs);
+            fill = next_of(fill);
+        }
+    }
+
+    if (!combine_slices<Cfg>(acc, g.split, w)) return;
+    hstore_tile<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
+        g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
+    }
+}
+
+template <class Cfg>
+int launch_hgemm_mfma16_dma(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
+{
+    const int tiles = g.tiles_m * g.tiles_n;
+    const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
+    if (a_kcontig && b_kcontig)
+        hipLaunchKernelGGL((hgemm_mfma16_dma_kernel<Cfg, true, true>), grid, block, 0, stream, g);
+    else if (a_kcontig)
+        hipLaunchKernelGGL((hgemm_mfma16_dma_kernel<Cfg, true, false>), grid, block, 0, stream, g);
+    else if (b_kcontig)
+        hipLaunchKernelGGL((hgemm_mfma16_dma_kernel<Cfg, false, true>), grid, block, 0, stream, g);
+    else
+        return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
 template <class Cfg>
 int launch_hgemm_mfma16(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
 {
@@ -432,7 +732,8 @@ int launch_hgemm_mfma16(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipS
 struct HCfgDesc {
     const char *name;
     int BM, BN, BK, NT, lds_bytes;
-    int (*launch)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);
+    int (*launch)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);      // all loads through registers
+    int (*launch_dma)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);  // operands stored along k: global -> LDS
 };
 constexpr int kNumHCfg = 3;
 const HCfgDesc &hcfg_desc(int i);  // defined in hgemm_instance.hip

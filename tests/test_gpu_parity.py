@@ -678,7 +678,7 @@ def test_hgemm_4096_sampled(dm, torch):
 
 @pytest.mark.parametrize("tA,tB", TRANS)
 @pytest.mark.parametrize("K", [32, 64, 96, 128, 160, 192, 224, 256, 288, 512])
-@pytest.mark.parametrize("path", [1, 2, 3])
+@pytest.mark.parametrize("path", [1, 2, 3, 17, 19])
 def test_hgemm_fp16_instruction_k_ranges(dm, torch, tA, tB, K, path):
     """The FP16-input matrix-instruction kernels (8-wave and 4-wave tile) over every prologue / steady / drain
     combination of K tiles."""
@@ -688,7 +688,7 @@ def test_hgemm_fp16_instruction_k_ranges(dm, torch, tA, tB, K, path):
 
 
 @pytest.mark.parametrize("tA,tB", TRANS)
-@pytest.mark.parametrize("path", [1, 2, 3])
+@pytest.mark.parametrize("path", [1, 2, 3, 18])
 def test_hgemm_fp16_instruction_shapes(dm, torch, tA, tB, path):
     dm.dmath_set_hgemm_path(path)
     m_odd = 37 if tA == 0 else 40          # an operand stored along its own index needs a multiple of 8
@@ -711,7 +711,7 @@ def test_hgemm_fp16_instruction_conditions(dm, torch):
     assert dm.dmath_hgemm(0, 0, 64, 60, 64, 1.0, t, 64, t, 64, 0.0, t, 64) == dm.ERR_UNSUPPORTED      # N % 8, B along n
     assert dm.dmath_hgemm(0, 0, 64, 64, 64, 1.0, t[1:], 64, t, 64, 0.0, t, 64) == dm.ERR_UNSUPPORTED  # alignment
     assert dm.dmath_hgemm(0, 0, 64, 64, 64, 1.0, t, 68, t, 64, 0.0, t, 64) == dm.ERR_UNSUPPORTED      # lda % 8
-    assert dm.dmath_set_hgemm_path(4) == dm.ERR_INVALID_ARG
+    assert dm.dmath_set_hgemm_path(4) == dm.ERR_INVALID_ARG and dm.dmath_set_hgemm_path(16) == dm.ERR_INVALID_ARG
     dm.dmath_set_hgemm_path(0)             # the widening kernel takes all of them
     run_hgemm_case(dm, torch, 0, 0, 64, 64, 64, seed=1)
     dm.dmath_set_hgemm_path(-1)
@@ -724,7 +724,7 @@ def test_hgemm_paths_agree_on_integers(dm, torch):
     A = torch.from_numpy(rng.integers(-2, 3, size=(M, K)).astype(np.float16)).cuda()
     B = torch.from_numpy(rng.integers(-2, 3, size=(K, N)).astype(np.float16)).cuda()
     out = []
-    for path in (0, 1, 2, 3):
+    for path in (0, 1, 2, 3, 17):
         dm.dmath_set_hgemm_path(path)
         C = torch.zeros((M, N), dtype=torch.float16, device="cuda")
         dm.check(dm.dmath_hgemm(0, 0, M, N, K, 1.0, A, K, B, N, 0.0, C, N))
