@@ -852,3 +852,76 @@ def test_other_entry_points_on_a_side_stream(dm, torch):
     assert np.array_equal(C16.cpu().numpy().astype(np.float64), want)
     assert np.array_equal(C64.cpu().numpy(), want)
     assert np.array_equal(C32.cpu().numpy().astype(np.float64), want)
+
+
+# ------------------------------------------------------------------ seeded random sweeps of shapes and strides
+
+def _rand_gemm_args(rng, big=False):
+    hi = 700 if big else 200
+    M, N, K = (int(rng.integers(1, hi)) for _ in range(3))
+    tA, tB = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+    alpha = float(rng.choice([1.0, -1.0, 0.5, 2.0, 0.0]))
+    beta = float(rng.choice([0.0, 1.0, -0.5, 2.0]))
+    ld_extra = tuple(int(rng.choice([0, 0, 1, 3, 4, 8])) for _ in range(3))
+    lead = tuple(int(rng.choice([0, 0, 0, 1, 2, 4])) for _ in range(3))
+    return dict(tA=tA, tB=tB, M=M, N=N, K=K, alpha=alpha, beta=beta, ld_extra=ld_extra, lead=lead)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_gemm_shapes_every_precision(dm, torch, seed):
+    rng = np.random.default_rng(1000 + seed)
+    for i in range(12):
+        a = _rand_gemm_args(rng, big=(i % 4 == 0))
+        run_gemm_case(dm, torch, a["tA"], a["tB"], a["M"], a["N"], a["K"], alpha=a["alpha"], beta=a["beta"],
+                      ld_extra=a["ld_extra"], lead=a["lead"], seed=seed * 100 + i, c_nan=(a["beta"] == 0.0))
+        run_hgemm_case(dm, torch, a["tA"], a["tB"], a["M"], a["N"], a["K"], alpha=a["alpha"], beta=a["beta"],
+                       ld_extra=a["ld_extra"], lead=a["lead"], seed=seed * 100 + i)
+        run_dgemm_case(dm, torch, a["tA"], a["tB"], a["M"], a["N"], a["K"], alpha=a["alpha"], beta=a["beta"],
+                       ld_extra=a["ld_extra"], lead=a["lead"], seed=seed * 100 + i)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_random_hgemm_shapes_on_the_fp16_instruction(dm, torch, seed):
+    """Shapes that satisfy the conditions of the FP16-input kernels (multiples of 8, K of 32, aligned)."""
+    rng = np.random.default_rng(2000 + seed)
+    for i in range(10):
+        M, N = 8 * int(rng.integers(1, 90)), 8 * int(rng.integers(1, 90))
+        K = 32 * int(rng.integers(1, 20))
+        tA, tB = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        dm.dmath_set_hgemm_path(int(rng.choice([-1, 1, 2, 3, 17, 18, 19])))
+        dm.dmath_set_override(-1, int(rng.choice([-1, -1, 2, 5])))
+        run_hgemm_case(dm, torch, tA, tB, M, N, K, alpha=float(rng.choice([1.0, 0.5])), beta=float(rng.choice([0.0, 1.0])),
+                       ld_extra=tuple(8 * int(rng.integers(0, 3)) for _ in range(3)),
+                       lead=(8 * int(rng.integers(0, 2)), 8 * int(rng.integers(0, 2)), int(rng.integers(0, 3))),
+                       seed=seed * 50 + i, ints=(i % 3 == 0), exact=(i % 3 == 0))
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_random_convolution_shapes_forward_and_gradients(dm, torch, seed):
+    rng = np.random.default_rng(3000 + seed)
+    for i in range(8):
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        pad = (int(rng.integers(0, R)), int(rng.integers(0, S)))
+        stride = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+        H = int(rng.integers(max(1, R - 2 * pad[0]), 20))
+        W = int(rng.integers(max(1, S - 2 * pad[1]), 20))
+        shape = dict(N=int(rng.integers(1, 5)), C=int(rng.choice([1, 3, 16, 20, 32])), H=H, W=W,
+                     Kout=int(rng.choice([1, 5, 16, 40])), R=R, S=S, pad=pad, stride=stride)
+        alpha, beta = float(rng.choice([1.0, 0.5])), float(rng.choice([0.0, 1.0, -2.0]))
+        run_conv_case(dm, torch, alpha=alpha, beta=beta, seed=seed * 40 + i, lead=int(rng.integers(0, 3)), **shape)
+        run_conv_bwd_data_case(dm, torch, alpha=alpha, beta=beta, seed=seed * 40 + i, lead=int(rng.integers(0, 3)), **shape)
+        run_conv_bwd_filter_case(dm, torch, alpha=alpha, beta=beta, seed=seed * 40 + i, lead=int(rng.integers(0, 3)), **shape)
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_random_panel_lists(dm, torch, seed):
+    rng = np.random.default_rng(4000 + seed)
+    for i in range(8):
+        M, N = int(rng.integers(1, 300)), int(rng.integers(1, 300))
+        K = int(rng.choice([16, 32, 48, 7, 20]))
+        P = int(rng.integers(1, 9))
+        if i % 2 == 0:      # the fused path needs multiples of 4 where operands run along their own index
+            M, N = 4 * (M // 4 + 1), 4 * (N // 4 + 1)
+        run_gemm_panels_case(dm, torch, int(rng.integers(0, 2)), int(rng.integers(0, 2)), M, N, K, P,
+                             alpha=float(rng.choice([1.0, -0.5])), beta=float(rng.choice([0.0, 1.0])),
+                             ld_extra=tuple(4 * int(rng.integers(0, 2)) for _ in range(3)), seed=seed * 30 + i)
