@@ -76,6 +76,17 @@ def _time_steps(torch, step, steps, warmup):
     return e0.elapsed_time(e1) / steps, (t1 - t0) * 1e3 / steps
 
 
+def _cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def _cpu_baseline_gemm(oracle, call, arrays, budget_s=15.0):
     """The oracle as it stands on a bounded sample: the first R rows of C (all N columns, full K)."""
     A, B = arrays[call.A], arrays[call.B]
@@ -96,7 +107,7 @@ def _cpu_baseline_gemm(oracle, call, arrays, budget_s=15.0):
     t = run(rows)
     flop = 2.0 * rows * call.N * call.K
     return {
-        "value": flop / t / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "value": flop / t / 1e12, "unit": "TFLOP/s", "cores": threads, "cpu_model": _cpu_model(), "kind": "oracle",
         "sample": "first %d of %d rows of C (all %d columns, full K=%d), FP64 sums plus the magnitude sums, %.1f s"
                   % (rows, call.M, call.N, call.K, t),
     }
@@ -121,7 +132,7 @@ def _cpu_baseline_conv(oracle, wl, budget_s=15.0):
     npts = int(min(total, max(probe, probe * budget_s / t_probe)))
     t = run(npts)
     return {
-        "value": 2.0 * npts * K / t / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "value": 2.0 * npts * K / t / 1e12, "unit": "TFLOP/s", "cores": threads, "cpu_model": _cpu_model(), "kind": "oracle",
         "sample": "%d random output elements of %d (all %d taps each), FP64 sums plus the magnitude sums, %.1f s"
                   % (npts, total, K, t),
     }
