@@ -43,7 +43,12 @@
  * file to produce the expected value (integer-exact cases against int64
  * arithmetic, identity / permutation / rank-1 / all-ones closed forms,
  * transposition identities, delta filters, tap-count closed forms, brute force
- * in Python, and library float64 matmul / conv2d).
+ * in Python, and library float64 matmul / conv2d; for the gradients the adjoint
+ * identity and torch.nn.grad; for the panel sum the product of concatenations;
+ * for half storage numpy's own binary16 conversion on all 65536 patterns; for
+ * double precision exact rational arithmetic and cancellation cases that FP64
+ * accumulation gets wrong).  Each has a hand-worked fixture under
+ * tests/golden/ where the paper prints no example of its own.
  */
 #include <math.h>
 #include <stddef.h>
