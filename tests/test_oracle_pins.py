@@ -441,6 +441,25 @@ def test_half_bound_formula():
 
 # ----------------------------------------------------------------------------- double precision
 
+def test_dgemm_hand_worked_fixture():
+    raw = {}
+    with open(os.path.join(GOLDEN, "dgemm_hand_worked.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                key, *vals = line.split()
+                raw[key] = vals
+    M, N, K = int(raw["M"][0]), int(raw["N"][0]), int(raw["K"][0])
+    A = np.array([float.fromhex(v) for v in raw["A"]]).reshape(M, K)
+    B = np.array([float.fromhex(v) for v in raw["B"]]).reshape(K, N)
+    want = np.array([float.fromhex(v) for v in raw["ref"]]).reshape(M, N)
+    for tA, tB in itertools.product((0, 1), (0, 1)):
+        a = np.ascontiguousarray(A.T if tA else A)
+        b = np.ascontiguousarray(B.T if tB else B)
+        ref, _ = oracle.dgemm(tA, tB, M, N, K, 1.0, a, a.shape[1], b, b.shape[1])
+        assert np.array_equal(ref, want), (tA, tB, [x.hex() for x in ref.ravel()])
+
+
 def test_dgemm_accumulates_wider_than_double():
     assert oracle.long_double_digits() >= 64
     # 2^60 + 1 - 2^60 summed left to right: FP64 accumulation loses the 1, the oracle must not
