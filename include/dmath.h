@@ -112,6 +112,8 @@ dmath_status dmath_hgemm(dmath_op transA, dmath_op transB,
                          float beta, uint16_t *C, int64_t ldc,
                          void *stream);
 dmath_status dmath_set_hgemm_path(int path);
+/* Workspace dmath_hgemm would like for this shape (either kernel; 0 if it would not split). */
+size_t dmath_hgemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K);
 
 /*
  * The same multiply in double precision (section "Precisions": single and double precision are the

@@ -320,6 +320,34 @@ bool prepare_split(const Plan &p, int64_t tiles, int64_t M, int64_t N, void *ws,
 
 using namespace dmath;
 
+// Tile configuration and split-K factor of the FP16-input kernels for a shape (this thread's forced path
+// and split included).  Automatic: the 256 x 256 tile once it fills a good part of the device, else the
+// 128 x 128 tile; few tiles: K is cut so that the slices fill the compute units (plain split-K with FP32
+// slices), as far as `avail` bytes of workspace allow.
+int hgemm_tile_choice(int64_t M, int64_t N)
+{
+    if (g_state.hgemm_path >= 1) return g_state.hgemm_path - 1;
+    return ceil_div(M, 256) * ceil_div(N, 256) < 96 ? 2 : 0;
+}
+
+int64_t hgemm_split_choice(int hidx, int64_t M, int64_t N, int64_t K, size_t avail)
+{
+    const HCfgDesc &h = hcfg_desc(hidx);
+    const int64_t tiles = ceil_div(M, h.BM) * ceil_div(N, h.BN), ktiles = K / h.BK;
+    int64_t s = 1;
+    if (g_state.force_split >= 1)
+        s = g_state.force_split;
+    else if (tiles < kNumCU / 2)
+        s = kNumCU / tiles;
+    else if (hidx == 2 && tiles < kNumCU)
+        s = 2 * kNumCU / tiles;  // two of the small workgroups fit a compute unit
+    if (s > kMaxSplits) s = kMaxSplits;
+    if (s > ktiles / 2) s = ktiles / 2;
+    const size_t slice_bytes = (size_t)M * (size_t)N * sizeof(float);
+    if (s > 1 && (size_t)s * slice_bytes > avail) s = (int64_t)(avail / slice_bytes);
+    return s < 2 ? 1 : s;
+}
+
 // Body of dmath_gemm (T = float) and dmath_hgemm (T = _Float16: same kernels, operands widened on the
 // way into LDS, result rounded once on the way out).
 template <class T>
@@ -363,31 +391,15 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     if constexpr (kHalf) {
         // The FP16-input matrix instruction computes the same FP32 sums of exact products 16 times
         // faster; its kernel needs whole K tiles and 16-byte chunks everywhere.
-        // automatic: the 256 x 256 tile once it fills a good part of the device, else the 128 x 128 tile
-        int hidx = g_state.hgemm_path >= 1 ? g_state.hgemm_path - 1 : 0;
-        if (g_state.hgemm_path < 1 && ceil_div(M, 256) * ceil_div(N, 256) < 96) hidx = 2;
+        const int hidx = hgemm_tile_choice(M, N);
         const HCfgDesc &h = hcfg_desc(hidx);
         const bool fits = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0 && K % h.BK == 0 &&
                           (a_k || M % 8 == 0) && (b_k || N % 8 == 0);
         if (g_state.hgemm_path >= 1 && !fits) return fail(DMATH_ERR_UNSUPPORTED, 0);
         if (fits && g_state.hgemm_path != 0 && g_state.force_cfg < 0) {
             const int64_t tiles_m = ceil_div(M, h.BM), tiles_n = ceil_div(N, h.BN), tiles = tiles_m * tiles_n;
-            const int64_t ktiles = K / h.BK;
             if (tiles * 64 > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
-            // few tiles: cut K so that the slices fill the compute units (plain split-K, FP32 slices)
-            int64_t s = 1;
-            if (g_state.force_split >= 1)
-                s = g_state.force_split;
-            else if (tiles < kNumCU / 2)
-                s = kNumCU / tiles;
-            else if (hidx == 2 && tiles < kNumCU)
-                s = 2 * kNumCU / tiles;  // two of the small workgroups fit a compute unit
-            if (s > kMaxSplits) s = kMaxSplits;
-            if (s > ktiles / 2) s = ktiles / 2;
-            const size_t avail = g_state.ws ? g_state.ws_bytes : 0;
-            const size_t slice_bytes = (size_t)M * (size_t)N * sizeof(float);
-            if (s > 1 && s * slice_bytes > avail) s = (int64_t)(avail / slice_bytes);
-            if (s < 2) s = 1;
+            const int64_t s = hgemm_split_choice(hidx, M, N, K, g_state.ws ? g_state.ws_bytes : 0);
             HGemmArgs g;
             g.A = A;
             g.B = B;
@@ -546,6 +558,18 @@ size_t dmath_gemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, i
     const Plan p = resolve_plan(M, N, K, 0, true);
     const CfgDesc &d = desc(p.cfg);
     return plan_bytes(p, ceil_div(M, d.BM) * ceil_div(N, d.BN), M, N);
+}
+
+size_t dmath_hgemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    size_t need = dmath_gemm_workspace_bytes(transA, transB, M, N, K);  // the widening kernels plan like dmath_gemm
+    if (g_state.hgemm_path != 0 && K % 32 == 0) {
+        const int64_t s = hgemm_split_choice(hgemm_tile_choice(M, N), M, N, K, ~(size_t)0);
+        const size_t fast = s > 1 ? (size_t)s * (size_t)M * (size_t)N * sizeof(float) : 0;
+        if (fast > need) need = fast;
+    }
+    return need;
 }
 
 dmath_status dmath_gemm_plan(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, int *tile_config,

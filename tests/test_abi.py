@@ -111,3 +111,14 @@ def test_workspace_and_override_api(dm):
     forced = dm.dmath_gemm_workspace_bytes(0, 0, 256, 4096, 4096)
     assert 4 * 256 * 4096 * 4 <= forced <= 4 * 256 * 4096 * 4 + 4096  # 4 slices of every tile + counters
     assert dm.dmath_set_override(-1, -1) == dm.OK
+
+
+def test_hgemm_workspace_query_is_host_side_only():
+    from paper_1604_01416_amd import dmath as dm
+    assert dm.dmath_hgemm_workspace_bytes(0, 0, 0, 16, 16) == 0
+    # a ragged K rules the FP16-input kernels out: the widening kernels plan like dmath_gemm
+    assert dm.dmath_hgemm_workspace_bytes(0, 0, 256, 4096, 4090) == dm.dmath_gemm_workspace_bytes(0, 0, 256, 4096, 4090)
+    # skinny product: FP32 slices of the whole output, a whole number of them
+    need = dm.dmath_hgemm_workspace_bytes(0, 0, 256, 4096, 4096)
+    assert need > 0 and need % (256 * 4096 * 4) == 0
+    assert dm.dmath_hgemm_workspace_bytes(0, 0, 8192, 8192, 8192) == dm.dmath_gemm_workspace_bytes(0, 0, 8192, 8192, 8192)
