@@ -270,6 +270,34 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
         yoff[bn] = n * a.Kout * a.PQ + (gc - n * a.PQ);
     }
     const bool full_vec = Cfg::NB == 4 && a.yvec && (col + Cfg::NB <= a.NPQ);
+    if constexpr (Cfg::NB == 4) {
+        if (full_vec && a.beta != 0.0f) {
+            // old values fetched kEpiRows rows at a time before the first use (see store_tile_rowmajor)
+#pragma unroll
+            for (int bm = 0; bm < Cfg::MB; ++bm) {
+#pragma unroll
+                for (int r0 = 0; r0 < 16; r0 += kEpiRows) {
+                    CV old[kEpiRows];
+#pragma unroll
+                    for (int j = 0; j < kEpiRows; ++j) {
+                        const int r = r0 + j;
+                        const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+                        old[j] = *reinterpret_cast<const CV *>(a.y + yoff[0] + (row < a.Kout ? row : a.Kout - 1) * a.PQ);
+                    }
+#pragma unroll
+                    for (int j = 0; j < kEpiRows; ++j) {
+                        const int r = r0 + j;
+                        const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+                        CV o;
+#pragma unroll
+                        for (int bn = 0; bn < 4; ++bn) o[bn] = __builtin_fmaf(a.beta, old[j][bn], a.alpha * acc[bm][bn][r]);
+                        if (row < a.Kout) *reinterpret_cast<CV *>(a.y + yoff[0] + row * a.PQ) = o;
+                    }
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int bm = 0; bm < Cfg::MB; ++bm) {
 #pragma unroll

@@ -250,6 +250,27 @@ __device__ __forceinline__ void dstore_tile(const doublex4 (&acc)[Cfg::MB][Cfg::
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 15, h = lane >> 4;
     const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
+    if (beta != 0.0 && m0 + Cfg::BM <= M && n0 + Cfg::BN <= N) {
+        // Tile wholly inside C: the old values of a block row are fetched before the first is used, so
+        // that the epilogue does not wait out the memory latency once per element.
+        double *base = C + (m0 + wm0 + 2 * h) * ldc + (n0 + wn0 + 2 * j);
+#pragma unroll
+        for (int bm = 0; bm < Cfg::MB; ++bm) {
+            double old[4][Cfg::NB];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int bn = 0; bn < Cfg::NB; ++bn)
+                    old[r][bn] = base[(32 * (bm / 2) + 8 * r + (bm % 2)) * ldc + 32 * (bn / 2) + (bn % 2)];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int bn = 0; bn < Cfg::NB; ++bn)
+                    base[(32 * (bm / 2) + 8 * r + (bm % 2)) * ldc + 32 * (bn / 2) + (bn % 2)] =
+                        __builtin_fma(beta, old[r][bn], alpha * acc[bm][bn][r]);
+        }
+        return;
+    }
 #pragma unroll
     for (int bm = 0; bm < Cfg::MB; ++bm)
 #pragma unroll

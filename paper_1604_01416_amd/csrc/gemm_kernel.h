@@ -20,6 +20,7 @@ struct GemmArgsT {
     int tiles_m, tiles_n;
     int cvec;         // C rows allow aligned NB-wide vector access
     SplitPlan split;
+    unsigned stagger_ticks = 0;  // 0, or how long workgroups 256..511 wait before they start (100 MHz ticks)
     unsigned long long *clock_probe;  // optional: 4 stamps from each of workgroups 0..7 (see dmath_set_clock_probe)
 };
 typedef GemmArgsT<float> GemmArgs;
@@ -46,6 +47,7 @@ struct ColLoaderSel<Cfg, false, VEC, T> {
 // predication.  Lane (i, h) owns, for block row bm and accumulator register r, the NB consecutive
 // columns n0 + wn0 + NB*i .. of row m0 + wm0 + MB*(8*(r/4) + 4*h + r%4) + bm.  A slice of a plain
 // split-K launch writes its raw sums to its M x N array in the workspace instead.
+constexpr int kEpiRows = 8;  // old values of C fetched per batch in the epilogue (4, 8 and 16 measure alike)
 template <class Cfg>
 __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::MB][Cfg::NB], float *C, int64_t ldc_,
                                                     int64_t M, int64_t N, float alpha_, float beta_, bool cvec,
@@ -61,6 +63,36 @@ __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::M
     const int64_t ldc = raw_slice ? N : ldc_;
     const float alpha = raw_slice ? 1.0f : alpha_, beta = raw_slice ? 0.0f : beta_;
     const bool full_vec = (raw_slice ? (N % 4 == 0) : cvec) && (col + Cfg::NB <= N);
+    if constexpr (Cfg::NB > 1) {
+        if (full_vec && beta != 0.0f) {
+            // Old values are fetched eight rows at a time before any of them is used: one load per row
+            // followed by its use would leave a single 16-byte request per wave in flight and make the
+            // epilogue wait out the memory latency 16*MB times.  Rows past M read row M-1 (never stored).
+#pragma unroll
+            for (int bm = 0; bm < Cfg::MB; ++bm) {
+#pragma unroll
+                for (int r0 = 0; r0 < 16; r0 += kEpiRows) {
+                    CV old[kEpiRows];
+#pragma unroll
+                    for (int j = 0; j < kEpiRows; ++j) {
+                        const int r = r0 + j;
+                        const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+                        old[j] = *reinterpret_cast<const CV *>(Cz + (row < M ? row : M - 1) * ldc + col);
+                    }
+#pragma unroll
+                    for (int j = 0; j < kEpiRows; ++j) {
+                        const int r = r0 + j;
+                        const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+                        CV o;
+#pragma unroll
+                        for (int bn = 0; bn < Cfg::NB; ++bn) o[bn] = __builtin_fmaf(beta, old[j][bn], alpha * acc[bm][bn][r]);
+                        if (row < M) *reinterpret_cast<CV *>(Cz + row * ldc + col) = o;
+                    }
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int bm = 0; bm < Cfg::MB; ++bm) {
 #pragma unroll
@@ -118,6 +150,35 @@ __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::M
     const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
     const int64_t col = n0 + wn0 + Cfg::NB * i;
     const bool full_vec = cvec && Cfg::NB > 1 && (col + Cfg::NB <= N);
+    if constexpr (Cfg::NB > 1) {
+        if (full_vec && beta != 0.0f) {
+            // old values fetched kEpiRows rows at a time before the first use, as in the FP32 epilogue
+#pragma unroll
+            for (int bm = 0; bm < Cfg::MB; ++bm) {
+#pragma unroll
+                for (int r0 = 0; r0 < 16; r0 += kEpiRows) {
+                    HV old[kEpiRows];
+#pragma unroll
+                    for (int j = 0; j < kEpiRows; ++j) {
+                        const int r = r0 + j;
+                        const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+                        old[j] = *reinterpret_cast<const HV *>(C + (row < M ? row : M - 1) * ldc + col);
+                    }
+#pragma unroll
+                    for (int j = 0; j < kEpiRows; ++j) {
+                        const int r = r0 + j;
+                        const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
+                        HV o;
+#pragma unroll
+                        for (int bn = 0; bn < Cfg::NB; ++bn)
+                            o[bn] = (_Float16)__builtin_fmaf(beta, (float)old[j][bn], alpha * acc[bm][bn][r]);
+                        if (row < M) *reinterpret_cast<HV *>(C + row * ldc + col) = o;
+                    }
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int bm = 0; bm < Cfg::MB; ++bm) {
 #pragma unroll
@@ -165,6 +226,13 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
     if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
         g.clock_probe[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();      // shader-clock counter
         g.clock_probe[blockIdx.x * 4 + 1] = __builtin_amdgcn_s_memrealtime();  // fixed 100 MHz counter
+    }
+    // Second workgroup of every compute unit (the dispatcher places workgroups 0..255 one per unit and
+    // the next 256 beside them): held back so that the two run out of phase and one's epilogue falls
+    // into the other's K loop.  The wait is on the free-running 100 MHz counter and always ends.
+    if (g.stagger_ticks != 0 && blockIdx.x >= kNumCU && blockIdx.x < 2 * kNumCU) {
+        const uint64_t t0 = __builtin_amdgcn_s_memrealtime();
+        while (__builtin_amdgcn_s_memrealtime() - t0 < (uint64_t)g.stagger_ticks) __builtin_amdgcn_s_sleep(16);
     }
     const int tiles = g.tiles_m * g.tiles_n;
     const WorkItem w = work_item(blockIdx.x, tiles, g.split);

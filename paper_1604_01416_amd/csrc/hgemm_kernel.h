@@ -351,6 +351,29 @@ __device__ __forceinline__ void hstore_tile(const floatx16 (&acc)[Cfg::MB][Cfg::
     const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
     const bool raw = split.plain && w.nslice > 1;
     float *Z = raw ? split.partials + (int64_t)w.slice * split.slice_stride : nullptr;
+    if (!raw && beta != 0.0f && m0 + Cfg::BM <= M && n0 + Cfg::BN <= N) {
+        // Tile wholly inside C: the old values of eight rows are fetched before the first is used, so
+        // that the epilogue does not wait out the memory latency once per row.
+        _Float16 *base = C + (m0 + wm0 + 4 * h) * ldc + (n0 + wn0 + i);
+#pragma unroll
+        for (int bm = 0; bm < Cfg::MB; ++bm)
+#pragma unroll
+            for (int r0 = 0; r0 < 16; r0 += 8) {
+                _Float16 old[8][Cfg::NB];
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int bn = 0; bn < Cfg::NB; ++bn)
+                        old[j][bn] = base[(32 * bm + 8 * ((r0 + j) / 4) + ((r0 + j) % 4)) * ldc + 32 * bn];
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int bn = 0; bn < Cfg::NB; ++bn)
+                        base[(32 * bm + 8 * ((r0 + j) / 4) + ((r0 + j) % 4)) * ldc + 32 * bn] =
+                            (_Float16)__builtin_fmaf(beta, (float)old[j][bn], alpha * acc[bm][bn][r0 + j]);
+            }
+        return;
+    }
 #pragma unroll
     for (int bm = 0; bm < Cfg::MB; ++bm)
 #pragma unroll

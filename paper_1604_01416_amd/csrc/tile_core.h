@@ -68,6 +68,7 @@ template <> struct VecOf<1> { typedef float type; };
 template <> struct VecOf<2> { typedef floatx2 type; };
 template <> struct VecOf<4> { typedef floatx4 type; };
 
+constexpr int kNumCU = 256;  // MI355X: compute units
 constexpr int kNumXcd = 8;  // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 
 // Tile configuration.  WM = BM / WAVES_M and WN = BN / WAVES_N are the wave tile.
