@@ -21,6 +21,7 @@ struct ThreadState {
     int force_split = -1;
     int hgemm_path = -1;
     bool hgemm_no_dma = false;  // dmath_set_hgemm_path(path + 16): the register-only variant of path
+    bool hgemm_no_k64 = false;  // dmath_set_hgemm_path(path + 32): global -> LDS loads with the K tile of 32
     int dgemm_cfg = -1;   // -1 automatic, else index of the FP64 tile configuration  // -1 automatic, 0 FP32 matrix instruction on widened operands, 1 FP16-input instruction
     int last_error_arg = 0;
     unsigned long long *clock_probe = nullptr;
@@ -436,7 +437,12 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
             // both operands stored along k: they go global -> LDS directly (unless the register-only kernel
             // is asked for); mixed products measured slower that way
             const bool dma = a_k && b_k && !g_state.hgemm_no_dma;
-            if ((dma ? h.launch_dma : h.launch)(g, a_k, b_k, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+            // with a K tile of 64 when there is such a kernel and K allows it: every cache line requested once
+            // (that kernel takes every orientation: an operand stored along its own index is read back
+            // with the transposing LDS read)
+            const bool k64 = h.launch_dma64 != nullptr && K % 64 == 0 && !g_state.hgemm_no_k64 && !g_state.hgemm_no_dma;
+            if ((k64 ? h.launch_dma64 : dma ? h.launch_dma : h.launch)(g, a_k, b_k, stream) != (int)hipSuccess)
+                return fail(DMATH_ERR_LAUNCH, 0);
             if (s > 1) {
                 const bool v4 = (N % 4 == 0) && g.cvec;
                 const int64_t items = v4 ? M * (N / 4) : M * N;
@@ -538,11 +544,14 @@ dmath_status dmath_set_override(int tile_config, int split_k)
 
 dmath_status dmath_set_hgemm_path(int path)
 {
+    const bool no_k64 = path >= 32;
+    if (no_k64) path -= 32;
     const bool no_dma = path >= 16;
     if (no_dma) path -= 16;
-    if (path < -1 || path > kNumHCfg || (no_dma && path < 1)) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (path < -1 || path > kNumHCfg || ((no_dma || no_k64) && path < 1)) return fail(DMATH_ERR_INVALID_ARG, 1);
     g_state.hgemm_path = path;
     g_state.hgemm_no_dma = no_dma;
+    g_state.hgemm_no_k64 = no_k64;
     return DMATH_OK;
 }
 

@@ -149,24 +149,25 @@ struct HLoaderN {
 // global_load_lds_dwordx4 writes the 16 bytes of lane l at (wave-uniform LDS address) + 16*l (checked on
 // the device), so one instruction fills 16 consecutive 64-byte rows of the swizzled image and each lane
 // fetches the chunk that belongs at its position.  No staging registers, no LDS store instructions.
-template <int BR, int BK, int NT, int LDK_UNUSED, int SLOTS_UNUSED>
+template <int BR, int BK, int NT>
 struct HLoaderKDma {
-    static constexpr bool DMA = true;
     static constexpr int NW = NT / 64;
     static constexpr int NP = BR / (16 * NW);      // instructions per thread and tile
-    static constexpr int NFILL = NP, NFETCH = 0;
+    static constexpr int NFILL = NP;
     static constexpr int LD = BK;
     static_assert(BK == 32 && BR % (16 * NW) == 0 && NP >= 1, "16 rows of 64 bytes per wave instruction");
-    const char *tile;
-    uint32_t off[NP];
-    int lds0;  // image offset (halves) of this wave's first row group
+    const char *tile;   // workgroup-uniform, kept in scalar registers
+    uint32_t off[NP];   // this lane's byte offsets from it
+    uint32_t wave_lds;  // byte offset of this wave's first row group inside the image
 
     __device__ __forceinline__ void init(const _Float16 *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
     {
         const int wave = tid / 64, lane = tid % 64;
         const int ch = (lane & 3) ^ ((lane >> 4) & 3);  // logical chunk stored at this lane's position
-        tile = reinterpret_cast<const char *>(base + r0 * ld + k0);
-        lds0 = __builtin_amdgcn_readfirstlane(wave * 16 * LD);
+        const uint64_t t0 = reinterpret_cast<uint64_t>(base + r0 * ld + k0);  // the same in every lane
+        tile = reinterpret_cast<const char *>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(t0 >> 32)) << 32) |
+                                              (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)t0));
+        wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane(wave * 16 * LD * 2);
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             int64_t lr = (wave + p * NW) * 16 + lane / 4;
@@ -178,58 +179,23 @@ struct HLoaderKDma {
     {
         return row * LD + (((2 * ks + h) ^ ((row >> 2) & 3)) * 8);
     }
-    template <int SLOT, int I>
-    __device__ __forceinline__ void fill_piece(_Float16 *S) const
+    // image_lds: LDS byte address of this operand's image in the stage being filled.  LDS addresses are
+    // handled as integers here: through generic pointers every load paid a null check and a
+    // 64-bit add in scalar instructions, a dozen of them between two matrix instructions.
+    template <int I>
+    __device__ __forceinline__ void fill_piece(uint32_t image_lds) const
     {
         // Written as assembly on purpose: for the builtin form the compiler, which cannot tell which LDS
         // bytes a global -> LDS load writes, waits for all of them (vmcnt(0)) before every later LDS
         // read, which serialises the very loads this path is meant to keep in flight.  The waits are
-        // placed by hand instead (htile_iter_dma).  m0 = LDS byte address of lane 0's 16 bytes.
-#if defined(__HIP_DEVICE_COMPILE__)
-        typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
-        const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr)(S + lds0 + I * NW * 16 * LD);
-        const char *src = tile + off[I];
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+        // placed by hand instead (htile_iter_dma).  m0 = LDS byte address of lane 0's 16 bytes; the
+        // global address is the tile pointer in scalar registers plus the lane's 32-bit offset.
+        asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1"
                      :
-                     : "v"(src), "s"(__builtin_amdgcn_readfirstlane(dst))
-                     : "memory");
-#else
-        (void)S;
-#endif
+                     : "v"(off[I]), "s"(tile), "s"(image_lds + wave_lds), "n"(I * NW * 16 * LD * 2)
+                     : "memory", "scc");
     }
-    template <int SLOT, int I>
-    __device__ __forceinline__ void fetch_piece() {}
     __device__ __forceinline__ void advance_fill() { tile += BK * 2; }
-    __device__ __forceinline__ void advance_fetch() {}
-};
-
-// The register-path loader for an operand stored along its own index, under the fill / fetch names.
-template <int BR, int BK, int NT, int LDK, int SLOTS>
-struct HLoaderNReg : HLoaderN<BR, BK, NT, LDK, SLOTS> {
-    typedef HLoaderN<BR, BK, NT, LDK, SLOTS> Base;
-    static constexpr bool DMA = false;
-    static constexpr int NFILL = Base::NSTORE, NFETCH = Base::NLOAD;
-    template <int SLOT, int I>
-    __device__ __forceinline__ void fill_piece(_Float16 *S) const
-    {
-        Base::template store_piece<SLOT, I>(S);
-    }
-    template <int SLOT, int I>
-    __device__ __forceinline__ void fetch_piece()
-    {
-        Base::template load_piece<SLOT, I>();
-    }
-    __device__ __forceinline__ void advance_fill() {}
-    __device__ __forceinline__ void advance_fetch() { Base::advance(); }
-};
-
-template <class Cfg, bool KCONTIG, int BR>
-struct HDmaLoaderSel {
-    typedef HLoaderKDma<BR, Cfg::BK, Cfg::NT, Cfg::LDK, 2> type;
-};
-template <class Cfg, int BR>
-struct HDmaLoaderSel<Cfg, false, BR> {
-    typedef HLoaderNReg<BR, Cfg::BK, Cfg::NT, Cfg::LDK, 2> type;
 };
 
 template <class Cfg, bool KCONTIG, int BR, int SLOTS>
@@ -528,41 +494,38 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 constexpr int waitcnt_vm_lds0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
-// One K tile of the kernel with global -> LDS loads.  k step 0: fragments of k step 1, and stage `fill`
-// receives tile t + S - 1 (LDS-DMA loads for a copied operand, LDS stores from register set SLOT for a
-// transposed one).  Then the barrier, before which every wave waits until its own loads of tile t + 1
-// have landed (they were issued S - 2 iterations ago; WAIT_YOUNGER vector-memory operations issued
-// since may stay in flight).  k step 1: the next tile's first fragments, and the register-path loads
-// of tile t + S + 1.
-template <class Cfg, int SLOT, bool STEADY, class RL, class CL>
+// One K tile of the kernel with global -> LDS loads.  k step 0: fragments of k step 1, and the stage
+// at LDS byte address fill_lds receives tile t + S - 1.  Then the barrier, before which every wave
+// waits until its own loads of tile t + 1 have landed (they were issued S - 2 iterations ago; the
+// WAIT_YOUNGER loads issued since may stay in flight).  k step 1: the next tile's first fragments.
+template <class Cfg, bool STEADY, class RL, class CL>
 __device__ __forceinline__ void htile_iter_dma(RL &rl, CL &cl, HFrag<Cfg> (&fr)[2], floatx16 (&acc)[Cfg::MB][Cfg::NB],
-                                               const _Float16 *cur, const _Float16 *nxt, _Float16 *fill, int a_halves,
+                                               const _Float16 *cur, const _Float16 *nxt, uint32_t fill_lds,
                                                const int (&a_off)[2], const int (&b_off)[2], bool do_fill = true,
-                                               bool do_fetch = true, bool has_next = true)
+                                               bool has_next = true)
 {
     if constexpr (STEADY) {
         do_fill = true;
-        do_fetch = true;
         has_next = true;
     }
     constexpr int NMMA = Cfg::MB * Cfg::NB, NFRAG = Cfg::MB + Cfg::NB;
-    constexpr int NFILL = RL::NFILL + CL::NFILL, NFETCH = RL::NFETCH + CL::NFETCH;
+    constexpr int NFILL = RL::NFILL + CL::NFILL;
     constexpr int PER = (NFILL + NMMA - 1) / NMMA;
-    constexpr int NDMA = (RL::DMA ? RL::NFILL : 0) + (CL::DMA ? CL::NFILL : 0);
-    constexpr int WAIT_YOUNGER = (Cfg::STAGES - 2) * (NDMA + NFETCH);
-    static_assert(Cfg::KSTEPS == 2 && NFRAG <= NMMA && NFETCH <= NMMA && WAIT_YOUNGER < 64, "slots and counter range");
+    constexpr int A_H = Cfg::BM * RL::LD;
+    constexpr int WAIT_YOUNGER = (Cfg::STAGES - 2) * NFILL;
+    static_assert(Cfg::KSTEPS == 2 && NFRAG <= NMMA && WAIT_YOUNGER < 64, "slots and counter range");
     static_for<NMMA>([&](auto qc) {
         constexpr int q = decltype(qc)::value;
         hmma_one<Cfg, q>(fr[0], acc);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (q < NFRAG) hload_frag_piece<Cfg, RL::LD, CL::LD, 1, q>(fr[1], cur, cur + a_halves, a_off, b_off);
+        if constexpr (q < NFRAG) hload_frag_piece<Cfg, RL::LD, CL::LD, 1, q>(fr[1], cur, cur + A_H, a_off, b_off);
         if (do_fill) {
             static_for<PER>([&](auto ec) {
                 constexpr int st = q * PER + decltype(ec)::value;
                 if constexpr (st < RL::NFILL)
-                    rl.template fill_piece<SLOT, st>(fill);
+                    rl.template fill_piece<st>(fill_lds);
                 else if constexpr (st < NFILL)
-                    cl.template fill_piece<SLOT, st - RL::NFILL>(fill + a_halves);
+                    cl.template fill_piece<st - RL::NFILL>(fill_lds + A_H * 2);
             });
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -571,7 +534,6 @@ __device__ __forceinline__ void htile_iter_dma(RL &rl, CL &cl, HFrag<Cfg> (&fr)[
         rl.advance_fill();
         cl.advance_fill();
     }
-    // LDS stores of this iteration done; own loads of the tile read next have landed
     if constexpr (STEADY)
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(WAIT_YOUNGER));
     else
@@ -583,39 +545,32 @@ __device__ __forceinline__ void htile_iter_dma(RL &rl, CL &cl, HFrag<Cfg> (&fr)[
         hmma_one<Cfg, q>(fr[1], acc);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (q < NFRAG) {
-            if (has_next) hload_frag_piece<Cfg, RL::LD, CL::LD, 0, q>(fr[0], nxt, nxt + a_halves, a_off, b_off);
-        }
-        if constexpr (q < NFETCH) {
-            if (do_fetch) {
-                if constexpr (q < RL::NFETCH)
-                    rl.template fetch_piece<SLOT, q>();
-                else
-                    cl.template fetch_piece<SLOT, q - RL::NFETCH>();
-            }
+            if (has_next) hload_frag_piece<Cfg, RL::LD, CL::LD, 0, q>(fr[0], nxt, nxt + A_H, a_off, b_off);
         }
         __builtin_amdgcn_sched_barrier(0);
     });
-    if (do_fetch) {
-        rl.advance_fetch();
-        cl.advance_fetch();
-    }
 }
 
-// The kernel for products with operands stored along k: such an operand goes global -> LDS directly,
-// the other (if stored along its own index) through registers as in hgemm_mfma16_kernel.
-// Cfg::STAGES LDS stages (4: a load has two iterations to land).  Same requirements as above.
-// Measured at 8192^3: both operands direct (NT) 1167 TFLOP/s against 1121 for the register kernel;
-// one direct, one through registers (NN) 891 against 1101 (the compiler's own waits for the register
-// loads count the direct loads too and drain them early), so the host uses it for NT only.
-template <class Cfg, bool A_KCONTIG, bool B_KCONTIG>
+// The kernel for products with both operands stored along k: they go global -> LDS directly.
+// Cfg::STAGES LDS stages (4: a load has two iterations to land).  The steady loop is unrolled over the
+// stages so that every LDS address in it is a constant.  Same requirements as hgemm_mfma16_kernel.
+// A product with one operand direct and one through registers measured slower than the register
+// kernel (891 against 1101 TFLOP/s at 8192^3: the compiler's own waits for the register loads count
+// the direct loads too and drain them early), so there is no mixed form.
+template <class Cfg>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma_kernel(const HGemmArgs g)
 {
-    static_assert(A_KCONTIG || B_KCONTIG, "at least one operand takes the direct path");
-    typedef typename HDmaLoaderSel<Cfg, A_KCONTIG, Cfg::BM>::type RLT;
-    typedef typename HDmaLoaderSel<Cfg, B_KCONTIG, Cfg::BN>::type CLT;
+    typedef HLoaderKDma<Cfg::BM, Cfg::BK, Cfg::NT> RLT;
+    typedef HLoaderKDma<Cfg::BN, Cfg::BK, Cfg::NT> CLT;
     constexpr int S = Cfg::STAGES;
     constexpr int A_H = Cfg::BM * RLT::LD, B_H = Cfg::BN * CLT::LD, STAGE_H = A_H + B_H;
     __shared__ __attribute__((aligned(1024))) _Float16 smem[S * STAGE_H];
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lds_ptr)smem;
+#else
+    const uint32_t smem_lds = 0;
+#endif
 
     if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
         g.clock_probe[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();
@@ -648,35 +603,18 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma_kern
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
 
-    auto stage = [&](int s) { return smem + s * STAGE_H; };
-    auto next_of = [](int s) { return s + 1 == S ? 0 : s + 1; };
-    auto fetch_all = [&](auto slotc) {
-        constexpr int SL = decltype(slotc)::value;
-        static_for<RLT::NFETCH>([&](auto ic) { rl.template fetch_piece<SL, decltype(ic)::value>(); });
-        static_for<CLT::NFETCH>([&](auto ic) { cl.template fetch_piece<SL, decltype(ic)::value>(); });
-        rl.advance_fetch();
-        cl.advance_fetch();
-    };
-    auto fill_all = [&](_Float16 *st) {  // from register set 0 / by direct loads
-        static_for<RLT::NFILL>([&](auto ic) { rl.template fill_piece<0, decltype(ic)::value>(st); });
-        static_for<CLT::NFILL>([&](auto ic) { cl.template fill_piece<0, decltype(ic)::value>(st + A_H); });
+    auto fill_all = [&](uint32_t stage_lds) {
+        static_for<RLT::NFILL>([&](auto ic) { rl.template fill_piece<decltype(ic)::value>(stage_lds); });
+        static_for<CLT::NFILL>([&](auto ic) { cl.template fill_piece<decltype(ic)::value>(stage_lds + A_H * 2); });
         rl.advance_fill();
         cl.advance_fill();
     };
-    typedef std::integral_constant<int, 0> Slot0;
-    typedef std::integral_constant<int, 1> Slot1;
 
-    // Prologue: tiles 0 .. S-2 into stages 0 .. S-2; the register path then holds tiles S-1 and S in
-    // its two register sets.  Everything has landed before the first barrier.
+    // Prologue: tiles 0 .. S-2 into stages 0 .. S-2, all landed before the first barrier.
 #pragma unroll
     for (int s = 0; s < S - 1; ++s) {
-        if (s < T) {
-            fetch_all(Slot0());
-            fill_all(stage(s));
-        }
+        if (s < T) fill_all(smem_lds + s * STAGE_H * 2);
     }
-    if (S - 1 < T) fetch_all(Slot0());
-    if (S < T) fetch_all(Slot1());
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -687,29 +625,348 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma_kern
             hload_frag_piece<Cfg, RLT::LD, CLT::LD, 0, decltype(pc)::value>(fr[0], smem, smem + A_H, a_off, b_off);
         });
 
-    int cs = 0, fill = S - 1, t = 0;
-    // steady state: a tile to fill, one to fetch (register path: tile t + S + 1) and a next one, for both
-    // halves of the trip
-    while (t + S + 2 < T) {
-        htile_iter_dma<Cfg, 0, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), A_H, a_off, b_off);
-        cs = next_of(cs);
-        fill = next_of(fill);
-        htile_iter_dma<Cfg, 1, true>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), A_H, a_off, b_off);
-        cs = next_of(cs);
-        fill = next_of(fill);
+    int t = 0;
+    // steady state, one trip = S tiles (tile t + j is read from stage j): every iteration of the trip
+    // has a tile to fill and a next tile
+    while (t + 2 * S - 2 < T) {
+        static_for<S>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            htile_iter_dma<Cfg, true>(rl, cl, fr, acc, smem + j * STAGE_H, smem + ((j + 1) % S) * STAGE_H,
+                                      smem_lds + ((j + S - 1) % S) * STAGE_H * 2, a_off, b_off);
+        });
+        t += S;
+    }
+    // the last tiles of the range (t is a multiple of S here): the same iteration with its conditions
+    for (int cs = 0; t < T; ++t) {
+        const int nx = cs + 1 == S ? 0 : cs + 1, fill = cs == 0 ? S - 1 : cs - 1;
+        htile_iter_dma<Cfg, false>(rl, cl, fr, acc, smem + cs * STAGE_H, smem + nx * STAGE_H,
+                                   smem_lds + fill * STAGE_H * 2, a_off, b_off, t + S - 1 < T, t + 1 < T);
+        cs = nx;
+    }
+
+    if (!combine_slices<Cfg>(acc, g.split, w)) return;
+    hstore_tile<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
+        g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same product with a K tile of 64.  A row of a 32-wide K tile is 64 bytes, half a 128-byte
+// cache line: each line is then requested twice, by consecutive K tiles, and by the time of the
+// second request the 32 KB first-level cache has seen 64 KB of other lines, so the line comes from
+// L2 again (counters at 8192^3: 133.8 M line requests to L2 against 67.1 M for the vendor kernel,
+// whose K tile is 64).  That doubled traffic, not the load instructions' latency, issue slots or
+// scalar bookkeeping, is what the loads cost here (a timing-only variant without them: +26 %).
+// With 128-byte rows every line is requested once.  Two stages of 64 KB; four k steps per tile.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_>
+struct HTile64Cfg {
+    static constexpr int BM = BM_, BN = BN_, BK = 64;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = 2;
+    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int MB = WM / 32, NB = WN / 32;
+    static constexpr int A_HALVES = BM * BK, B_HALVES = BN * BK, STAGE_HALVES = A_HALVES + B_HALVES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_HALVES * 2;
+    static constexpr int KSTEPS = BK / 16;
+    static constexpr int MIN_WAVES = (NT / 64 + 3) / 4;
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && LDS_BYTES <= 160 * 1024, "wave tile is made of 32x32 blocks");
+};
+
+// Global -> LDS loader for an operand stored along k, 128-byte image rows: one instruction fills 8
+// consecutive rows; lane l writes position l%8 of row l/8 and fetches the logical chunk
+// pos ^ ((row >> 1) & 7), so that the 16 lanes of a fragment read (16 consecutive rows, one logical
+// chunk) fall into 16 different 16-byte bank groups of the 256-byte LDS line.
+// W0: first row of the wave's tile is W0-strided per wave index (see the kernel); NBLK blocks of 32 rows.
+template <int BR, int NT, int NBLK>
+struct HLoaderKDma64 {
+    static constexpr int NW = NT / 64;
+    static constexpr int NP = BR / (8 * NW);  // instructions per thread and tile
+    static constexpr int NFILL = NP;
+    static constexpr int READS = 1;           // LDS instructions per fragment
+    static_assert(BR % (8 * NW) == 0 && NP >= 1, "8 rows of 128 bytes per wave instruction");
+    const char *tile;   // workgroup-uniform, kept in scalar registers
+    uint32_t off[NP];   // this lane's byte offsets from it
+    uint32_t wave_lds;  // byte offset of this wave's first row group inside the image
+    uint32_t foff[4];   // byte offset of the lane's fragment of block 0, per k step
+
+    // w0: first row of this wave's part of the tile
+    __device__ __forceinline__ void init(const _Float16 *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid, int w0)
+    {
+        const int wave = tid / 64, lane = tid % 64;
+        const uint64_t t0 = reinterpret_cast<uint64_t>(base + r0 * ld + k0);  // the same in every lane
+        tile = reinterpret_cast<const char *>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(t0 >> 32)) << 32) |
+                                              (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)t0));
+        wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane(wave * 8 * 128);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int row = (wave + p * NW) * 8 + lane / 8;  // image row
+            const int ch = (lane & 7) ^ ((row >> 1) & 7);   // logical chunk stored at this lane's position
+            int64_t lr = row;
+            lr = r0 + lr < R ? lr : R - 1 - r0;
+            off[p] = (uint32_t)((lr * ld + ch * 8) * 2);
+        }
+        const int row = w0 + (lane & 31), h = lane >> 5;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) foff[ks] = (uint32_t)(row * 128 + (((2 * ks + h) ^ ((row >> 1) & 7)) * 16));
+    }
+    template <int I>
+    __device__ __forceinline__ void fill_piece(uint32_t image_lds) const
+    {
+        // assembly for the reason given in HLoaderKDma::fill_piece
+        asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(off[I]), "s"(tile), "s"(image_lds + wave_lds), "n"(I * NW * 8 * 128)
+                     : "memory", "scc");
+    }
+    __device__ __forceinline__ void advance_fill(int64_t) { tile += 64 * 2; }
+    // the lane's 8 halves of block BLK (32 rows), k step KS: 8 consecutive k of one row
+    template <int KS, int BLK>
+    __device__ __forceinline__ halfx8 read_frag(uint32_t image_lds) const
+    {
+#if defined(__HIP_DEVICE_COMPILE__)
+        typedef const __attribute__((address_space(3))) halfx8 *lp;
+        return *(lp)(uintptr_t)(image_lds + foff[KS] + BLK * 32 * 128);
+#else
+        (void)image_lds;
+        return halfx8{};
+#endif
+    }
+};
+
+// Global -> LDS loader for an operand stored along its own index (element (k, x) at base[k*ld + x]),
+// read back with the transposing LDS read.  ds_read_b64_tr_b16 (checked on the device with an image
+// whose element i holds i): in a group of 16 lanes, lane s supplies the address of 4 consecutive
+// 16-bit elements, taken as row s/4, columns 4*(s%4)..+3 of a 4 x 16 block, and lane j receives
+// column j of the 4 rows.  With rows = k and columns = x a lane gets 4 consecutive k of one x, which
+// is what the matrix instruction wants, from an image that keeps the operand's own layout.
+// The image is made of 1 KB units of 4 k rows x 128 x (one load instruction each: lane l = 16-byte
+// position l of the unit); position r*16 + (c ^ 4r) holds chunk c (8 x) of row r, so that the 4 rows x
+// 32 bytes of a 16-lane group, and the two groups that share a pass, use different banks.
+// Unit (k/4, x/128) is unit number (k/4)*(BR/128) + x/128.
+template <int BR, int NT, int NBLK>
+struct HLoaderNDma64 {
+    static constexpr int NW = NT / 64;
+    static constexpr int XH = BR / 128;             // units per row group
+    static constexpr int NP = (16 * XH) / NW;       // instructions per thread and tile
+    static constexpr int NFILL = NP;
+    static constexpr int READS = 2;
+    static_assert(BR % 128 == 0 && (16 * XH) % NW == 0 && NP >= 1, "whole units per wave");
+    const char *tile;
+    uint32_t off[NP];
+    uint32_t wave_lds;
+    uint32_t foff[NBLK];  // byte offset of the lane's source address for block b, k step 0, first half
+
+    __device__ __forceinline__ void init(const _Float16 *base, int64_t ld, int64_t x0, int64_t X, int64_t k0, int tid, int w0)
+    {
+        const int wave = tid / 64, lane = tid % 64;
+        const uint64_t t0 = reinterpret_cast<uint64_t>(base + k0 * ld + x0);
+        tile = reinterpret_cast<const char *>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(t0 >> 32)) << 32) |
+                                              (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)t0));
+        wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane(wave * 1024);
+        const int r = lane / 16, c = (lane % 16) ^ (4 * r);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int u = wave + p * NW;
+            const int k = (u / XH) * 4 + r;
+            int64_t x = (u % XH) * 128 + c * 8;
+            x = x0 + x + 8 <= X ? x : X - 8 - x0;  // past the edge: the last whole chunk (never used)
+            off[p] = (uint32_t)((k * ld + x) * 2);
+        }
+        // source address this lane supplies to the transposing read of block b (k step 0, k 0..3 of its 8)
+        const int kk = 8 * (lane / 32) + (lane % 16) / 4;
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+            const int x = w0 + b * 32 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
+            const int u = (kk / 4) * XH + x / 128, rr = kk % 4, cc = (x % 128) / 8;
+            foff[b] = (uint32_t)(u * 1024 + (rr * 16 + (cc ^ (4 * rr))) * 16 + (x % 8) * 2);
+        }
+    }
+    template <int I>
+    __device__ __forceinline__ void fill_piece(uint32_t image_lds) const
+    {
+        asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(off[I]), "s"(tile), "s"(image_lds + wave_lds), "n"(I * NW * 1024)
+                     : "memory", "scc");
+    }
+    __device__ __forceinline__ void advance_fill(int64_t ld) { tile += 64 * ld * 2; }
+    template <int KS, int BLK>
+    __device__ __forceinline__ halfx8 read_frag(uint32_t image_lds) const
+    {
+#if defined(__HIP_DEVICE_COMPILE__)
+        typedef short shortx4 __attribute__((ext_vector_type(4)));
+        typedef short shortx8 __attribute__((ext_vector_type(8)));
+        typedef __attribute__((address_space(3))) shortx4 *lp;
+        // k step KS starts 4 row groups further, the second half of the lane's 8 k one row group further
+        const uint32_t a = image_lds + foff[BLK] + KS * 4 * XH * 1024;
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(uintptr_t)a);
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(uintptr_t)(a + XH * 1024));
+        const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(halfx8, both);
+#else
+        (void)image_lds;
+        return halfx8{};
+#endif
+    }
+};
+
+template <bool KCONTIG, int BR, int NT, int NBLK>
+struct HLoader64Sel {
+    typedef HLoaderKDma64<BR, NT, NBLK> type;
+};
+template <int BR, int NT, int NBLK>
+struct HLoader64Sel<false, BR, NT, NBLK> {
+    typedef HLoaderNDma64<BR, NT, NBLK> type;
+};
+
+// Fragment piece P of k step KS in the order the matrix instructions need them: block row 0 of A,
+// the block columns of B, then the other block rows of A.
+template <class Cfg, int KS, int P, class RL, class CL>
+__device__ __forceinline__ void hload_frag_piece64(HFrag<Cfg> &f, const RL &rl, const CL &cl, uint32_t a_lds, uint32_t b_lds)
+{
+    if constexpr (P == 0)
+        f.a[0] = rl.template read_frag<KS, 0>(a_lds);
+    else if constexpr (P <= Cfg::NB)
+        f.b[P - 1] = cl.template read_frag<KS, P - 1>(b_lds);
+    else
+        f.a[P - Cfg::NB] = rl.template read_frag<KS, P - Cfg::NB>(a_lds);
+}
+
+// One K tile of 64.  k steps 0..2 run on the current stage and read the fragments of the following
+// step.  Then the one barrier of the iteration, before which a wave waits for its own loads of the
+// next tile and for its last fragment reads of this one: after it the other stage is complete and the
+// current stage is free.  k step 3 reads the next tile's first fragments and issues the loads of
+// tile t + 2 into the current stage; they have three k steps to land.
+// cur_lds / nxt_lds: LDS byte addresses of the two stages.
+template <class Cfg, bool STEADY, class RL, class CL>
+__device__ __forceinline__ void htile_iter_dma64(RL &rl, CL &cl, HFrag<Cfg> (&fr)[2], floatx16 (&acc)[Cfg::MB][Cfg::NB],
+                                                 uint32_t cur_lds, uint32_t nxt_lds, int64_t lda, int64_t ldb,
+                                                 bool do_fill = true, bool has_next = true)
+{
+    if constexpr (STEADY) {
+        do_fill = true;
+        has_next = true;
+    }
+    constexpr int NMMA = Cfg::MB * Cfg::NB, NFRAG = Cfg::MB + Cfg::NB;
+    constexpr int NFILL = RL::NFILL + CL::NFILL;
+    constexpr int PER = (NFILL + NMMA - 1) / NMMA;
+    constexpr uint32_t B_IMG = Cfg::A_HALVES * 2;
+    static_assert(Cfg::KSTEPS == 4 && NFRAG <= NMMA, "fragment reads fit between the matrix instructions of a k step");
+    static_for<3>([&](auto kc) {
+        constexpr int ks = decltype(kc)::value;
+        static_for<NMMA>([&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            hmma_one<Cfg, q>(fr[ks & 1], acc);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (q < NFRAG) hload_frag_piece64<Cfg, ks + 1, q>(fr[(ks + 1) & 1], rl, cl, cur_lds, cur_lds + B_IMG);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    });
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<NMMA>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        hmma_one<Cfg, q>(fr[1], acc);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (q < NFRAG) {
+            if (has_next) hload_frag_piece64<Cfg, 0, q>(fr[0], rl, cl, nxt_lds, nxt_lds + B_IMG);
+        }
+        if (do_fill) {
+            static_for<PER>([&](auto ec) {
+                constexpr int st = q * PER + decltype(ec)::value;
+                if constexpr (st < RL::NFILL)
+                    rl.template fill_piece<st>(cur_lds);
+                else if constexpr (st < NFILL)
+                    cl.template fill_piece<st - RL::NFILL>(cur_lds + B_IMG);
+            });
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    if (do_fill) {
+        rl.advance_fill(lda);
+        cl.advance_fill(ldb);
+    }
+}
+
+// Needs K a multiple of 64 and the alignment of hgemm_mfma16_kernel (an operand stored along its own
+// index: a multiple of 8 rows / columns).  All four orientations.
+template <class Cfg, bool A_KCONTIG, bool B_KCONTIG>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma64_kernel(const HGemmArgs g)
+{
+    typedef typename HLoader64Sel<A_KCONTIG, Cfg::BM, Cfg::NT, Cfg::MB>::type RLT;
+    typedef typename HLoader64Sel<B_KCONTIG, Cfg::BN, Cfg::NT, Cfg::NB>::type CLT;
+    constexpr int A_H = Cfg::A_HALVES, STAGE_H = Cfg::STAGE_HALVES;
+    constexpr uint32_t STAGE_B = STAGE_H * 2;
+    __shared__ __attribute__((aligned(1024))) _Float16 smem[2 * STAGE_H];
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lds_ptr)smem;
+#else
+    const uint32_t smem_lds = 0;
+#endif
+
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();
+        g.clock_probe[blockIdx.x * 4 + 1] = __builtin_amdgcn_s_memrealtime();
+    }
+    const int tiles = g.tiles_m * g.tiles_n;
+    const WorkItem w = work_item(blockIdx.x, tiles, g.split);
+    int tm, tn;
+    tile_coords<8>(w.tile, g.tiles_m, g.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
+    int kt0, T, krem;
+    slice_range((int)(g.K / Cfg::BK), 0, w.slice, w.nslice, kt0, T, krem);
+    const int64_t k0 = (int64_t)kt0 * Cfg::BK;
+
+    const int wave = threadIdx.x >> 6;
+    RLT rl;
+    CLT cl;
+    rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x, (wave / Cfg::WAVES_N) * Cfg::WM);
+    cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x, (wave % Cfg::WAVES_N) * Cfg::WN);
+
+    floatx16 acc[Cfg::MB][Cfg::NB];
+#pragma unroll
+    for (int bm = 0; bm < Cfg::MB; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < Cfg::NB; ++bn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
+
+    auto fill_all = [&](uint32_t stage_lds) {
+        static_for<RLT::NFILL>([&](auto ic) { rl.template fill_piece<decltype(ic)::value>(stage_lds); });
+        static_for<CLT::NFILL>([&](auto ic) { cl.template fill_piece<decltype(ic)::value>(stage_lds + A_H * 2); });
+        rl.advance_fill(g.lda);
+        cl.advance_fill(g.ldb);
+    };
+
+    // Prologue: tile 0 landed in stage 0 and visible to all waves; tile 1 on its way into stage 1.
+    if (T > 0) fill_all(smem_lds);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (T > 1) fill_all(smem_lds + STAGE_B);
+
+    HFrag<Cfg> fr[2];
+    if (T > 0)
+        static_for<Cfg::MB + Cfg::NB>([&](auto pc) {
+            hload_frag_piece64<Cfg, 0, decltype(pc)::value>(fr[0], rl, cl, smem_lds, smem_lds + A_H * 2);
+        });
+
+    int t = 0;
+    // steady state, two tiles per trip (stage addresses are constants): both have a tile to fill
+    while (t + 3 < T) {
+        htile_iter_dma64<Cfg, true>(rl, cl, fr, acc, smem_lds, smem_lds + STAGE_B, g.lda, g.ldb);
+        htile_iter_dma64<Cfg, true>(rl, cl, fr, acc, smem_lds + STAGE_B, smem_lds, g.lda, g.ldb);
         t += 2;
     }
-    for (; t < T; t += 2) {
-        htile_iter_dma<Cfg, 0, false>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), A_H, a_off, b_off,
-                                      t + S - 1 < T, t + S + 1 < T, t + 1 < T);
-        cs = next_of(cs);
-        fill = next_of(fill);
-        if (t + 1 < T) {
-            htile_iter_dma<Cfg, 1, false>(rl, cl, fr, acc, stage(cs), stage(next_of(cs)), stage(fill), A_H, a_off, b_off,
-                                          t + S < T, t + S + 2 < T, t + 2 < T);
-            cs = next_of(cs);
-            fill = next_of(fill);
-        }
+    // the last tiles (t is even here): the same iteration with its conditions
+    for (; t < T; ++t) {
+        const uint32_t cs = (uint32_t)(t & 1);
+        htile_iter_dma64<Cfg, false>(rl, cl, fr, acc, smem_lds + cs * STAGE_B, smem_lds + (cs ^ 1u) * STAGE_B, g.lda, g.ldb,
+                                     t + 2 < T, t + 1 < T);
     }
 
     if (!combine_slices<Cfg>(acc, g.split, w)) return;
@@ -721,18 +978,29 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma_kern
 }
 
 template <class Cfg>
-int launch_hgemm_mfma16_dma(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
+int launch_hgemm_mfma16_dma64(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
 {
+    if (g.K % Cfg::BK != 0) return (int)hipErrorInvalidValue;
     const int tiles = g.tiles_m * g.tiles_n;
     const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
     if (a_kcontig && b_kcontig)
-        hipLaunchKernelGGL((hgemm_mfma16_dma_kernel<Cfg, true, true>), grid, block, 0, stream, g);
+        hipLaunchKernelGGL((hgemm_mfma16_dma64_kernel<Cfg, true, true>), grid, block, 0, stream, g);
     else if (a_kcontig)
-        hipLaunchKernelGGL((hgemm_mfma16_dma_kernel<Cfg, true, false>), grid, block, 0, stream, g);
+        hipLaunchKernelGGL((hgemm_mfma16_dma64_kernel<Cfg, true, false>), grid, block, 0, stream, g);
     else if (b_kcontig)
-        hipLaunchKernelGGL((hgemm_mfma16_dma_kernel<Cfg, false, true>), grid, block, 0, stream, g);
+        hipLaunchKernelGGL((hgemm_mfma16_dma64_kernel<Cfg, false, true>), grid, block, 0, stream, g);
     else
-        return (int)hipErrorInvalidValue;
+        hipLaunchKernelGGL((hgemm_mfma16_dma64_kernel<Cfg, false, false>), grid, block, 0, stream, g);
+    return (int)hipGetLastError();
+}
+
+template <class Cfg>
+int launch_hgemm_mfma16_dma(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
+{
+    if (!(a_kcontig && b_kcontig)) return (int)hipErrorInvalidValue;
+    const int tiles = g.tiles_m * g.tiles_n;
+    const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
+    hipLaunchKernelGGL((hgemm_mfma16_dma_kernel<Cfg>), grid, block, 0, stream, g);
     return (int)hipGetLastError();
 }
 
@@ -757,6 +1025,7 @@ struct HCfgDesc {
     int BM, BN, BK, NT, lds_bytes;
     int (*launch)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);      // all loads through registers
     int (*launch_dma)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);  // operands stored along k: global -> LDS
+    int (*launch_dma64)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);  // the same with a K tile of 64 (K % 64 == 0), or null
 };
 constexpr int kNumHCfg = 3;
 const HCfgDesc &hcfg_desc(int i);  // defined in hgemm_instance.hip
