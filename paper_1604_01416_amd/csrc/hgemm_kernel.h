@@ -670,7 +670,8 @@ struct HTile64Cfg {
     static constexpr int A_HALVES = BM * BK, B_HALVES = BN * BK, STAGE_HALVES = A_HALVES + B_HALVES;
     static constexpr int LDS_BYTES = STAGES * STAGE_HALVES * 2;
     static constexpr int KSTEPS = BK / 16;
-    static constexpr int MIN_WAVES = (NT / 64 + 3) / 4;
+    // waves per SIMD the register budget is sized for: as many workgroups as the LDS holds
+    static constexpr int MIN_WAVES = ((NT / 64 + 3) / 4) * ((160 * 1024 / LDS_BYTES) < 2 ? 1 : 2);
     static_assert(WM % 32 == 0 && WN % 32 == 0 && LDS_BYTES <= 160 * 1024, "wave tile is made of 32x32 blocks");
 };
 
