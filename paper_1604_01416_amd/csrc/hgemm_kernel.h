@@ -838,8 +838,10 @@ __device__ __forceinline__ void hload_frag_piece64(HFrag<Cfg> &f, const RL &rl, 
 // One K tile of 64.  k steps 0..2 run on the current stage and read the fragments of the following
 // step.  Then the one barrier of the iteration, before which a wave waits for its own loads of the
 // next tile and for its last fragment reads of this one: after it the other stage is complete and the
-// current stage is free.  k step 3 reads the next tile's first fragments and issues the loads of
-// tile t + 2 into the current stage; they have three k steps to land.
+// current stage is free.  k step 3 reads the next tile's first fragments and issues the first half of
+// the loads of tile t + 2 into the current stage; the second half follows during k step 0 of the next
+// iteration.  All of a tile's loads in one k step overran the load queue (64 KB is 1024 cycles of
+// first-level cache bandwidth, a k step lasts 512) and the waves stalled at issue: spread, +4 % at 4096^3.
 // cur_lds / nxt_lds: LDS byte addresses of the two stages.
 template <class Cfg, bool STEADY, class RL, class CL>
 __device__ __forceinline__ void htile_iter_dma64(RL &rl, CL &cl, HFrag<Cfg> (&fr)[2], floatx16 (&acc)[Cfg::MB][Cfg::NB],
@@ -852,9 +854,19 @@ __device__ __forceinline__ void htile_iter_dma64(RL &rl, CL &cl, HFrag<Cfg> (&fr
     }
     constexpr int NMMA = Cfg::MB * Cfg::NB, NFRAG = Cfg::MB + Cfg::NB;
     constexpr int NFILL = RL::NFILL + CL::NFILL;
-    constexpr int PER = (NFILL + NMMA - 1) / NMMA;
     constexpr uint32_t B_IMG = Cfg::A_HALVES * 2;
     static_assert(Cfg::KSTEPS == 4 && NFRAG <= NMMA, "fragment reads fit between the matrix instructions of a k step");
+    // loads of a tile: first half during k step 3 (into the stage just freed), second half during k step 0
+    // of the next iteration, STRIDE matrix instructions apart
+    constexpr int HALF = NFILL / 2, STRIDE = NMMA / HALF;
+    static_assert(NFILL % 2 == 0 && NMMA % HALF == 0, "loads spread evenly over two k steps");
+    auto fill_one = [&](auto stc, uint32_t stage_lds) {
+        constexpr int st = decltype(stc)::value;
+        if constexpr (st < RL::NFILL)
+            rl.template fill_piece<st>(stage_lds);
+        else if constexpr (st < NFILL)
+            cl.template fill_piece<st - RL::NFILL>(stage_lds + B_IMG);
+    };
     static_for<3>([&](auto kc) {
         constexpr int ks = decltype(kc)::value;
         static_for<NMMA>([&](auto qc) {
@@ -862,8 +874,17 @@ __device__ __forceinline__ void htile_iter_dma64(RL &rl, CL &cl, HFrag<Cfg> (&fr
             hmma_one<Cfg, q>(fr[ks & 1], acc);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (q < NFRAG) hload_frag_piece64<Cfg, ks + 1, q>(fr[(ks + 1) & 1], rl, cl, cur_lds, cur_lds + B_IMG);
+            if constexpr (ks == 0 && q % STRIDE == STRIDE - 1) {
+                if (has_next) fill_one(std::integral_constant<int, HALF + q / STRIDE>{}, nxt_lds);
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
+        if constexpr (ks == 0) {
+            if (has_next) {
+                rl.advance_fill(lda);
+                cl.advance_fill(ldb);
+            }
+        }
     });
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
     __builtin_amdgcn_s_barrier();
@@ -875,21 +896,11 @@ __device__ __forceinline__ void htile_iter_dma64(RL &rl, CL &cl, HFrag<Cfg> (&fr
         if constexpr (q < NFRAG) {
             if (has_next) hload_frag_piece64<Cfg, 0, q>(fr[0], rl, cl, nxt_lds, nxt_lds + B_IMG);
         }
-        if (do_fill) {
-            static_for<PER>([&](auto ec) {
-                constexpr int st = q * PER + decltype(ec)::value;
-                if constexpr (st < RL::NFILL)
-                    rl.template fill_piece<st>(cur_lds);
-                else if constexpr (st < NFILL)
-                    cl.template fill_piece<st - RL::NFILL>(cur_lds + B_IMG);
-            });
+        if constexpr (q % STRIDE == STRIDE - 1) {
+            if (do_fill) fill_one(std::integral_constant<int, q / STRIDE>{}, cur_lds);
         }
         __builtin_amdgcn_sched_barrier(0);
     });
-    if (do_fill) {
-        rl.advance_fill(lda);
-        cl.advance_fill(ldb);
-    }
 }
 
 // Needs K a multiple of 64 and the alignment of hgemm_mfma16_kernel (an operand stored along its own
@@ -936,19 +947,31 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma64_ke
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
 
-    auto fill_all = [&](uint32_t stage_lds) {
-        static_for<RLT::NFILL>([&](auto ic) { rl.template fill_piece<decltype(ic)::value>(stage_lds); });
-        static_for<CLT::NFILL>([&](auto ic) { cl.template fill_piece<decltype(ic)::value>(stage_lds + A_H * 2); });
-        rl.advance_fill(g.lda);
-        cl.advance_fill(g.ldb);
+    constexpr int NFILL = RLT::NFILL + CLT::NFILL;
+    auto fill_range = [&](auto loc, auto hic, uint32_t stage_lds) {  // pieces LO .. HI-1 of the tile at the fill pointers
+        constexpr int LO = decltype(loc)::value, HI = decltype(hic)::value;
+        static_for<HI - LO>([&](auto ic) {
+            constexpr int st = LO + decltype(ic)::value;
+            if constexpr (st < RLT::NFILL)
+                rl.template fill_piece<st>(stage_lds);
+            else
+                cl.template fill_piece<st - RLT::NFILL>(stage_lds + A_H * 2);
+        });
     };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, NFILL> IAll;
 
     // Prologue: tile 0 landed in stage 0 and visible to all waves; tile 1 on its way into stage 1.
-    if (T > 0) fill_all(smem_lds);
+    if (T > 0) {
+        fill_range(I0(), IAll(), smem_lds);
+        rl.advance_fill(g.lda);
+        cl.advance_fill(g.ldb);
+    }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    if (T > 1) fill_all(smem_lds + STAGE_B);
+    // the first half of tile 1; iteration 0 issues the second half and moves the pointers on
+    if (T > 1) fill_range(I0(), std::integral_constant<int, NFILL / 2>(), smem_lds + STAGE_B);
 
     HFrag<Cfg> fr[2];
     if (T > 0)
