@@ -50,7 +50,11 @@ MEASURED_HBM_TRAFFIC_BYTES = {
 }
 
 WORKLOADS = ("gemm4096", "gemm256", "summa", "fc", "conv", "conv_bwd_data", "conv_bwd_filter", "summa_fused",
-             "fc_nn", "fc_nt", "fc_tn", "hgemm4096", "fc_half", "dgemm4096")
+             "fc_nn", "fc_nt", "fc_tn", "hgemm4096", "fc_half", "dgemm4096", "square")
+
+# One-GPU column of the paper's table "Matrix Multiplication Performance" (seconds per multiply on one
+# K80 GPU with cuBLAS 7.5; the larger sizes did not fit its memory).  Context only, never a target.
+PAPER_TABLE_ONE_GPU_SECONDS = {4096: 0.052, 6144: 0.174, 8192: 0.413, 12288: 1.450, 16384: 3.340, 24576: 12.279}
 
 
 def _device_arrays(torch, arrays):
@@ -144,6 +148,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", choices=WORKLOADS, default="gemm4096")
+    ap.add_argument("--size", type=int, default=16384,
+                    help="--workload square: FP32 NN product of size^3, operands uniform[-1,1] drawn on the device "
+                         "(the sizes of the paper's multiplication table: 4096 6144 8192 12288 16384 24576 32768 49152 65536)")
     ap.add_argument("--tile-config", type=int, default=-1, help="force a tile configuration (tuning only)")
     ap.add_argument("--split-k", type=int, default=-1, help="force a split-K factor (tuning only)")
     ap.add_argument("--hgemm-path", type=int, default=-1, help="force the dmath_hgemm kernel (see dmath_set_hgemm_path)")
@@ -210,6 +217,21 @@ def main():
 
         flop, alg_bytes, launches = conv.flop, conv.algorithmic_bytes, 1
         wl_name = conv.name + ("_bwd_data" if bwd else "_bwd_filter" if bwd_filter else "")
+    elif args.workload == "square":
+        # a size of the paper's table: drawn on the device (65536^2 elements would take minutes on the host)
+        n = args.size
+        assert 1 <= n <= 65536
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(n)
+        dA = torch.rand((n, n), generator=gen, device="cuda").mul_(2.0).sub_(1.0)
+        dB = torch.rand((n, n), generator=gen, device="cuda").mul_(2.0).sub_(1.0)
+        dC = torch.empty((n, n), device="cuda")
+        call = workloads.GemmCall(0, 0, n, n, n, 1.0, "A", n, "B", n, 0.0, "C", n)
+
+        def step():
+            dm.check(dm.dmath_gemm(0, 0, n, n, n, 1.0, dA, n, dB, n, 0.0, dC, n))
+
+        flop, alg_bytes, launches, wl_name = call.flop, call.algorithmic_bytes, 1, "gemm_nn_%d" % n
     else:
         wl = {"gemm4096": workloads.config2, "gemm256": workloads.config1, "summa": workloads.config3,
               "summa_fused": workloads.config3, "fc": workloads.config4, "fc_nn": workloads.config4,
@@ -269,7 +291,7 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        if args.workload in ("hgemm4096", "fc_half", "dgemm4096"):
+        if args.workload in ("hgemm4096", "fc_half", "dgemm4096", "square"):
             cpu_baseline = None   # the FP32 workloads of the same shapes carry the oracle timing
         elif conv is not None and args.workload != "conv":
             cpu_baseline = None   # the forward workload carries the oracle timing of this layer
@@ -317,6 +339,9 @@ def main():
                          "cuBLAS 7.5 took 0.052 s (about 2.64 TFLOP/s, precision not stated); other hardware, "
                          "context only",
     }
+    if args.workload == "square":
+        line["seconds_per_multiply"] = ms_ev / 1e3
+        line["paper_table_one_gpu_seconds"] = PAPER_TABLE_ONE_GPU_SECONDS.get(args.size)  # None: did not fit one K80 GPU
     print(json.dumps(line))
 
 

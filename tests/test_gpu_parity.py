@@ -925,3 +925,118 @@ def test_random_panel_lists(dm, torch, seed):
         run_gemm_panels_case(dm, torch, int(rng.integers(0, 2)), int(rng.integers(0, 2)), M, N, K, P,
                              alpha=float(rng.choice([1.0, -0.5])), beta=float(rng.choice([0.0, 1.0])),
                              ld_extra=tuple(4 * int(rng.integers(0, 2)) for _ in range(3)), seed=seed * 30 + i)
+
+
+# ------------------------------------------------------------------ operands beyond 2^31 elements
+
+def _sub_check(torch, gpu_sub, A_rows, B_cols, K, alpha, beta, C0_sub, what, kind="f32"):
+    """The sums at the sampled rows x sampled columns form a small product of their own: the rows of op(A)
+    and the columns of op(B) go to the oracle as that product's operands."""
+    A_rows = np.ascontiguousarray(A_rows)
+    B_cols = np.ascontiguousarray(B_cols)
+    m, n = A_rows.shape[0], B_cols.shape[1]
+    C0 = None if C0_sub is None else np.ascontiguousarray(C0_sub)
+    if kind == "f16":
+        ref, mag = oracle.hgemm(0, 0, m, n, K, alpha, A_rows, K, B_cols, n, beta=beta, C0=C0, ldc=n)
+        err = np.abs(gpu_sub.astype(np.float64) - ref)
+        assert (err <= oracle.half_bound(K, mag, ref)).all(), what
+    elif kind == "f64":
+        ref, mag = oracle.dgemm(0, 0, m, n, K, alpha, A_rows, K, B_cols, n, beta=beta, C0=C0, ldc=n)
+        err = np.abs(gpu_sub.astype(np.float64) - ref)
+        assert (err <= oracle.double_bound(K, mag)).all(), what
+    else:
+        ref, mag = oracle.gemm(0, 0, m, n, K, alpha, A_rows, K, B_cols, n, beta=beta, C0=C0, ldc=n)
+        check_bound(gpu_sub, ref, mag, K, what)
+
+
+def _uniform(torch, shape, seed, dtype):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    t = torch.rand(shape, generator=g, device="cuda", dtype=torch.float32 if dtype == torch.float16 else dtype)
+    t.mul_(2.0).sub_(1.0)
+    return t.to(dtype) if dtype == torch.float16 else t
+
+
+def test_gemm_output_beyond_2_31_elements(dm, torch):
+    """C of 49152 x 49152 (9.7 GB): element offsets of its last rows do not fit 31 bits.  K is short, beta = 1:
+    the epilogue's addressing, read and write, is what this checks; rows on both sides of offset 2^31."""
+    n, K = 49152, 64
+    A = _uniform(torch, (n, K), 11, torch.float32)
+    B = _uniform(torch, (K, n), 12, torch.float32)
+    C = _uniform(torch, (n, n), 13, torch.float32)
+    rows = torch.tensor([0, 1, 255, 256, 43689, 43690, 43691, 43692, 49150, 49151], device="cuda")
+    cols = torch.tensor([0, 1, 127, 128, 32767, 32768, 40000, 49150, 49151], device="cuda")
+    C0 = C[rows][:, cols].cpu().numpy()
+    checksum_rows = torch.tensor([2, 30000, 45000], device="cuda")
+    before = C[checksum_rows].double().sum(dim=1).cpu().numpy()
+    dm.check(dm.dmath_gemm(0, 0, n, n, K, 0.5, A, K, B, n, 1.0, C, n))
+    torch.cuda.synchronize()
+    got = C[rows][:, cols].cpu().numpy()
+    _sub_check(torch, got, A[rows].cpu().numpy(), B[:, cols].cpu().numpy(), K, 0.5, 1.0, C0, "C beyond 2^31")
+    # rows that are not sampled changed too (each by 0.5 * sum over the row of A_i . B): not left untouched
+    after = C[checksum_rows].double().sum(dim=1).cpu().numpy()
+    want = 0.5 * (A[checksum_rows].double() @ B.double().sum(dim=1)).cpu().numpy()
+    assert np.allclose(after - before, want, rtol=0, atol=1e-2)
+
+
+@pytest.mark.parametrize("tA", [0, 1])
+def test_gemm_operand_beyond_2_31_elements(dm, torch, tA):
+    """A of 40960 x 65536 (10.7 GB; stored transposed for tA = 1): rows past 32768 start beyond element 2^31.
+    Long K, so the plan splits it; N is small."""
+    M, K, N = 40960, 65536, 256
+    A = _uniform(torch, (K, M) if tA else (M, K), 21 + tA, torch.float32)
+    B = _uniform(torch, (K, N), 23, torch.float32)
+    C = torch.full((M, N), float("nan"), device="cuda")
+    dm.check(dm.dmath_gemm(tA, 0, M, N, K, 1.0, A, A.shape[1], B, N, 0.0, C, N))
+    torch.cuda.synchronize()
+    rows = torch.tensor([0, 255, 32767, 32768, 32769, 40000, 40959], device="cuda")
+    A_rows = (A[:, rows].t() if tA else A[rows]).contiguous().cpu().numpy()
+    assert not torch.isnan(C).any()
+    _sub_check(torch, C[rows].cpu().numpy(), A_rows, B.cpu().numpy(), K, 1.0, 0.0, None, "A beyond 2^31, tA=%d" % tA)
+
+
+@pytest.mark.parametrize("tA", [0, 1])
+def test_hgemm_operand_beyond_2_31_elements(dm, torch, tA):
+    """The same for half storage (FP16-input kernels with global -> LDS loads)."""
+    M, K, N = 40960, 65536, 256
+    A = _uniform(torch, (K, M) if tA else (M, K), 31 + tA, torch.float16)
+    B = _uniform(torch, (K, N), 33, torch.float16)
+    C = torch.full((M, N), float("nan"), device="cuda", dtype=torch.float16)
+    dm.check(dm.dmath_hgemm(tA, 0, M, N, K, 1.0, A, A.shape[1], B, N, 0.0, C, N))
+    torch.cuda.synchronize()
+    rows = torch.tensor([0, 255, 32767, 32768, 32769, 40000, 40959], device="cuda")
+    A_rows = (A[:, rows].t() if tA else A[rows]).contiguous().cpu().numpy()
+    assert not torch.isnan(C).any()
+    _sub_check(torch, C[rows].cpu().numpy(), A_rows, B.cpu().numpy(), K, 1.0, 0.0, None, "half A beyond 2^31, tA=%d" % tA,
+               kind="f16")
+
+
+def test_dgemm_operand_beyond_2_31_elements(dm, torch):
+    """FP64: A of 36864 x 65536 (19.3 GB)."""
+    M, K, N = 36864, 65536, 128
+    A = _uniform(torch, (M, K), 41, torch.float64)
+    B = _uniform(torch, (K, N), 42, torch.float64)
+    C = torch.full((M, N), float("nan"), device="cuda", dtype=torch.float64)
+    dm.check(dm.dmath_dgemm(0, 0, M, N, K, 1.0, A, K, B, N, 0.0, C, N))
+    torch.cuda.synchronize()
+    rows = torch.tensor([0, 255, 32767, 32768, 32769, 36863], device="cuda")
+    assert not torch.isnan(C).any()
+    _sub_check(torch, C[rows].cpu().numpy(), A[rows].cpu().numpy(), B.cpu().numpy(), K, 1.0, 0.0, None, "FP64 A beyond 2^31",
+               kind="f64")
+
+
+@pytest.mark.parametrize("n", [6144, 16384])
+def test_paper_table_sizes_sampled(dm, torch, n):
+    """Sizes of the paper's table "Matrix Multiplication Performance" beyond config 2, in the launch bench.py
+    times for `--workload square`: sampled rows x sampled columns against the oracle."""
+    A = _uniform(torch, (n, n), n, torch.float32)
+    B = _uniform(torch, (n, n), n + 1, torch.float32)
+    C = torch.full((n, n), float("nan"), device="cuda")
+    dm.check(dm.dmath_gemm(0, 0, n, n, n, 1.0, A, n, B, n, 0.0, C, n))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(n)
+    rows = torch.from_numpy(np.unique(np.concatenate([[0, 255, 256, n - 1], rng.integers(0, n, 28)]))).cuda()
+    cols = torch.from_numpy(np.unique(np.concatenate([[0, 127, 128, n - 1], rng.integers(0, n, 28)]))).cuda()
+    assert not torch.isnan(C).any()
+    _sub_check(torch, C[rows][:, cols].cpu().numpy(), A[rows].cpu().numpy(), B[:, cols].cpu().numpy(), n, 1.0, 0.0, None,
+               "table size %d" % n)
