@@ -103,8 +103,10 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB,
  * UNSUPPORTED when the conditions do not hold); adding 16 to 1, 2 or 3 selects the variant of that
  * kernel that stages every operand through registers (by default a product with both operands stored
  * along k, transA == N and transB == T, loads them global -> LDS directly, with a K tile of 64 when K
- * is a multiple of 64 and the tile has such a kernel; adding 32 keeps the direct loads at a K tile of
- * 32); a tile configuration forced with dmath_set_override also selects the FP32 instruction.
+ * is a multiple of 64 and the tile has such a kernel, and then on the 16x16x32 form of the instruction
+ * where the tile has that kernel; adding 32 keeps the direct loads at a K tile of 32, adding 64 keeps
+ * the K tile of 64 on the 32x32x16 form); a tile configuration forced with dmath_set_override also
+ * selects the FP32 instruction.
  */
 dmath_status dmath_hgemm(dmath_op transA, dmath_op transB,
                          int64_t M, int64_t N, int64_t K,

@@ -22,6 +22,7 @@ struct ThreadState {
     int hgemm_path = -1;
     bool hgemm_no_dma = false;  // dmath_set_hgemm_path(path + 16): the register-only variant of path
     bool hgemm_no_k64 = false;  // dmath_set_hgemm_path(path + 32): global -> LDS loads with the K tile of 32
+    bool hgemm_no_mi16 = false; // dmath_set_hgemm_path(path + 64): the K = 64 kernel on the 32x32x16 instruction
     int dgemm_cfg = -1;   // -1 automatic, else index of the FP64 tile configuration  // -1 automatic, 0 FP32 matrix instruction on widened operands, 1 FP16-input instruction
     int last_error_arg = 0;
     unsigned long long *clock_probe = nullptr;
@@ -441,7 +442,9 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
             // (that kernel takes every orientation: an operand stored along its own index is read back
             // with the transposing LDS read)
             const bool k64 = h.launch_dma64 != nullptr && K % 64 == 0 && !g_state.hgemm_no_k64 && !g_state.hgemm_no_dma;
-            if ((k64 ? h.launch_dma64 : dma ? h.launch_dma : h.launch)(g, a_k, b_k, stream) != (int)hipSuccess)
+            // ... and on the 16x16x32 form of the instruction, which sustains a higher clock under the power limit
+            const bool mi16 = k64 && h.launch_mi16 != nullptr && !g_state.hgemm_no_mi16;
+            if ((mi16 ? h.launch_mi16 : k64 ? h.launch_dma64 : dma ? h.launch_dma : h.launch)(g, a_k, b_k, stream) != (int)hipSuccess)
                 return fail(DMATH_ERR_LAUNCH, 0);
             if (s > 1) {
                 const bool v4 = (N % 4 == 0) && g.cvec;
@@ -544,12 +547,15 @@ dmath_status dmath_set_override(int tile_config, int split_k)
 
 dmath_status dmath_set_hgemm_path(int path)
 {
+    const bool no_mi16 = path >= 64;
+    if (no_mi16) path -= 64;
     const bool no_k64 = path >= 32;
     if (no_k64) path -= 32;
     const bool no_dma = path >= 16;
     if (no_dma) path -= 16;
-    if (path < -1 || path > kNumHCfg || ((no_dma || no_k64) && path < 1)) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (path < -1 || path > kNumHCfg || ((no_dma || no_k64 || no_mi16) && path < 1)) return fail(DMATH_ERR_INVALID_ARG, 1);
     g_state.hgemm_path = path;
+    g_state.hgemm_no_mi16 = no_mi16;
     g_state.hgemm_no_dma = no_dma;
     g_state.hgemm_no_k64 = no_k64;
     return DMATH_OK;

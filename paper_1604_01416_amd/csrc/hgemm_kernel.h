@@ -680,7 +680,9 @@ struct HTile64Cfg {
 // pos ^ ((row >> 1) & 7), so that the 16 lanes of a fragment read (16 consecutive rows, one logical
 // chunk) fall into 16 different 16-byte bank groups of the 256-byte LDS line.
 // W0: first row of the wave's tile is W0-strided per wave index (see the kernel); NBLK blocks of 32 rows.
-template <int BR, int NT, int NBLK>
+// MI: 32 for the 32x32x16 matrix instruction (fragments of 32 rows, four k steps of 16 per tile), 16 for
+// 16x16x32 (fragments of 16 rows, two k steps of 32).
+template <int BR, int NT, int NBLK, int MI = 32>
 struct HLoaderKDma64 {
     static constexpr int NW = NT / 64;
     static constexpr int NP = BR / (8 * NW);  // instructions per thread and tile
@@ -708,9 +710,15 @@ struct HLoaderKDma64 {
             lr = r0 + lr < R ? lr : R - 1 - r0;
             off[p] = (uint32_t)((lr * ld + ch * 8) * 2);
         }
-        const int row = w0 + (lane & 31), h = lane >> 5;
+        if constexpr (MI == 32) {
+            const int row = w0 + (lane & 31), h = lane >> 5;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) foff[ks] = (uint32_t)(row * 128 + (((2 * ks + h) ^ ((row >> 1) & 7)) * 16));
+            for (int ks = 0; ks < 4; ++ks) foff[ks] = (uint32_t)(row * 128 + (((2 * ks + h) ^ ((row >> 1) & 7)) * 16));
+        } else {
+            const int row = w0 + (lane & 15), q = lane >> 4;  // lane holds k = 32*ks + 8*q .. +7 of its row
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) foff[ks] = (uint32_t)(row * 128 + (((4 * ks + q) ^ ((row >> 1) & 7)) * 16));
+        }
     }
     template <int I>
     __device__ __forceinline__ void fill_piece(uint32_t image_lds) const
@@ -728,7 +736,7 @@ struct HLoaderKDma64 {
     {
 #if defined(__HIP_DEVICE_COMPILE__)
         typedef const __attribute__((address_space(3))) halfx8 *lp;
-        return *(lp)(uintptr_t)(image_lds + foff[KS] + BLK * 32 * 128);
+        return *(lp)(uintptr_t)(image_lds + foff[KS] + BLK * MI * 128);
 #else
         (void)image_lds;
         return halfx8{};
@@ -746,7 +754,9 @@ struct HLoaderKDma64 {
 // position l of the unit); position r*16 + (c ^ 4r) holds chunk c (8 x) of row r, so that the 4 rows x
 // 32 bytes of a 16-lane group, and the two groups that share a pass, use different banks.
 // Unit (k/4, x/128) is unit number (k/4)*(BR/128) + x/128.
-template <int BR, int NT, int NBLK>
+// For the 16x16x32 instruction (MI == 16) the two 16-lane groups that share a pass read k rows 8 apart, not
+// columns 16 apart: the chunk position is also XORed with 2*((k >> 3) & 1) to keep them on different banks.
+template <int BR, int NT, int NBLK, int MI = 32>
 struct HLoaderNDma64 {
     static constexpr int NW = NT / 64;
     static constexpr int XH = BR / 128;             // units per row group
@@ -766,22 +776,34 @@ struct HLoaderNDma64 {
         tile = reinterpret_cast<const char *>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(t0 >> 32)) << 32) |
                                               (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)t0));
         wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane(wave * 1024);
-        const int r = lane / 16, c = (lane % 16) ^ (4 * r);
+        const int r = lane / 16;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             const int u = wave + p * NW;
             const int k = (u / XH) * 4 + r;
+            const int c = (lane % 16) ^ (4 * r) ^ (MI == 16 ? 2 * ((k >> 3) & 1) : 0);
             int64_t x = (u % XH) * 128 + c * 8;
             x = x0 + x + 8 <= X ? x : X - 8 - x0;  // past the edge: the last whole chunk (never used)
             off[p] = (uint32_t)((k * ld + x) * 2);
         }
         // source address this lane supplies to the transposing read of block b (k step 0, k 0..3 of its 8)
-        const int kk = 8 * (lane / 32) + (lane % 16) / 4;
+        if constexpr (MI == 32) {
+            const int kk = 8 * (lane / 32) + (lane % 16) / 4;
 #pragma unroll
-        for (int b = 0; b < NBLK; ++b) {
-            const int x = w0 + b * 32 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
-            const int u = (kk / 4) * XH + x / 128, rr = kk % 4, cc = (x % 128) / 8;
-            foff[b] = (uint32_t)(u * 1024 + (rr * 16 + (cc ^ (4 * rr))) * 16 + (x % 8) * 2);
+            for (int b = 0; b < NBLK; ++b) {
+                const int x = w0 + b * 32 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
+                const int u = (kk / 4) * XH + x / 128, rr = kk % 4, cc = (x % 128) / 8;
+                foff[b] = (uint32_t)(u * 1024 + (rr * 16 + (cc ^ (4 * rr))) * 16 + (x % 8) * 2);
+            }
+        } else {
+            // the group of 16 lanes l/16 reads k = 8*(l/16) .. +3 (then +4 .. +7) of 16 columns
+            const int kk = 8 * (lane / 16) + (lane % 16) / 4;
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int x = w0 + b * 16 + 4 * (lane % 4);
+                const int u = (kk / 4) * XH + x / 128, rr = kk % 4, cc = (x % 128) / 8;
+                foff[b] = (uint32_t)(u * 1024 + (rr * 16 + (cc ^ (4 * rr) ^ (2 * ((kk >> 3) & 1)))) * 16 + (x % 8) * 2);
+            }
         }
     }
     template <int I>
@@ -800,8 +822,8 @@ struct HLoaderNDma64 {
         typedef short shortx4 __attribute__((ext_vector_type(4)));
         typedef short shortx8 __attribute__((ext_vector_type(8)));
         typedef __attribute__((address_space(3))) shortx4 *lp;
-        // k step KS starts 4 row groups further, the second half of the lane's 8 k one row group further
-        const uint32_t a = image_lds + foff[BLK] + KS * 4 * XH * 1024;
+        // k step KS starts 4 (MI == 16: 8) row groups further, the second half of the lane's 8 k one row group further
+        const uint32_t a = image_lds + foff[BLK] + KS * (MI == 32 ? 4 : 8) * XH * 1024;
         const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(uintptr_t)a);
         const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(uintptr_t)(a + XH * 1024));
         const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -813,13 +835,13 @@ struct HLoaderNDma64 {
     }
 };
 
-template <bool KCONTIG, int BR, int NT, int NBLK>
+template <bool KCONTIG, int BR, int NT, int NBLK, int MI = 32>
 struct HLoader64Sel {
-    typedef HLoaderKDma64<BR, NT, NBLK> type;
+    typedef HLoaderKDma64<BR, NT, NBLK, MI> type;
 };
-template <int BR, int NT, int NBLK>
-struct HLoader64Sel<false, BR, NT, NBLK> {
-    typedef HLoaderNDma64<BR, NT, NBLK> type;
+template <int BR, int NT, int NBLK, int MI>
+struct HLoader64Sel<false, BR, NT, NBLK, MI> {
+    typedef HLoaderNDma64<BR, NT, NBLK, MI> type;
 };
 
 // Fragment piece P of k step KS in the order the matrix instructions need them: block row 0 of A,
@@ -1001,6 +1023,252 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma64_ke
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The K = 64 kernel on v_mfma_f32_16x16x32_f16.  Same tile, loads and LDS images (the image of an operand
+// stored along its own index with one more XOR, see HLoaderNDma64); a wave tile is MB16 x NB16 blocks
+// of 16 x 16, a k step is 32 wide, two per tile.  Operand layout of the instruction: lane l holds row
+// (column) l%16 and k = 8*(l/16) .. +7; result register r of lane l is row 4*(l/16) + r, column l%16.
+// Why: a stream of this instruction sustains a higher clock than 32x32x16 under the power limit
+// (2155 against 1875 TFLOP/s for nothing but matrix instructions with lane-varying operands), and a
+// timing-only variant of the 32x32 kernel with each instruction replaced by two of these ran 7-12 %
+// faster.  Fragments are single-buffered and replaced as they die: block row bm of A after the last
+// instruction of row bm, block column bn of B after its last use in the last row.
+template <class Cfg>
+struct HFrag16 {
+    halfx8 a[Cfg::WM / 16], b[Cfg::WN / 16];
+};
+
+// Slot program of one tile (NMMA matrix instructions per k step, numbered q; row bm = q / NB16):
+//   k step 0: operands of k step 1 replace those of k step 0 as they die (read from the current stage);
+//             the last loads of tile t + 1 (those that did not fit k step 1 of the previous iteration).
+//   k step 1: after row 0 the one barrier of the iteration: by then the wave has used every fragment
+//             it read from the current stage and has waited for its own loads of tile t + 1, so after
+//             it the current stage is free and the next stage complete.  The rest of the step reads
+//             the next tile's first operands from the next stage and issues the loads of tile t + 2
+//             into the current stage, one every SP instructions.
+template <class Cfg, bool STEADY, class RL, class CL>
+__device__ __forceinline__ void htile_iter_mi16(RL &rl, CL &cl, HFrag16<Cfg> &fr, floatx4 (&acc)[Cfg::WM / 16][Cfg::WN / 16],
+                                                uint32_t cur_lds, uint32_t nxt_lds, int64_t lda, int64_t ldb,
+                                                bool do_fill = true, bool has_next = true)
+{
+    if constexpr (STEADY) {
+        do_fill = true;
+        has_next = true;
+    }
+    constexpr int MB16 = Cfg::WM / 16, NB16 = Cfg::WN / 16, NMMA = MB16 * NB16;
+    constexpr int NFILL = RL::NFILL + CL::NFILL;
+    constexpr int SP = NMMA / NFILL;                       // matrix instructions between two loads
+    constexpr int N1 = (NMMA - NB16 + SP - 1) / SP;        // loads issued in k step 1 (after the barrier)
+    constexpr uint32_t B_IMG = Cfg::A_HALVES * 2;
+    static_assert(NMMA % NFILL == 0 && N1 <= NFILL && (NFILL - N1) * SP <= NMMA, "loads fit their slots");
+    auto fill_one = [&](auto stc, uint32_t stage_lds) {
+        constexpr int st = decltype(stc)::value;
+        if constexpr (st < RL::NFILL)
+            rl.template fill_piece<st>(stage_lds);
+        else
+            cl.template fill_piece<st - RL::NFILL>(stage_lds + B_IMG);
+    };
+    static_for<2>([&](auto kc) {
+        constexpr int ks = decltype(kc)::value;
+        const uint32_t src = ks == 0 ? cur_lds : nxt_lds;   // stage the replacement operands come from
+        const bool rd = ks == 0 ? true : has_next;
+        static_for<NMMA>([&](auto qc) {
+            constexpr int q = decltype(qc)::value, bm = q / NB16, bn = q % NB16;
+            acc[bm][bn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fr.a[bm], fr.b[bn], acc[bm][bn], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (ks == 1 && q == NB16 - 1) {
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (bn == NB16 - 1) {   // row bm done: its A operand is dead
+                if (rd) fr.a[bm] = rl.template read_frag<1 - ks, bm>(src);
+            }
+            if constexpr (bm == MB16 - 1) {   // last row: this B operand is dead
+                if (rd) fr.b[bn] = cl.template read_frag<1 - ks, bn>(src + B_IMG);
+            }
+            if constexpr (ks == 1 && q >= NB16 && (q - NB16) % SP == 0) {
+                if (do_fill) fill_one(std::integral_constant<int, (q - NB16) / SP>{}, cur_lds);
+            }
+            if constexpr (ks == 0 && q % SP == 0 && N1 + q / SP < NFILL) {
+                if (has_next) fill_one(std::integral_constant<int, N1 + q / SP>{}, nxt_lds);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if constexpr (ks == 0) {
+            if (has_next) {
+                rl.advance_fill(lda);
+                cl.advance_fill(ldb);
+            }
+        }
+    });
+}
+
+// Epilogue of the 16x16 blocks: lane l holds, for block (bm, bn) and register r, tile row
+// wm0 + 16*bm + 4*(l/16) + r and tile column wn0 + 16*bn + l%16.
+template <class Cfg>
+__device__ __forceinline__ void hstore_tile16(const floatx4 (&acc)[Cfg::WM / 16][Cfg::WN / 16], _Float16 *C, int64_t ldc,
+                                              int64_t M, int64_t N, float alpha, float beta, int64_t m0, int64_t n0,
+                                              const SplitPlan &split, const WorkItem &w)
+{
+    constexpr int MB16 = Cfg::WM / 16, NB16 = Cfg::WN / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
+    const bool raw = split.plain && w.nslice > 1;
+    float *Z = raw ? split.partials + (int64_t)w.slice * split.slice_stride : nullptr;
+    if (!raw && beta != 0.0f && m0 + Cfg::BM <= M && n0 + Cfg::BN <= N) {
+        // tile wholly inside C: old values of a block row are fetched before the first is used
+        _Float16 *base = C + (m0 + wm0 + 4 * g) * ldc + (n0 + wn0 + i);
+#pragma unroll
+        for (int bm = 0; bm < MB16; ++bm) {
+            _Float16 old[4][NB16];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int bn = 0; bn < NB16; ++bn) old[r][bn] = base[(16 * bm + r) * ldc + 16 * bn];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int bn = 0; bn < NB16; ++bn)
+                    base[(16 * bm + r) * ldc + 16 * bn] = (_Float16)__builtin_fmaf(beta, (float)old[r][bn], alpha * acc[bm][bn][r]);
+        }
+        return;
+    }
+#pragma unroll
+    for (int bm = 0; bm < MB16; ++bm)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t row = m0 + wm0 + 16 * bm + 4 * g + r;
+            if (row >= M) continue;
+#pragma unroll
+            for (int bn = 0; bn < NB16; ++bn) {
+                const int64_t col = n0 + wn0 + 16 * bn + i;
+                if (col >= N) continue;
+                if (raw) {
+                    Z[row * N + col] = acc[bm][bn][r];
+                } else {
+                    _Float16 *dst = C + row * ldc + col;
+                    float o = alpha * acc[bm][bn][r];
+                    if (beta != 0.0f) o += beta * (float)*dst;
+                    *dst = (_Float16)o;
+                }
+            }
+        }
+}
+
+// Needs K a multiple of 64, the alignment of hgemm_mfma16_kernel, and a plain split-K plan (raw slices).
+template <class Cfg, bool A_KCONTIG, bool B_KCONTIG>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mi16_dma64_kernel(const HGemmArgs g)
+{
+    constexpr int MB16 = Cfg::WM / 16, NB16 = Cfg::WN / 16;
+    typedef typename HLoader64Sel<A_KCONTIG, Cfg::BM, Cfg::NT, MB16, 16>::type RLT;
+    typedef typename HLoader64Sel<B_KCONTIG, Cfg::BN, Cfg::NT, NB16, 16>::type CLT;
+    constexpr int A_H = Cfg::A_HALVES, STAGE_H = Cfg::STAGE_HALVES;
+    constexpr uint32_t STAGE_B = STAGE_H * 2;
+    constexpr int NMMA = MB16 * NB16, NFILL = RLT::NFILL + CLT::NFILL, SP = NMMA / NFILL;
+    constexpr int N1 = (NMMA - NB16 + SP - 1) / SP;
+    __shared__ __attribute__((aligned(1024))) _Float16 smem[2 * STAGE_H];
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lds_ptr)smem;
+#else
+    const uint32_t smem_lds = 0;
+#endif
+
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();
+        g.clock_probe[blockIdx.x * 4 + 1] = __builtin_amdgcn_s_memrealtime();
+    }
+    const int tiles = g.tiles_m * g.tiles_n;
+    const WorkItem w = work_item(blockIdx.x, tiles, g.split);
+    int tm, tn;
+    tile_coords<8>(w.tile, g.tiles_m, g.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
+    int kt0, T, krem;
+    slice_range((int)(g.K / Cfg::BK), 0, w.slice, w.nslice, kt0, T, krem);
+    const int64_t k0 = (int64_t)kt0 * Cfg::BK;
+
+    const int wave = threadIdx.x >> 6;
+    RLT rl;
+    CLT cl;
+    rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x, (wave / Cfg::WAVES_N) * Cfg::WM);
+    cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x, (wave % Cfg::WAVES_N) * Cfg::WN);
+
+    floatx4 acc[MB16][NB16];
+#pragma unroll
+    for (int bm = 0; bm < MB16; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < NB16; ++bn)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[bm][bn][r] = 0.0f;
+
+    auto fill_range = [&](auto loc, auto hic, uint32_t stage_lds) {  // pieces LO .. HI-1 of the tile at the fill pointers
+        constexpr int LO = decltype(loc)::value, HI = decltype(hic)::value;
+        static_for<HI - LO>([&](auto ic) {
+            constexpr int st = LO + decltype(ic)::value;
+            if constexpr (st < RLT::NFILL)
+                rl.template fill_piece<st>(stage_lds);
+            else
+                cl.template fill_piece<st - RLT::NFILL>(stage_lds + A_H * 2);
+        });
+    };
+    typedef std::integral_constant<int, 0> I0;
+
+    // Prologue: tile 0 landed in stage 0 and visible to all waves; the first N1 loads of tile 1 on their way
+    // into stage 1 (iteration 0 issues the rest and moves the pointers on).
+    if (T > 0) {
+        fill_range(I0(), std::integral_constant<int, NFILL>(), smem_lds);
+        rl.advance_fill(g.lda);
+        cl.advance_fill(g.ldb);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (T > 1) fill_range(I0(), std::integral_constant<int, N1>(), smem_lds + STAGE_B);
+
+    HFrag16<Cfg> fr;
+    if (T > 0) {
+        static_for<MB16>([&](auto bc) { fr.a[decltype(bc)::value] = rl.template read_frag<0, decltype(bc)::value>(smem_lds); });
+        static_for<NB16>([&](auto bc) { fr.b[decltype(bc)::value] = cl.template read_frag<0, decltype(bc)::value>(smem_lds + A_H * 2); });
+    }
+
+    int t = 0;
+    while (t + 3 < T) {   // steady state, two tiles per trip (stage addresses are constants)
+        htile_iter_mi16<Cfg, true>(rl, cl, fr, acc, smem_lds, smem_lds + STAGE_B, g.lda, g.ldb);
+        htile_iter_mi16<Cfg, true>(rl, cl, fr, acc, smem_lds + STAGE_B, smem_lds, g.lda, g.ldb);
+        t += 2;
+    }
+    for (; t < T; ++t) {  // the last tiles (t is even here): the same iteration with its conditions
+        const uint32_t cs = (uint32_t)(t & 1);
+        htile_iter_mi16<Cfg, false>(rl, cl, fr, acc, smem_lds + cs * STAGE_B, smem_lds + (cs ^ 1u) * STAGE_B, g.lda, g.ldb,
+                                    t + 2 < T, t + 1 < T);
+    }
+
+    hstore_tile16<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
+    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
+        g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
+        g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
+    }
+}
+
+template <class Cfg>
+int launch_hgemm_mi16_dma64(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
+{
+    const int tiles = g.tiles_m * g.tiles_n;
+    if (g.K % Cfg::BK != 0 || (g.split.splits > 1 && (!g.split.plain || g.split.dp_tiles != 0))) return (int)hipErrorInvalidValue;
+    const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
+    if (a_kcontig && b_kcontig)
+        hipLaunchKernelGGL((hgemm_mi16_dma64_kernel<Cfg, true, true>), grid, block, 0, stream, g);
+    else if (a_kcontig)
+        hipLaunchKernelGGL((hgemm_mi16_dma64_kernel<Cfg, true, false>), grid, block, 0, stream, g);
+    else if (b_kcontig)
+        hipLaunchKernelGGL((hgemm_mi16_dma64_kernel<Cfg, false, true>), grid, block, 0, stream, g);
+    else
+        hipLaunchKernelGGL((hgemm_mi16_dma64_kernel<Cfg, false, false>), grid, block, 0, stream, g);
+    return (int)hipGetLastError();
+}
+
 template <class Cfg>
 int launch_hgemm_mfma16_dma64(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
 {
@@ -1050,6 +1318,7 @@ struct HCfgDesc {
     int (*launch)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);      // all loads through registers
     int (*launch_dma)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);  // operands stored along k: global -> LDS
     int (*launch_dma64)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);  // the same with a K tile of 64 (K % 64 == 0), or null
+    int (*launch_mi16)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);   // K tile of 64 on the 16x16x32 instruction, or null
 };
 constexpr int kNumHCfg = 3;
 const HCfgDesc &hcfg_desc(int i);  // defined in hgemm_instance.hip

@@ -678,17 +678,17 @@ def test_hgemm_4096_sampled(dm, torch):
 
 @pytest.mark.parametrize("tA,tB", TRANS)
 @pytest.mark.parametrize("K", [32, 64, 96, 128, 160, 192, 224, 256, 288, 320, 384, 448, 512, 640])
-@pytest.mark.parametrize("path", [1, 2, 3, 17, 19, 33])
+@pytest.mark.parametrize("path", [1, 2, 3, 17, 19, 33, 65, 67])
 def test_hgemm_fp16_instruction_k_ranges(dm, torch, tA, tB, K, path):
     """The FP16-input matrix-instruction kernels (8-wave and 4-wave tile; register staging, global -> LDS loads
-    with K tiles of 32 and of 64) over every prologue / steady / drain combination of K tiles."""
+    with K tiles of 32 and of 64, the latter on both forms of the instruction) over every prologue / steady / drain combination of K tiles."""
     dm.dmath_set_hgemm_path(path)
     run_hgemm_case(dm, torch, tA, tB, 264, 520, K, ints=True, exact=True, beta=1.0, seed=K + tA)
     run_hgemm_case(dm, torch, tA, tB, 264, 520, K, alpha=0.75, beta=-0.5, seed=K + tB, ld_extra=(8, 16, 3))
 
 
 @pytest.mark.parametrize("tA,tB", TRANS)
-@pytest.mark.parametrize("path", [1, 2, 3, 18, 33])
+@pytest.mark.parametrize("path", [1, 2, 3, 18, 33, 65, 67])
 def test_hgemm_fp16_instruction_shapes(dm, torch, tA, tB, path):
     dm.dmath_set_hgemm_path(path)
     m_odd = 37 if tA == 0 else 40          # an operand stored along its own index needs a multiple of 8
