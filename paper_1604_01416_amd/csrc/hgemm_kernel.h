@@ -1038,14 +1038,16 @@ struct HFrag16 {
     halfx8 a[Cfg::WM / 16], b[Cfg::WN / 16];
 };
 
-// Slot program of one tile (NMMA matrix instructions per k step, numbered q; row bm = q / NB16):
+// Slot program of one tile (NMMA matrix instructions per k step, numbered q):
 //   k step 0: operands of k step 1 replace those of k step 0 as they die (read from the current stage);
 //             the last loads of tile t + 1 (those that did not fit k step 1 of the previous iteration).
-//   k step 1: after row 0 the one barrier of the iteration: by then the wave has used every fragment
-//             it read from the current stage and has waited for its own loads of tile t + 1, so after
-//             it the current stage is free and the next stage complete.  The rest of the step reads
-//             the next tile's first operands from the next stage and issues the loads of tile t + 2
-//             into the current stage, one every SP instructions.
+//   k step 1: after the first pair of rows the one barrier of the iteration: by then the wave has used
+//             every fragment it read from the current stage and has waited for its own loads of tile
+//             t + 1, so after it the current stage is free and the next stage complete.  The rest of
+//             the step reads the next tile's first operands from the next stage and issues the loads
+//             of tile t + 2 into the current stage, one every SP instructions.
+// Block rows go in pairs, alternating along the block columns: a B operand then dies 2*NB16 - 1
+// instructions before its replacement is first used (NB16 with the rows one after the other).
 template <class Cfg, bool STEADY, class RL, class CL>
 __device__ __forceinline__ void htile_iter_mi16(RL &rl, CL &cl, HFrag16<Cfg> &fr, floatx4 (&acc)[Cfg::WM / 16][Cfg::WN / 16],
                                                 uint32_t cur_lds, uint32_t nxt_lds, int64_t lda, int64_t ldb,
@@ -1058,9 +1060,10 @@ __device__ __forceinline__ void htile_iter_mi16(RL &rl, CL &cl, HFrag16<Cfg> &fr
     constexpr int MB16 = Cfg::WM / 16, NB16 = Cfg::WN / 16, NMMA = MB16 * NB16;
     constexpr int NFILL = RL::NFILL + CL::NFILL;
     constexpr int SP = NMMA / NFILL;                       // matrix instructions between two loads
-    constexpr int N1 = (NMMA - NB16 + SP - 1) / SP;        // loads issued in k step 1 (after the barrier)
+    constexpr int BAR = 2 * NB16 - 1;                      // the barrier follows this instruction of k step 1
+    constexpr int N1 = (NMMA - BAR - 1 + SP - 1) / SP;     // loads issued in k step 1 (after the barrier)
     constexpr uint32_t B_IMG = Cfg::A_HALVES * 2;
-    static_assert(NMMA % NFILL == 0 && N1 <= NFILL && (NFILL - N1) * SP <= NMMA, "loads fit their slots");
+    static_assert(MB16 % 2 == 0 && NMMA % NFILL == 0 && N1 <= NFILL && (NFILL - N1) * SP <= NMMA, "loads fit their slots");
     auto fill_one = [&](auto stc, uint32_t stage_lds) {
         constexpr int st = decltype(stc)::value;
         if constexpr (st < RL::NFILL)
@@ -1073,22 +1076,27 @@ __device__ __forceinline__ void htile_iter_mi16(RL &rl, CL &cl, HFrag16<Cfg> &fr
         const uint32_t src = ks == 0 ? cur_lds : nxt_lds;   // stage the replacement operands come from
         const bool rd = ks == 0 ? true : has_next;
         static_for<NMMA>([&](auto qc) {
-            constexpr int q = decltype(qc)::value, bm = q / NB16, bn = q % NB16;
+            // block rows are taken in pairs, the two rows of a pair alternating along the block columns
+            constexpr int q = decltype(qc)::value, pair = q / (2 * NB16), wi = q % (2 * NB16);
+            constexpr int bm = 2 * pair + wi % 2, bn = wi / 2;
             acc[bm][bn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fr.a[bm], fr.b[bn], acc[bm][bn], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (ks == 1 && q == NB16 - 1) {
+            if constexpr (ks == 1 && q == BAR) {
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if constexpr (bn == NB16 - 1) {   // row bm done: its A operand is dead
-                if (rd) fr.a[bm] = rl.template read_frag<1 - ks, bm>(src);
+            if constexpr (wi == 2 * NB16 - 1) {    // pair done: both its A operands are dead (after the barrier, if any)
+                if (rd) {
+                    fr.a[bm - 1] = rl.template read_frag<1 - ks, bm - 1>(src);
+                    fr.a[bm] = rl.template read_frag<1 - ks, bm>(src);
+                }
             }
-            if constexpr (bm == MB16 - 1) {   // last row: this B operand is dead
+            if constexpr (bm == MB16 - 1) {        // last pair, second row: this B operand is dead
                 if (rd) fr.b[bn] = cl.template read_frag<1 - ks, bn>(src + B_IMG);
             }
-            if constexpr (ks == 1 && q >= NB16 && (q - NB16) % SP == 0) {
-                if (do_fill) fill_one(std::integral_constant<int, (q - NB16) / SP>{}, cur_lds);
+            if constexpr (ks == 1 && q > BAR && (q - BAR - 1) % SP == 0) {
+                if (do_fill) fill_one(std::integral_constant<int, (q - BAR - 1) / SP>{}, cur_lds);
             }
             if constexpr (ks == 0 && q % SP == 0 && N1 + q / SP < NFILL) {
                 if (has_next) fill_one(std::integral_constant<int, N1 + q / SP>{}, nxt_lds);
@@ -1167,7 +1175,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mi16_dma64_kern
     constexpr int A_H = Cfg::A_HALVES, STAGE_H = Cfg::STAGE_HALVES;
     constexpr uint32_t STAGE_B = STAGE_H * 2;
     constexpr int NMMA = MB16 * NB16, NFILL = RLT::NFILL + CLT::NFILL, SP = NMMA / NFILL;
-    constexpr int N1 = (NMMA - NB16 + SP - 1) / SP;
+    constexpr int N1 = (NMMA - 2 * NB16 + SP - 1) / SP;   // as in htile_iter_mi16
     __shared__ __attribute__((aligned(1024))) _Float16 smem[2 * STAGE_H];
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
