@@ -1,7 +1,15 @@
-// GEMM on half-precision storage computed on the FP16-input matrix instruction
-// (v_mfma_f32_32x32x16_f16): the product of two halves is exact in FP32 and the instruction accumulates
-// in FP32, so the arithmetic is the single-precision arithmetic on converted operands that section
-// "Precisions" of the paper describes, at the rate of the 16-bit matrix pipe.
+// GEMM on half-precision storage computed on the FP16-input matrix instructions
+// (v_mfma_f32_32x32x16_f16, v_mfma_f32_16x16x32_f16): the product of two halves is exact in FP32 and the
+// instructions accumulate in FP32, so the arithmetic is the single-precision arithmetic on converted
+// operands that section "Precisions" of the paper describes, at the rate of the 16-bit matrix pipe.
+//
+// Four kernels, oldest first; the host (gemm_entry in dmath_api.hip) picks the last one that applies:
+//   hgemm_mfma16_kernel       K tile 32, operands staged through registers, every orientation (K % 32 == 0)
+//   hgemm_mfma16_dma_kernel   K tile 32, global -> LDS loads, both operands stored along k
+//   hgemm_mfma16_dma64_kernel K tile 64 (whole cache lines), global -> LDS loads, every orientation: an operand
+//                             stored along its own index is read back with the transposing LDS read (K % 64 == 0)
+//   hgemm_mi16_dma64_kernel   the same on the 16x16x32 instruction, which holds a higher clock under the power limit
+// The text below describes the first; each of the others is described where it is defined.
 //
 // Operand layout of the instruction (checked on the device with one-hot operands): lane l holds, for
 // A, row l%32 and the 8 consecutive k = 8*(l/32) .. +7; for B, column l%32 and the same k; the 32x32
