@@ -429,6 +429,7 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
             g.tiles_n = (int)tiles_n;
             g.clock_probe = g_state.clock_probe;
             g.cvec = ((reinterpret_cast<uintptr_t>(C) & 7u) == 0 && ldc % 4 == 0) ? 1 : 0;
+            if (aligned16(C) && ldc % 8 == 0) g.cvec = 2;  // 16-byte stores of whole row pieces are possible
             g.split.dp_tiles = s > 1 ? 0 : (int)tiles;
             g.split.splits = (int)s;
             g.split.partials = s > 1 ? static_cast<float *>(g_state.ws) : nullptr;

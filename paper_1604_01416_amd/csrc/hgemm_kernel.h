@@ -1174,6 +1174,54 @@ __device__ __forceinline__ void hstore_tile16(const floatx4 (&acc)[Cfg::WM / 16]
         }
 }
 
+// Epilogue through LDS for beta == 0 and a tile wholly inside an aligned C: in the accumulator layout a
+// store instruction writes 32-byte pieces of four rows (2 bytes per lane), 128 of them per lane, and at
+// 4096^3 that epilogue was 11 % of the kernel.  Each wave instead rounds its WM x WN block to half into
+// a region of its own in LDS (the stages are dead by then: every wave has passed the last barrier of
+// the K loop, after its last fragment read) and copies it out with 16-byte stores of whole 256-byte row
+// pieces.  Rows are padded by 16 bytes so that the four row groups of a 2-byte write and the rows of a
+// 16-byte read fall on different banks.
+template <class Cfg>
+struct HEpilogueLds {
+    static constexpr int ROWB = Cfg::WN * 2 + 16;                          // bytes per staged row
+    static constexpr int BYTES = (Cfg::NT / 64) * Cfg::WM * ROWB;          // all waves
+    static constexpr int CH = Cfg::WN * 2 / 16, RPI = 64 / CH;             // 16-byte chunks per row, rows per instruction
+};
+
+template <class Cfg>
+__device__ __forceinline__ void hstore_tile16_lds(const floatx4 (&acc)[Cfg::WM / 16][Cfg::WN / 16], _Float16 *C, int64_t ldc,
+                                                  float alpha, int64_t m0, int64_t n0, uint32_t smem_lds)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef HEpilogueLds<Cfg> E;
+    constexpr int MB16 = Cfg::WM / 16, NB16 = Cfg::WN / 16;
+    typedef __attribute__((address_space(3))) _Float16 *lp16;
+    typedef __attribute__((address_space(3))) const halfx8 *lp128;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
+    const uint32_t region = smem_lds + (uint32_t)wave * (Cfg::WM * E::ROWB);
+    const uint32_t wr = region + (uint32_t)(4 * g) * E::ROWB + (uint32_t)i * 2;
+#pragma unroll
+    for (int bm = 0; bm < MB16; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < NB16; ++bn)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                *(lp16)(uintptr_t)(wr + (16 * bm + r) * E::ROWB + 32 * bn) = (_Float16)(alpha * acc[bm][bn][r]);
+    // the region is this wave's own: its writes only have to have landed
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(63));
+    const int row = lane / E::CH, ch = lane % E::CH;
+    const uint32_t rd = region + (uint32_t)row * E::ROWB + (uint32_t)ch * 16;
+    _Float16 *dst = C + (m0 + wm0 + row) * ldc + (n0 + wn0 + ch * 8);
+#pragma unroll
+    for (int it = 0; it < Cfg::WM / E::RPI; ++it) {
+        const halfx8 v = *(lp128)(uintptr_t)(rd + it * E::RPI * E::ROWB);
+        *reinterpret_cast<halfx8 *>(dst + (int64_t)it * E::RPI * ldc) = v;
+    }
+#endif
+}
+
 // Needs K a multiple of 64, the alignment of hgemm_mfma16_kernel, and a plain split-K plan (raw slices).
 template <class Cfg, bool A_KCONTIG, bool B_KCONTIG>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mi16_dma64_kernel(const HGemmArgs g)
@@ -1185,7 +1233,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mi16_dma64_kern
     constexpr uint32_t STAGE_B = STAGE_H * 2;
     constexpr int NMMA = MB16 * NB16, NFILL = RLT::NFILL + CLT::NFILL, SP = NMMA / NFILL;
     constexpr int N1 = (NMMA - 2 * NB16 + SP - 1) / SP < NFILL ? (NMMA - 2 * NB16 + SP - 1) / SP : NFILL;  // as in htile_iter_mi16
-    __shared__ __attribute__((aligned(1024))) _Float16 smem[2 * STAGE_H];
+    constexpr int SMEM_H = 2 * STAGE_H > HEpilogueLds<Cfg>::BYTES / 2 ? 2 * STAGE_H : HEpilogueLds<Cfg>::BYTES / 2;
+    static_assert(SMEM_H * 2 <= 160 * 1024, "LDS of one compute unit");
+    __shared__ __attribute__((aligned(1024))) _Float16 smem[SMEM_H];
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lds_ptr)smem;
@@ -1262,7 +1312,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mi16_dma64_kern
                                     t + 2 < T, t + 1 < T);
     }
 
-    hstore_tile16<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
+    // cvec here: C 16-byte aligned with ldc a multiple of 8 (set by the host for this kernel)
+    const bool raw = g.split.plain && w.nslice > 1;
+    if (!raw && g.beta == 0.0f && g.cvec == 2 && T > 0 && m0 + Cfg::BM <= g.M && n0 + Cfg::BN <= g.N)
+        hstore_tile16_lds<Cfg>(acc, g.C, g.ldc, g.alpha, m0, n0, smem_lds);
+    else
+        hstore_tile16<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
     if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
         g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
         g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();

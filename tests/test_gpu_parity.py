@@ -1040,3 +1040,14 @@ def test_paper_table_sizes_sampled(dm, torch, n):
     assert not torch.isnan(C).any()
     _sub_check(torch, C[rows][:, cols].cpu().numpy(), A[rows].cpu().numpy(), B[:, cols].cpu().numpy(), n, 1.0, 0.0, None,
                "table size %d" % n)
+
+
+@pytest.mark.parametrize("tA,tB", TRANS)
+@pytest.mark.parametrize("path", [1, 3])
+def test_hgemm_epilogue_through_lds(dm, torch, tA, tB, path):
+    """beta == 0, 16-byte aligned C with ldc a multiple of 8 and tiles wholly inside C: the 16x16x32 kernels round
+    the tile to half in LDS and store whole row pieces.  520 columns leave a ragged tile column on the other path."""
+    dm.dmath_set_hgemm_path(path)
+    run_hgemm_case(dm, torch, tA, tB, 512, 768, 192, ints=True, exact=True, seed=11 + path)
+    run_hgemm_case(dm, torch, tA, tB, 512, 520, 128, alpha=-1.5, seed=12 + path, ld_extra=(8, 8, 8))
+    run_hgemm_case(dm, torch, tA, tB, 264, 512, 64, seed=13 + path, ld_extra=(0, 0, 16), lead=(0, 0, 8))
