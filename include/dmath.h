@@ -122,9 +122,13 @@ size_t dmath_hgemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, 
  * The same multiply in double precision (section "Precisions": single and double precision are the
  * library's two nominal precisions): A, B, C, alpha and beta are FP64, products and sums are FP64 on
  * the double-precision matrix instruction.  Layout conventions, quick returns and error codes as for
- * dmath_gemm; any 8-byte aligned pointers and any legal leading dimensions are accepted.  There is no
- * split-K: a product with few output tiles runs on few compute units.  dmath_set_dgemm_config forces
- * one of the two tile configurations (0: 256 x 128, 1: 128 x 128; -1 automatic) for this thread.
+ * dmath_gemm; any 8-byte aligned pointers and any legal leading dimensions are accepted.  A product
+ * with few output tiles is cut into K slices when the registered workspace holds them (FP64 arrays of
+ * M x N, added in slice order by a second kernel: results do not depend on timing); without a workspace
+ * it runs unsplit on few compute units.  dmath_dgemm_workspace_bytes returns what the automatic plan
+ * would like (0 if it would not split); a split factor forced with dmath_set_override applies here too.
+ * dmath_set_dgemm_config forces one of the two tile configurations (0: 256 x 128, 1: 128 x 128;
+ * -1 automatic) for this thread.
  */
 dmath_status dmath_dgemm(dmath_op transA, dmath_op transB,
                          int64_t M, int64_t N, int64_t K,
@@ -133,6 +137,7 @@ dmath_status dmath_dgemm(dmath_op transA, dmath_op transB,
                          double beta, double *C, int64_t ldc,
                          void *stream);
 dmath_status dmath_set_dgemm_config(int tile_config);
+size_t dmath_dgemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K);
 
 /*
  * Accumulating sequence of block multiplies in one call (section "Matrix Multiplication": a worker's

@@ -302,16 +302,20 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void dgemm_tile_kernel(con
     __shared__ __attribute__((aligned(16))) double smem[S * Cfg::STAGE_DOUBLES];
 
     const int tiles = g.tiles_m * g.tiles_n;
-    const int tile = xcd_contiguous_id(blockIdx.x, tiles);
+    const WorkItem w = work_item(blockIdx.x, tiles, g.split);
     int tm, tn;
-    tile_coords<8>(tile, g.tiles_m, g.tiles_n, tm, tn);
+    tile_coords<8>(w.tile, g.tiles_m, g.tiles_n, tm, tn);
     const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
-    const int T = (int)(g.K / Cfg::BK), krem = (int)(g.K - (int64_t)T * Cfg::BK);
+    // K range of this workgroup: the whole K, or one slice of it (plain split-K: raw sums to the workspace)
+    const int ktiles_total = (int)(g.K / Cfg::BK);
+    int kt0, T, krem;
+    slice_range(ktiles_total, (int)(g.K - (int64_t)ktiles_total * Cfg::BK), w.slice, w.nslice, kt0, T, krem);
+    const int64_t k0 = (int64_t)kt0 * Cfg::BK;
 
     typename DLoaderSel<Cfg, A_KCONTIG, Cfg::BM, Cfg::LDA, VEC>::type rl;
     typename DLoaderSel<Cfg, B_KCONTIG, Cfg::BN, Cfg::LDB, VEC>::type cl;
-    rl.init(g.A, g.lda, m0, g.M, 0, threadIdx.x);
-    cl.init(g.B, g.ldb, n0, g.N, 0, threadIdx.x);
+    rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x);
+    cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int a_off = (lane >> 4) * Cfg::LDA + (wave / Cfg::WAVES_N) * Cfg::WM + 2 * (lane & 15);
@@ -381,13 +385,20 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void dgemm_tile_kernel(con
         first_frags(smem);
         dtile_iter<Cfg, false>(rl, cl, fr, acc, smem, smem, smem, a_off, b_off, false, false, false);
     }
+    if (w.nslice > 1) {
+        // slice `slice` of the tile: its raw FP64 sums go to slice array `slice` (M x N, dense) in the workspace
+        double *Z = reinterpret_cast<double *>(g.split.partials) + (int64_t)w.slice * g.split.slice_stride;
+        dstore_tile<Cfg>(acc, Z, g.N, g.M, g.N, 1.0, 0.0, m0, n0);
+        return;
+    }
     dstore_tile<Cfg>(acc, g.C, g.ldc, g.M, g.N, sc.alpha, sc.beta, m0, n0);
 }
 
 template <class Cfg>
 int launch_dgemm(const DGemmArgs &g, double alpha, double beta, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t stream)
 {
-    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n)), block(Cfg::NT);
+    const int tiles = g.tiles_m * g.tiles_n;
+    const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
     const DGemmScalars sc = {alpha, beta};
 #define DMATH_DLAUNCH(AK, BK_, V) hipLaunchKernelGGL((dgemm_tile_kernel<Cfg, AK, BK_, V>), grid, block, 0, stream, g, sc)
     if (vec) {

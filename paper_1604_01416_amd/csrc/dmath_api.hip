@@ -71,6 +71,22 @@ __global__ void scale_kernel_f64(double *C, int64_t ldc, int64_t M, int64_t N, d
     }
 }
 
+// C = alpha * (slice 0 + slice 1 + ...) + beta * C for the FP64 product, slices added in slice order.
+__global__ void splitk_reduce_kernel_f64(const double *ws, int splits, int64_t slice_stride, double *C, int64_t ldc, int64_t M,
+                                         int64_t N, double alpha, double beta)
+{
+    const int64_t total = M * N;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        double sum = ws[e];
+        for (int z = 1; z < splits; ++z) sum += ws[(int64_t)z * slice_stride + e];
+        const int64_t row = e / N, col = e - row * N;
+        double *dst = C + row * ldc + col;
+        double o = alpha * sum;
+        if (beta != 0.0) o += beta * *dst;
+        *dst = o;
+    }
+}
+
 __global__ void scale_kernel(_Float16 *C, int64_t ldc, int64_t M, int64_t N, float beta)
 {
     const int64_t total = M * N;
@@ -514,6 +530,30 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     return DMATH_OK;
 }
 
+// FP64 product: tile configuration and K split.  Few tiles (fewer than 3/4 of the compute units with
+// the 128x128 tile) are cut into K slices, as many as fill the device, each at least 8 K tiles long;
+// the slices are FP64 arrays of M x N in the workspace, added in slice order by a second kernel.
+int dgemm_cfg_choice(int64_t M, int64_t N)
+{
+    if (g_state.dgemm_cfg >= 0) return g_state.dgemm_cfg;
+    return ceil_div(M, dcfg_desc(0).BM) * ceil_div(N, dcfg_desc(0).BN) >= (kNumCU * 3) / 4 ? 0 : 1;
+}
+
+int64_t dgemm_split_choice(int cfg, int64_t M, int64_t N, int64_t K, size_t avail)
+{
+    const DCfgDesc &d = dcfg_desc(cfg);
+    const int64_t tiles = ceil_div(M, d.BM) * ceil_div(N, d.BN), ktiles = K / d.BK;
+    int64_t s = 1;
+    if (g_state.force_split >= 1)
+        s = g_state.force_split;
+    else if (tiles < (kNumCU * 3) / 4)
+        s = kNumCU / tiles;
+    if (s > kMaxSplits) s = kMaxSplits;
+    if (s > ktiles / 8) s = ktiles / 8;
+    while (s > 1 && (size_t)s * (size_t)M * (size_t)N * sizeof(double) > avail) --s;
+    return s < 1 ? 1 : s;
+}
+
 extern "C" {
 
 const char *dmath_version(void) { return "dmath-mi355x 0.1 (gfx950, fp32 mfma)"; }
@@ -600,6 +640,15 @@ size_t dmath_hgemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, 
     return need;
 }
 
+size_t dmath_dgemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K)
+{
+    (void)transA;
+    (void)transB;
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    const int64_t s = dgemm_split_choice(dgemm_cfg_choice(M, N), M, N, K, ~(size_t)0);
+    return s > 1 ? (size_t)s * (size_t)M * (size_t)N * sizeof(double) : 0;
+}
+
 dmath_status dmath_gemm_plan(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, int *tile_config,
                              int *split_k)
 {
@@ -661,8 +710,7 @@ dmath_status dmath_dgemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N,
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
     // the large tile once it fills the compute units most of a round, else the small one
-    int cfg = g_state.dgemm_cfg;
-    if (cfg < 0) cfg = ceil_div(M, dcfg_desc(0).BM) * ceil_div(N, dcfg_desc(0).BN) >= (kNumCU * 3) / 4 ? 0 : 1;
+    const int cfg = dgemm_cfg_choice(M, N);
     const DCfgDesc &d = dcfg_desc(cfg);
     const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
     if (tiles_m * tiles_n > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
@@ -681,15 +729,24 @@ dmath_status dmath_dgemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N,
     g.tiles_m = (int)tiles_m;
     g.tiles_n = (int)tiles_n;
     g.cvec = 0;
-    g.split.dp_tiles = (int)(tiles_m * tiles_n);
-    g.split.splits = 1;
-    g.split.partials = nullptr;
+    const int64_t s = dgemm_split_choice(cfg, M, N, K, g_state.ws ? g_state.ws_bytes : 0);
+    if (tiles_m * tiles_n * s > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
+    g.split.dp_tiles = s > 1 ? 0 : (int)(tiles_m * tiles_n);
+    g.split.splits = (int)s;
+    g.split.partials = s > 1 ? static_cast<float *>(g_state.ws) : nullptr;   // FP64 slices; the kernel casts
     g.split.counters = nullptr;
-    g.split.plain = 0;
-    g.split.slice_stride = 0;
+    g.split.plain = s > 1 ? 1 : 0;
+    g.split.slice_stride = M * N;
     g.clock_probe = nullptr;
     const bool vec = aligned16(A) && aligned16(B) && lda % 2 == 0 && ldb % 2 == 0 && (a_k || M % 2 == 0) && (b_k || N % 2 == 0);
     if (d.launch(g, alpha, beta, a_k, b_k, vec, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    if (s > 1) {
+        const int64_t total = M * N;
+        const int blocks = (int)(ceil_div(total, 256) < 8192 ? ceil_div(total, 256) : 8192);
+        hipLaunchKernelGGL(splitk_reduce_kernel_f64, dim3(blocks), dim3(256), 0, stream, static_cast<const double *>(g_state.ws),
+                           (int)s, M * N, C, ldc, M, N, alpha, beta);
+        if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+    }
     return DMATH_OK;
 }
 

@@ -15,7 +15,7 @@ OK, ERR_INVALID_ARG, ERR_NULL_PTR, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_WORKSPACE = 
 OP_N, OP_T = 0, 1
 
 EXPORTS = (
-    "dmath_gemm", "dmath_conv2d_fwd", "dmath_conv2d_bwd_data", "dmath_conv2d_bwd_filter", "dmath_gemm_panels", "dmath_hgemm", "dmath_set_hgemm_path", "dmath_hgemm_workspace_bytes", "dmath_dgemm", "dmath_set_dgemm_config", "dmath_gemm_workspace_bytes", "dmath_set_workspace",
+    "dmath_gemm", "dmath_conv2d_fwd", "dmath_conv2d_bwd_data", "dmath_conv2d_bwd_filter", "dmath_gemm_panels", "dmath_hgemm", "dmath_set_hgemm_path", "dmath_hgemm_workspace_bytes", "dmath_dgemm", "dmath_set_dgemm_config", "dmath_dgemm_workspace_bytes", "dmath_gemm_workspace_bytes", "dmath_set_workspace",
     "dmath_set_override", "dmath_set_clock_probe", "dmath_gemm_plan", "dmath_num_configs", "dmath_config_name", "dmath_last_error_arg",
     "dmath_status_string", "dmath_version",
 )
@@ -43,6 +43,8 @@ _lib.dmath_set_dgemm_config.restype = _int
 _lib.dmath_set_dgemm_config.argtypes = [_int]
 _lib.dmath_hgemm_workspace_bytes.restype = ctypes.c_size_t
 _lib.dmath_hgemm_workspace_bytes.argtypes = [_int, _int, _i64, _i64, _i64]
+_lib.dmath_dgemm_workspace_bytes.restype = ctypes.c_size_t
+_lib.dmath_dgemm_workspace_bytes.argtypes = [_int, _int, _i64, _i64, _i64]
 _lib.dmath_set_hgemm_path.restype = _int
 _lib.dmath_set_hgemm_path.argtypes = [_int]
 _lib.dmath_gemm_panels.restype = _int
@@ -121,6 +123,10 @@ def dmath_set_dgemm_config(tile_config):
 
 def dmath_hgemm_workspace_bytes(transA, transB, M, N, K):
     return _lib.dmath_hgemm_workspace_bytes(transA, transB, M, N, K)
+
+
+def dmath_dgemm_workspace_bytes(transA, transB, M, N, K):
+    return _lib.dmath_dgemm_workspace_bytes(transA, transB, M, N, K)
 
 
 def dmath_set_hgemm_path(path):

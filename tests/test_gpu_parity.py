@@ -1051,3 +1051,26 @@ def test_hgemm_epilogue_through_lds(dm, torch, tA, tB, path):
     run_hgemm_case(dm, torch, tA, tB, 512, 768, 192, ints=True, exact=True, seed=11 + path)
     run_hgemm_case(dm, torch, tA, tB, 512, 520, 128, alpha=-1.5, seed=12 + path, ld_extra=(8, 8, 8))
     run_hgemm_case(dm, torch, tA, tB, 264, 512, 64, seed=13 + path, ld_extra=(0, 0, 16), lead=(0, 0, 8))
+
+
+@pytest.mark.parametrize("tA,tB", TRANS)
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_dgemm_split_k(dm, torch, tA, tB, cfg):
+    """FP64 products with few tiles are cut into K slices (FP64 slice arrays in the workspace, added in slice order):
+    automatic and forced split factors, ragged K, beta != 0, and the unsplit fallback without a workspace."""
+    dm.dmath_set_dgemm_config(cfg)
+    run_dgemm_case(dm, torch, tA, tB, 130, 264, 1000, alpha=1.25, beta=0.5, seed=1)            # automatic: several slices
+    run_dgemm_case(dm, torch, tA, tB, 260, 136, 512, ints=True, exact=True, beta=1.0, seed=2)
+    for split in (2, 3, 64):
+        dm.dmath_set_override(-1, split)
+        run_dgemm_case(dm, torch, tA, tB, 67, 93, 515, seed=split, lead=(1, 1, 1))
+        run_dgemm_case(dm, torch, tA, tB, 256, 128, 768, ints=True, exact=True, beta=1.0, seed=split + 10)
+    dm.dmath_set_override(-1, -1)
+    assert dm.dmath_dgemm_workspace_bytes(tA, tB, 130, 264, 1000) > 0
+    assert dm.dmath_dgemm_workspace_bytes(tA, tB, 4096, 4096, 4096) == 0
+    ws = dm._test_workspace
+    try:
+        dm.check(dm.dmath_set_workspace(None, 0))                                               # no room: runs unsplit
+        run_dgemm_case(dm, torch, tA, tB, 130, 264, 1000, alpha=-1.0, beta=2.0, seed=3)
+    finally:
+        dm.check(dm.dmath_set_workspace(ws, ws.numel()))
