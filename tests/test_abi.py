@@ -122,3 +122,12 @@ def test_hgemm_workspace_query_is_host_side_only():
     need = dm.dmath_hgemm_workspace_bytes(0, 0, 256, 4096, 4096)
     assert need > 0 and need % (256 * 4096 * 4) == 0
     assert dm.dmath_hgemm_workspace_bytes(0, 0, 8192, 8192, 8192) == dm.dmath_gemm_workspace_bytes(0, 0, 8192, 8192, 8192)
+
+
+def test_dgemm_workspace_query_is_host_side_only():
+    from paper_1604_01416_amd import dmath as dm
+    assert dm.dmath_dgemm_workspace_bytes(0, 0, 0, 16, 16) == 0
+    assert dm.dmath_dgemm_workspace_bytes(0, 0, 4096, 4096, 4096) == 0          # enough tiles: no split
+    need = dm.dmath_dgemm_workspace_bytes(0, 0, 1024, 1024, 4096)               # 64 tiles: FP64 slices of the whole output
+    assert need > 0 and need % (1024 * 1024 * 8) == 0
+    assert dm.dmath_dgemm_workspace_bytes(1, 1, 1024, 1024, 64) == 0            # K too short to cut
