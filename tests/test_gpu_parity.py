@@ -1074,3 +1074,39 @@ def test_dgemm_split_k(dm, torch, tA, tB, cfg):
         run_dgemm_case(dm, torch, tA, tB, 130, 264, 1000, alpha=-1.0, beta=2.0, seed=3)
     finally:
         dm.check(dm.dmath_set_workspace(ws, ws.numel()))
+
+
+def test_calls_can_be_captured_in_a_graph(dm, torch):
+    """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation, counters cleared
+    by a kernel): a fully connected layer's three products (split-K slices and their reduction included) captured
+    in a HIP graph replay to the bits of the eager calls, on every replay, with eager work in between."""
+    rng = np.random.default_rng(77)
+    X = torch.from_numpy(rng.standard_normal((256, 1024)).astype(np.float32)).cuda()
+    W = torch.from_numpy((0.01 * rng.standard_normal((1024, 1024))).astype(np.float32)).cuda()
+    dY = torch.from_numpy((1e-3 * rng.standard_normal((256, 1024))).astype(np.float32)).cuda()
+    Y, dX, dW = (torch.zeros((256, 1024), device="cuda"), torch.zeros((256, 1024), device="cuda"),
+                 torch.zeros((1024, 1024), device="cuda"))
+
+    def layer():
+        dm.check(dm.dmath_gemm(0, 0, 256, 1024, 1024, 1.0, X, 1024, W, 1024, 0.0, Y, 1024))
+        dm.check(dm.dmath_gemm(0, 1, 256, 1024, 1024, 1.0, dY, 1024, W, 1024, 0.0, dX, 1024))
+        dm.check(dm.dmath_gemm(1, 0, 1024, 1024, 256, 1.0, X, 1024, dY, 1024, 0.0, dW, 1024))
+
+    layer()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (Y, dX, dW)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        layer()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        layer()
+    for replay in range(3):
+        for t in (Y, dX, dW):
+            t.fill_(float("nan"))                 # eager work between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref, name in zip((Y, dX, dW), want, ("Y", "dX", "dW")):
+            assert torch.equal(got, ref), "replay %d: %s differs from the eager result" % (replay, name)
