@@ -155,6 +155,8 @@ def main():
     ap.add_argument("--split-k", type=int, default=-1, help="force a split-K factor (tuning only)")
     ap.add_argument("--hgemm-path", type=int, default=-1, help="force the dmath_hgemm kernel (see dmath_set_hgemm_path)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time its replays (launch-bound workloads: gemm256, fc, fc_half)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the workload, run `steps` device copies of 256 MiB (for scaling HBM counters)")
     args = ap.parse_args()
@@ -278,6 +280,18 @@ def main():
     if conv is None:
         probe = torch.zeros(32, dtype=torch.int64, device="cuda")
         dm.check(dm.dmath_set_clock_probe(probe))
+    if args.graph:   # the same kernels, launched by one graph replay per step
+        step()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        captured = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(captured, stream=side):
+            step()
+        eager_step, step = step, captured.replay
     ms_ev, ms_wall = _time_steps(torch, step, args.steps, args.warmup)
     tflops = flop / ms_ev / 1e9
     measured_clock_ghz = None
@@ -324,7 +338,7 @@ def main():
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_ev, "ms_per_step_host_clock": ms_wall, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": wl_name, "launches_per_step": launches, "flop_per_step": flop,
+        "config": {"workload": wl_name, "launches_per_step": launches, "flop_per_step": flop, "graph_replay": bool(args.graph),
                    "tile_config": dm.dmath_config_name(args.tile_config) if args.tile_config >= 0 else "auto",
                    "library": dm.dmath_version()},
         "pct_of_fp32_mfma_peak": 100.0 * tflops / peak if dtype == "f32" else None,
