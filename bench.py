@@ -43,7 +43,7 @@ MEASURED_HBM_TRAFFIC_BYTES = {
     "conv": int(((94222.2 + 1813.8) * 2.0 + 119617.7 + 2304.0) * 1024),         # profiles/conv3x3_n128_c256_k256_28x28_kernels.md
     "conv_bwd_data": int(((94333.7 + 5717.7) * 2.0 + 119641.9 + 2304.0) * 1024),   # profiles/conv3x3_..._bwd_data_kernels.md
     "conv_bwd_filter": int(((156909.8 + 32272.7) * 2.0 + 64512.0 + 2304.0) * 1024),  # profiles/conv3x3_..._bwd_filter_kernels.md
-    "hgemm4096": int((98406.3 * 2.0 + 32768.5) * 1024),                         # profiles/hgemm_nn_4096_half_storage_mfma16_kernel.md
+    "hgemm4096": int((98406.3 * 2.0 + 32768.5) * 1024),                         # profiles/hgemm_nn_4096_half_storage_mi16_dma64_kernel.md
     "fc_half": int(((2 * 8212.6 + 33922.3 + 6242.6 + 33920.1) * 2.0
                     + 2 * 2048.0 + 2 * 16384.5 + 32768.5) * 1024),              # profiles/fc_4096_batch256_half_storage_kernels.md
     "dgemm4096": int((666659.3 * 2.0 + 131745.2) * 1024),                       # profiles/dgemm_nn_4096_tile_kernel.md
