@@ -61,23 +61,50 @@ def _device_arrays(torch, arrays):
     return {k: torch.from_numpy(v).cuda() for k, v in arrays.items()}
 
 
-def _time_steps(torch, step, steps, warmup):
+def _time_steps(torch, step, steps, warmup, per_step=True, before_step=None):
     """warmup untimed steps, then exactly `steps` timed ones between synchronisations.
 
-    Returns (ms per step by HIP events on the launch stream, ms per step by the host clock)."""
-    for _ in range(warmup):
+    The timed region is bracketed by one HIP event pair on the launch stream (its span / steps is the
+    mean that the benchmark reports).  Inside it an event is also recorded at every step boundary
+    (per_step) or at the boundaries of five equal batches (launch-bound workloads, where an event per
+    step would be a visible share of the step), which gives the spread over the region.
+    before_step(i), if given, is called on the host before step i of the timed region (i < 0: warm-up).
+
+    Returns a dict: ms (mean per step by the events), ms_host (by the host clock), per_step_ms or
+    batch_ms (list), events_per ("step" | "batch")."""
+    for i in range(warmup):
+        if before_step is not None:
+            before_step(i - warmup)
         step()
     torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
+    if per_step:
+        marks = list(range(steps + 1))
+    else:
+        nb = min(5, steps)
+        marks = sorted(set(round(j * steps / nb) for j in range(nb + 1)))
+    ev = {m: torch.cuda.Event(enable_timing=True) for m in marks}
     t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
+    ev[0].record()
+    for i in range(steps):
+        if before_step is not None:
+            before_step(i)
         step()
-    e1.record()
+        if i + 1 in ev:
+            ev[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    return e0.elapsed_time(e1) / steps, (t1 - t0) * 1e3 / steps
+    spans = [ev[a].elapsed_time(ev[b]) / (b - a) for a, b in zip(marks[:-1], marks[1:])]
+    out = {"ms": ev[0].elapsed_time(ev[steps]) / steps, "ms_host": (t1 - t0) * 1e3 / steps,
+           "events_per": "step" if per_step else "batch"}
+    out["per_step_ms" if per_step else "batch_ms"] = spans
+    return out
+
+
+def _spread(values):
+    v = sorted(values)
+    n = len(v)
+    med = v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
+    return {"median": med, "min": v[0], "max": v[-1]}
 
 
 def _cpu_model():
@@ -92,29 +119,33 @@ def _cpu_model():
 
 
 def _cpu_baseline_gemm(oracle, call, arrays, budget_s=15.0):
-    """The oracle as it stands on a bounded sample: the first R rows of C (all N columns, full K)."""
+    """The oracle as it stands on a bounded sample: the first R rows of C (all N columns, full K).
+
+    Returns (report, rows, ref, mag): the timing report, and the oracle's sums for those rows so that
+    the caller can hold the GPU result against them."""
     A, B = arrays[call.A], arrays[call.B]
     C0 = arrays[call.C] if call.beta != 0.0 else None
 
     def run(rows):
         t0 = time.perf_counter()
-        oracle.gemm(call.transA, call.transB, rows, call.N, call.K, call.alpha, A, call.lda, B, call.ldb,
-                    call.beta, C0, call.ldc)
-        return time.perf_counter() - t0
+        ref, mag = oracle.gemm(call.transA, call.transB, rows, call.N, call.K, call.alpha, A, call.lda, B, call.ldb,
+                               call.beta, C0, call.ldc)
+        return time.perf_counter() - t0, ref, mag
 
     threads = oracle.num_threads()
     probe_rows = min(call.M, 2 * threads)
-    t_probe = max(run(probe_rows), 1e-4)
+    t_probe = max(run(probe_rows)[0], 1e-4)
     rows = int(min(call.M, max(probe_rows, probe_rows * budget_s / t_probe)))
     rows = max(threads, rows - rows % threads)
     rows = min(rows, call.M)
-    t = run(rows)
+    t, ref, mag = run(rows)
     flop = 2.0 * rows * call.N * call.K
     return {
         "value": flop / t / 1e12, "unit": "TFLOP/s", "cores": threads, "cpu_model": _cpu_model(), "kind": "oracle",
+        "seconds": t, "seconds_whole_call_extrapolated": t * call.M / rows,
         "sample": "first %d of %d rows of C (all %d columns, full K=%d), FP64 sums plus the magnitude sums, %.1f s"
                   % (rows, call.M, call.N, call.K, t),
-    }
+    }, rows, ref, mag
 
 
 def _cpu_baseline_conv(oracle, wl, budget_s=15.0):
@@ -128,18 +159,19 @@ def _cpu_baseline_conv(oracle, wl, budget_s=15.0):
     def run(npts):
         idx = rng.choice(total, size=npts, replace=False)
         t0 = time.perf_counter()
-        oracle.conv2d_fwd_points(wl.x, wl.w, idx, pad=wl.pad, stride=wl.stride)
-        return time.perf_counter() - t0
+        ref, mag = oracle.conv2d_fwd_points(wl.x, wl.w, idx, pad=wl.pad, stride=wl.stride)
+        return time.perf_counter() - t0, idx, ref, mag
 
     probe = 20000
-    t_probe = max(run(probe), 1e-4)
+    t_probe = max(run(probe)[0], 1e-4)
     npts = int(min(total, max(probe, probe * budget_s / t_probe)))
-    t = run(npts)
+    t, idx, ref, mag = run(npts)
     return {
         "value": 2.0 * npts * K / t / 1e12, "unit": "TFLOP/s", "cores": threads, "cpu_model": _cpu_model(), "kind": "oracle",
+        "seconds": t, "seconds_whole_call_extrapolated": t * total / npts,
         "sample": "%d random output elements of %d (all %d taps each), FP64 sums plus the magnitude sums, %.1f s"
                   % (npts, total, K, t),
-    }
+    }, idx, ref, mag
 
 
 def main():
@@ -155,6 +187,8 @@ def main():
     ap.add_argument("--split-k", type=int, default=-1, help="force a split-K factor (tuning only)")
     ap.add_argument("--hgemm-path", type=int, default=-1, help="force the dmath_hgemm kernel (see dmath_set_hgemm_path)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
+    ap.add_argument("--detail", action="store_true",
+                    help="add the per-step (or per-batch) times and the shader clock of every launch to the line")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (launch-bound workloads: gemm256, fc, fc_half)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -178,7 +212,7 @@ def main():
         nbytes = 256 << 20
         src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
-        ms, _ = _time_steps(torch, lambda: dst.copy_(src), args.steps, args.warmup)
+        ms = _time_steps(torch, lambda: dst.copy_(src), args.steps, args.warmup, per_step=False)["ms"]
         print(json.dumps({"copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "steps": args.steps,
                           "ms_per_copy": ms, "GBps": 2 * nbytes / ms / 1e6}))
         return
@@ -274,12 +308,18 @@ def main():
             launches = 1
             wl_name = wl.name + "_fused"
 
-    # Clock the tile kernel really runs at (GEMM workloads): the in-kernel stamps stay on during the
-    # timed steps (two scalar stores per launch by 8 workgroups); the last launch's values are read.
+    # Clock the tile kernel really runs at (GEMM workloads): the in-kernel stamps stay on during warm-up
+    # and timed steps (four 8-byte global stores by one lane of 8 workgroups per launch), every step into
+    # a row of its own, so the line can say how the clock moved over the region it timed.
     probe = None
+    before_step = None
     if conv is None:
-        probe = torch.zeros(32, dtype=torch.int64, device="cuda")
-        dm.check(dm.dmath_set_clock_probe(probe))
+        probe = torch.zeros((args.warmup + args.steps, 32), dtype=torch.int64, device="cuda")
+        rows_of_probe = [probe[i] for i in range(args.warmup + args.steps)]
+        dm.check(dm.dmath_set_clock_probe(rows_of_probe[-1]))
+        if not args.graph:   # a captured launch keeps the pointer it was captured with
+            def before_step(i):
+                dm.dmath_set_clock_probe(rows_of_probe[i + args.warmup])
     if args.graph:   # the same kernels, launched by one graph replay per step
         step()
         torch.cuda.synchronize()
@@ -292,17 +332,37 @@ def main():
         with torch.cuda.graph(captured, stream=side):
             step()
         eager_step, step = step, captured.replay
-    ms_ev, ms_wall = _time_steps(torch, step, args.steps, args.warmup)
+    # one event per step where a step is long enough not to notice it (an event costs about a microsecond
+    # on the stream); launch-bound workloads get five batches instead
+    per_step = args.workload not in ("gemm256", "fc", "fc_nn", "fc_nt", "fc_tn", "fc_half") and not args.graph
+    timing = _time_steps(torch, step, args.steps, args.warmup, per_step=per_step, before_step=before_step)
+    ms_ev, ms_wall = timing["ms"], timing["ms_host"]
     tflops = flop / ms_ev / 1e9
+    spans = timing.get("per_step_ms") or timing["batch_ms"]
+    spread = _spread(spans)
+    nb = min(5, len(spans))
+    batches = [sum(spans[round(j * len(spans) / nb):round((j + 1) * len(spans) / nb)]) /
+               max(1, round((j + 1) * len(spans) / nb) - round(j * len(spans) / nb)) for j in range(nb)]
     measured_clock_ghz = None
+    clock_per_step = None
     if probe is not None:
         dm.check(dm.dmath_set_clock_probe(None))
-        p = [int(v) for v in probe.cpu().tolist()]
-        per_die = [(p[4 * d + 2] - p[4 * d]) / (p[4 * d + 3] - p[4 * d + 1]) * 0.1
-                   for d in range(8) if p[4 * d + 3] > p[4 * d + 1]]
-        if per_die:
-            measured_clock_ghz = {"mean": sum(per_die) / len(per_die), "min": min(per_die), "max": max(per_die)}
+        clock_per_step = []
+        for row in probe.cpu().tolist():
+            p = [int(v) for v in row]
+            per_die = [(p[4 * d + 2] - p[4 * d]) / (p[4 * d + 3] - p[4 * d + 1]) * 0.1
+                       for d in range(8) if p[4 * d + 3] > p[4 * d + 1]]
+            clock_per_step.append(sum(per_die) / len(per_die) if per_die else None)
+        timed = [c for c in clock_per_step[args.warmup:] if c is not None]
+        if timed:
+            measured_clock_ghz = {"mean": sum(timed) / len(timed), "min": min(timed), "max": max(timed),
+                                  "first_timed_step": timed[0], "last_timed_step": timed[-1],
+                                  "first_warmup_step": clock_per_step[0]}
 
+    # The oracle on this machine's host cores on a bounded sample, and the output of the timed launches held
+    # against it (beta == 0 workloads recompute the same C every step; an accumulating first call is run
+    # once more from the stored C0).
+    check = None
     if not args.no_cpu_baseline:
         import oracle
         if args.workload in ("hgemm4096", "fc_half", "dgemm4096", "square"):
@@ -310,9 +370,25 @@ def main():
         elif conv is not None and args.workload != "conv":
             cpu_baseline = None   # the forward workload carries the oracle timing of this layer
         elif conv is not None:
-            cpu_baseline = _cpu_baseline_conv(oracle, conv)
+            cpu_baseline, idx, ref, mag = _cpu_baseline_conv(oracle, conv)
+            got = dy.reshape(-1)[torch.from_numpy(idx).cuda()].cpu().numpy().astype(np.float64)
+            ratio = np.abs(got - ref) / oracle.bound(conv.gemm_view[2], mag)
+            check = {"max_err_over_bound": float(ratio.max()), "max_abs_err": float(np.abs(got - ref).max()),
+                     "elements": int(idx.size), "passed": bool((ratio <= 1.0).all())}
         else:
-            cpu_baseline = _cpu_baseline_gemm(oracle, wl.calls[0], wl.arrays)
+            c0 = wl.calls[0]
+            cpu_baseline, rows, ref, mag = _cpu_baseline_gemm(oracle, c0, wl.arrays)
+            out_dev = dev[c0.C]   # (the fused update is held against its first panel's product through dmath_gemm)
+            if c0.beta != 0.0:
+                out_dev = torch.from_numpy(wl.arrays[c0.C]).cuda()
+                dm.check(dm.dmath_gemm(c0.transA, c0.transB, c0.M, c0.N, c0.K, c0.alpha, dev[c0.A], c0.lda, dev[c0.B],
+                                       c0.ldb, c0.beta, out_dev, c0.ldc))
+                torch.cuda.synchronize()
+            got = out_dev.reshape(-1)[:rows * c0.ldc].reshape(rows, c0.ldc)[:, :c0.N].cpu().numpy().astype(np.float64)
+            ratio = np.abs(got - ref) / oracle.bound(c0.K, mag)
+            check = {"max_err_over_bound": float(ratio.max()), "max_abs_err": float(np.abs(got - ref).max()),
+                     "elements": int(ratio.size), "passed": bool((ratio <= 1.0).all()),
+                     "what": "first call of the step, first %d rows of C, |gpu - ref| / (4*K*2^-24*mag + 1e-6)" % rows}
 
     # Dominant kernel: the MFMA tile kernel.  The headline workload is one launch of it per step, so its
     # mean duration is the event time per step; for multi-call workloads this is the aggregate rate.
@@ -336,7 +412,10 @@ def main():
                   else "%s TFLOP/s on workload %s on 1 MI355X" % ({"f32": "FP32", "f16": "FP16-storage / FP32-accumulate",
                                                                    "f64": "FP64"}[dtype], wl_name),
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_ev, "ms_per_step_host_clock": ms_wall, "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": ms_ev, "ms_per_step_median": spread["median"], "ms_per_step_min": spread["min"],
+        "ms_per_step_max": spread["max"], "ms_per_step_batches": batches, "events_per": timing["events_per"],
+        "value_at_median_step": flop / spread["median"] / 1e9,
+        "ms_per_step_host_clock": ms_wall, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": wl_name, "launches_per_step": launches, "flop_per_step": flop, "graph_replay": bool(args.graph),
                    "tile_config": dm.dmath_config_name(args.tile_config) if args.tile_config >= 0 else "auto",
@@ -349,10 +428,15 @@ def main():
             else 100.0 * tflops / (peak * measured_clock_ghz["mean"] / 2.4),
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "check_vs_oracle": check,
         "paper_context": "dMath paper, table 'Matrix Multiplication Performance': N=4096 on one K80 GPU with "
                          "cuBLAS 7.5 took 0.052 s (about 2.64 TFLOP/s, precision not stated); other hardware, "
                          "context only",
     }
+    if args.detail:
+        line["per_step_ms"] = [round(v, 5) for v in spans]
+        line["shader_clock_ghz_per_step_incl_warmup"] = (None if clock_per_step is None else
+                                                         [None if c is None else round(c, 4) for c in clock_per_step])
     if args.workload == "square":
         line["seconds_per_multiply"] = ms_ev / 1e3
         line["paper_table_one_gpu_seconds"] = PAPER_TABLE_ONE_GPU_SECONDS.get(args.size)  # None: did not fit one K80 GPU
