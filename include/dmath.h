@@ -80,6 +80,32 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB,
                         void *stream);
 
 /*
+ * dmath_gemm for callers that cannot allocate device memory or register a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, conventions,
+ * kernels and results as dmath_gemm, but the scratch of split plans (K slices of a product with few
+ * tiles, partial sums and counters of tail tiles) is an array of DMATH_NOALLOC_SCRATCH_BYTES that is
+ * part of the library's device image: every GPU the library runs on holds one copy until the process
+ * ends.  The call allocates nothing and frees nothing (no hipMalloc, no hipFree, no allocating library
+ * routine), ignores the workspace registered with dmath_set_workspace, and only enqueues kernels; the
+ * counters it needs at zero are cleared by a kernel on `stream`, not by a memset.
+ *
+ * A shape whose plan wants more scratch than that (dmath_gemm_workspace_bytes(...) >
+ * DMATH_NOALLOC_SCRATCH_BYTES, e.g. 6144^3) is refused with WORKSPACE (dmath_last_error_arg() == 0)
+ * before anything is launched, C untouched; it is not silently run on a slower plan.  All calls on one
+ * GPU share that GPU's array, which keeps the last call's contents: calls that overlap in time on one
+ * GPU (different streams, or different host threads) race and must be serialised by the caller.  The
+ * first call on a device looks the array's address up (hipGetSymbolAddress) and should be made outside
+ * stream capture; LAUNCH if that lookup fails.  Other errors as for dmath_gemm.
+ */
+#define DMATH_NOALLOC_SCRATCH_BYTES (32u << 20)
+dmath_status dmath_gemm_noalloc(dmath_op transA, dmath_op transB,
+                                int64_t M, int64_t N, int64_t K,
+                                float alpha, const float *A, int64_t lda,
+                                const float *B, int64_t ldb,
+                                float beta, float *C, int64_t ldc,
+                                void *stream);
+
+/*
  * The same multiply for matrices kept in half-precision storage (section "Precisions": IEEE 16-bit
  * half floats halve the bytes stored and moved, while the arithmetic stays single precision):
  *

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <cstdlib>
 
@@ -349,6 +350,28 @@ bool prepare_split(const Plan &p, int64_t tiles, int64_t M, int64_t N, void *ws,
 
 using namespace dmath;
 
+// Scratch of dmath_gemm_noalloc: split-K slices and tile counters live here instead of in a caller's
+// workspace.  Every device the library runs on holds its own copy of this array, at its own address,
+// until the process ends.  In host code the name is only a handle for hipGetSymbolAddress: kernels,
+// fills and copies are given the per-device address kept in g_scratch_ptr, never the name.
+static __device__ __align__(256) unsigned char scratch[DMATH_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Address of `scratch` on the current device, looked up once per device (threads that race here all
+// store the same value).  nullptr if the runtime cannot tell.
+static void *noalloc_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p != nullptr) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return nullptr;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
+}
+
 // Tile configuration and split-K factor of the FP16-input kernels for a shape (this thread's forced path
 // and split included).  Automatic: the 256 x 256 tile once it fills a good part of the device, else the
 // 128 x 128 tile; few tiles: K is cut so that the slices fill the compute units (plain split-K with FP32
@@ -379,9 +402,13 @@ int64_t hgemm_split_choice(int hidx, int64_t M, int64_t N, int64_t K, size_t ava
 
 // Body of dmath_gemm (T = float) and dmath_hgemm (T = _Float16: same kernels, operands widened on the
 // way into LDS, result rounded once on the way out).
+// ws / ws_bytes: the scratch split plans may use (the thread's registered workspace, or the library's
+// own array for dmath_gemm_noalloc).  strict: refuse (WORKSPACE) instead of falling back to a plan without
+// scratch when the plan this shape would get with unlimited scratch does not fit.
 template <class T>
 dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, float alpha, const T *A,
-                        int64_t lda, const T *B, int64_t ldb, float beta, T *C, int64_t ldc, void *stream_)
+                        int64_t lda, const T *B, int64_t ldb, float beta, T *C, int64_t ldc, void *stream_, void *ws,
+                        size_t ws_bytes, bool strict)
 {
     constexpr bool kHalf = !std::is_same<T, float>::value;
     constexpr uintptr_t kQuadAlign = 4 * sizeof(T) - 1;  // alignment of a 4-element vector access
@@ -428,7 +455,7 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
         if (fits && g_state.hgemm_path != 0 && g_state.force_cfg < 0) {
             const int64_t tiles_m = ceil_div(M, h.BM), tiles_n = ceil_div(N, h.BN), tiles = tiles_m * tiles_n;
             if (tiles * 64 > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
-            const int64_t s = hgemm_split_choice(hidx, M, N, K, g_state.ws ? g_state.ws_bytes : 0);
+            const int64_t s = hgemm_split_choice(hidx, M, N, K, ws ? ws_bytes : 0);
             HGemmArgs g;
             g.A = A;
             g.B = B;
@@ -448,7 +475,7 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
             if (aligned16(C) && ldc % 8 == 0) g.cvec = 2;  // 16-byte stores of whole row pieces are possible
             g.split.dp_tiles = s > 1 ? 0 : (int)tiles;
             g.split.splits = (int)s;
-            g.split.partials = s > 1 ? static_cast<float *>(g_state.ws) : nullptr;
+            g.split.partials = s > 1 ? static_cast<float *>(ws) : nullptr;
             g.split.counters = nullptr;
             g.split.plain = s > 1 ? 1 : 0;
             g.split.slice_stride = M * N;
@@ -469,17 +496,23 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
                 const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
                 if (v4)
                     hipLaunchKernelGGL(splitk_reduce_kernel_v4<_Float16>, dim3(blocks), dim3(256), 0, stream,
-                                       static_cast<const float *>(g_state.ws), (int)s, M * N, C, ldc, M, N, alpha, beta);
+                                       static_cast<const float *>(ws), (int)s, M * N, C, ldc, M, N, alpha, beta);
                 else
                     hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, stream,
-                                       static_cast<const float *>(g_state.ws), (int)s, M * N, C, ldc, M, N, alpha, beta);
+                                       static_cast<const float *>(ws), (int)s, M * N, C, ldc, M, N, alpha, beta);
                 if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
             }
             return DMATH_OK;
         }
     }
 
-    const Plan plan = resolve_plan(M, N, K, g_state.ws ? g_state.ws_bytes : 0, false);
+    if (strict) {
+        const Plan want = resolve_plan(M, N, K, 0, true);
+        const CfgDesc &wd = desc(want.cfg);
+        if (plan_bytes(want, ceil_div(M, wd.BM) * ceil_div(N, wd.BN), M, N) > (ws ? ws_bytes : 0))
+            return fail(DMATH_ERR_WORKSPACE, 0);
+    }
+    const Plan plan = resolve_plan(M, N, K, ws ? ws_bytes : 0, false);
     const CfgDesc &d = desc(plan.cfg);
     const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
     if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
@@ -506,7 +539,7 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     g.tiles_n = (int)tiles_n;
     g.clock_probe = g_state.clock_probe;
     g.cvec = (quad_aligned(C) && ldc % 4 == 0) ? 1 : 0;
-    if (!prepare_split(plan, tiles_m * tiles_n, M, N, g_state.ws, stream, g.split)) return fail(DMATH_ERR_LAUNCH, 0);
+    if (!prepare_split(plan, tiles_m * tiles_n, M, N, ws, stream, g.split)) return fail(DMATH_ERR_LAUNCH, 0);
     g.stagger_ticks = stagger_ticks(d, tiles_m * tiles_n, plan.splits);
     int rc;
     if constexpr (kHalf)
@@ -521,10 +554,10 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
         const int blocks = (int)(ceil_div(items, 256) < 8192 ? ceil_div(items, 256) : 8192);
         if (v4)
             hipLaunchKernelGGL(splitk_reduce_kernel_v4<T>, dim3(blocks), dim3(256), 0, stream,
-                               static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
+                               static_cast<const float *>(ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
         else
             hipLaunchKernelGGL(splitk_reduce_kernel<T>, dim3(blocks), dim3(256), 0, stream,
-                               static_cast<const float *>(g_state.ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
+                               static_cast<const float *>(ws), plan.splits, M * N, C, ldc, M, N, alpha, beta);
         if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
     }
     return DMATH_OK;
@@ -667,7 +700,18 @@ dmath_status dmath_gemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
                         const float *A, int64_t lda, const float *B, int64_t ldb, float beta, float *C,
                         int64_t ldc, void *stream_)
 {
-    return gemm_entry<float>(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream_);
+    return gemm_entry<float>(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream_, g_state.ws,
+                             g_state.ws_bytes, false);
+}
+
+dmath_status dmath_gemm_noalloc(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, float alpha,
+                                const float *A, int64_t lda, const float *B, int64_t ldb, float beta, float *C,
+                                int64_t ldc, void *stream_)
+{
+    void *ptr = noalloc_scratch();
+    if (ptr == nullptr) return fail(DMATH_ERR_LAUNCH, 0);
+    return gemm_entry<float>(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream_, ptr,
+                             (size_t)DMATH_NOALLOC_SCRATCH_BYTES, true);
 }
 
 dmath_status dmath_hgemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, float alpha,
@@ -676,7 +720,7 @@ dmath_status dmath_hgemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N,
 {
     return gemm_entry<_Float16>(transA, transB, M, N, K, alpha, reinterpret_cast<const _Float16 *>(A), lda,
                                 reinterpret_cast<const _Float16 *>(B), ldb, beta, reinterpret_cast<_Float16 *>(C), ldc,
-                                stream_);
+                                stream_, g_state.ws, g_state.ws_bytes, false);
 }
 
 dmath_status dmath_dgemm(dmath_op transA, dmath_op transB, int64_t M, int64_t N, int64_t K, double alpha,

@@ -15,7 +15,7 @@ OK, ERR_INVALID_ARG, ERR_NULL_PTR, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_WORKSPACE = 
 OP_N, OP_T = 0, 1
 
 EXPORTS = (
-    "dmath_gemm", "dmath_conv2d_fwd", "dmath_conv2d_bwd_data", "dmath_conv2d_bwd_filter", "dmath_gemm_panels", "dmath_hgemm", "dmath_set_hgemm_path", "dmath_hgemm_workspace_bytes", "dmath_dgemm", "dmath_set_dgemm_config", "dmath_dgemm_workspace_bytes", "dmath_gemm_workspace_bytes", "dmath_set_workspace",
+    "dmath_gemm", "dmath_gemm_noalloc", "dmath_conv2d_fwd", "dmath_conv2d_bwd_data", "dmath_conv2d_bwd_filter", "dmath_gemm_panels", "dmath_hgemm", "dmath_set_hgemm_path", "dmath_hgemm_workspace_bytes", "dmath_dgemm", "dmath_set_dgemm_config", "dmath_dgemm_workspace_bytes", "dmath_gemm_workspace_bytes", "dmath_set_workspace",
     "dmath_set_override", "dmath_set_clock_probe", "dmath_gemm_plan", "dmath_num_configs", "dmath_config_name", "dmath_last_error_arg",
     "dmath_status_string", "dmath_version",
 )
@@ -30,6 +30,8 @@ _i64, _f32, _vp, _int = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.
 
 _lib.dmath_gemm.restype = _int
 _lib.dmath_gemm.argtypes = [_int, _int, _i64, _i64, _i64, _f32, _vp, _i64, _vp, _i64, _f32, _vp, _i64, _vp]
+_lib.dmath_gemm_noalloc.restype = _int
+_lib.dmath_gemm_noalloc.argtypes = list(_lib.dmath_gemm.argtypes)
 _lib.dmath_conv2d_fwd.restype = _int
 _lib.dmath_conv2d_fwd.argtypes = [_i64] * 11 + [_f32, _vp, _vp, _f32, _vp, _vp]
 _lib.dmath_conv2d_bwd_data.restype = _int
@@ -91,6 +93,14 @@ def _stream(stream):
 def dmath_gemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=None):
     return _lib.dmath_gemm(transA, transB, M, N, K, alpha, _addr(A), lda, _addr(B), ldb, beta, _addr(C), ldc,
                            _stream(stream))
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20   # DMATH_NOALLOC_SCRATCH_BYTES of include/dmath.h
+
+
+def dmath_gemm_noalloc(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=None):
+    return _lib.dmath_gemm_noalloc(transA, transB, M, N, K, alpha, _addr(A), lda, _addr(B), ldb, beta, _addr(C), ldc,
+                                   _stream(stream))
 
 
 def dmath_conv2d_fwd(N, C, H, W, Kout, R, S, pad_h, pad_w, stride_h, stride_w, alpha, x, w, beta, y,
