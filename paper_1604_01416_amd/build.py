@@ -50,7 +50,8 @@ def build(force: bool = True, jobs: int = 8, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     work = [(os.path.join(CSRC, "dmath_api.hip"), os.path.join(OBJ, "dmath_api.o"), []),
             (os.path.join(CSRC, "hgemm_instance.hip"), os.path.join(OBJ, "hgemm_instance.o"), []),
-            (os.path.join(CSRC, "dgemm_instance.hip"), os.path.join(OBJ, "dgemm_instance.o"), [])]
+            (os.path.join(CSRC, "dgemm_instance.hip"), os.path.join(OBJ, "dgemm_instance.o"), []),
+            (os.path.join(CSRC, "wavek_instance.hip"), os.path.join(OBJ, "wavek_instance.o"), [])]
     for i in range(num_configs()):
         work.append((os.path.join(CSRC, "tile_instance.hip"), os.path.join(OBJ, "tile_%d.o" % i),
                      ["-DDMATH_CFG_INDEX=%d" % i]))

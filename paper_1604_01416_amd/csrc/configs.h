@@ -40,4 +40,14 @@ template <> const CfgDesc &cfg_desc<3>();
 template <> const CfgDesc &cfg_desc<4>();
 template <> const CfgDesc &cfg_desc<5>();
 
+
+// Wave-split kernels for products with few tiles and a long K (gemm_wavek_kernel.h), compiled in
+// wavek_instance.hip.  For dmath_set_override they are the configurations kNumCfg, kNumCfg + 1, ...
+constexpr int kNumWaveK = 1;
+struct WaveKDesc {
+    const char *name;
+    int (*gemm)(const GemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);
+};
+const WaveKDesc &wavek_desc(int i);
+
 }  // namespace dmath

@@ -307,10 +307,11 @@ unsigned stagger_ticks(const CfgDesc &d, int64_t tiles, int splits)
 Plan resolve_plan(int64_t M, int64_t N, int64_t K, size_t avail, bool measure_only)
 {
     const ThreadState &st = g_state;
-    Plan p = choose_plan(M, N, K, true, st.force_cfg, st.force_split, measure_only ? ~(size_t)0 : avail);
+    const int only = st.force_cfg < kNumCfg ? st.force_cfg : -1;  // a forced wave-split kernel only concerns dmath_gemm
+    Plan p = choose_plan(M, N, K, true, only, st.force_split, measure_only ? ~(size_t)0 : avail);
     const CfgDesc &d = desc(p.cfg);
     if (!measure_only && plan_bytes(p, ceil_div(M, d.BM) * ceil_div(N, d.BN), M, N) > avail)
-        p = choose_plan(M, N, K, false, st.force_cfg, -1);  // no room: best plan that needs no scratch
+        p = choose_plan(M, N, K, false, only, -1);  // no room: best plan that needs no scratch
     return p;
 }
 
@@ -398,6 +399,19 @@ int64_t hgemm_split_choice(int hidx, int64_t M, int64_t N, int64_t K, size_t ava
     const size_t slice_bytes = (size_t)M * (size_t)N * sizeof(float);
     if (s > 1 && (size_t)s * slice_bytes > avail) s = (int64_t)(avail / slice_bytes);
     return s < 2 ? 1 : s;
+}
+
+// Wave-split kernel (gemm_wavek_kernel.h) for this FP32 product, or -1.  Forced: configuration index
+// kNumCfg + v of dmath_set_override.  Automatic: the 64 x 64 tiles fill more than half of the compute
+// units but no more than one round of them, and K is long enough to give 8 waves a pipeline each; such a
+// product used to be cut into K slices across workgroups, with the slices written to and re-read from a
+// workspace by a second kernel.
+int wavek_choice(int64_t M, int64_t N, int64_t K)
+{
+    if (g_state.force_cfg >= kNumCfg) return g_state.force_cfg - kNumCfg;
+    if (g_state.force_cfg >= 0 || g_state.force_split >= 1) return -1;
+    const int64_t tiles = ceil_div(M, 64) * ceil_div(N, 64);
+    return (tiles > kNumCU / 2 && tiles <= kNumCU && K >= 1024) ? 0 : -1;
 }
 
 // Body of dmath_gemm (T = float) and dmath_hgemm (T = _Float16: same kernels, operands widened on the
@@ -506,6 +520,36 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
         }
     }
 
+    if constexpr (!kHalf) {
+        const int wk = wavek_choice(M, N, K);
+        if (wk >= 0) {
+            const int64_t tiles_m = ceil_div(M, 64), tiles_n = ceil_div(N, 64);
+            if (tiles_m * tiles_n > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
+            bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
+            if (!a_k && M % 4 != 0) vec = false;
+            if (!b_k && N % 4 != 0) vec = false;
+            GemmArgs g;
+            g.A = A;
+            g.B = B;
+            g.C = C;
+            g.lda = lda;
+            g.ldb = ldb;
+            g.ldc = ldc;
+            g.M = M;
+            g.N = N;
+            g.K = K;
+            g.alpha = alpha;
+            g.beta = beta;
+            g.tiles_m = (int)tiles_m;
+            g.tiles_n = (int)tiles_n;
+            g.clock_probe = g_state.clock_probe;
+            g.cvec = (aligned16(C) && ldc % 4 == 0) ? 1 : 0;
+            g.split = SplitPlan{(int)(tiles_m * tiles_n), 1, nullptr, nullptr, 0, 0};
+            g.stagger_ticks = 0;
+            if (wavek_desc(wk).gemm(g, a_k, b_k, vec, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
+            return DMATH_OK;
+        }
+    }
     if (strict) {
         const Plan want = resolve_plan(M, N, K, 0, true);
         const CfgDesc &wd = desc(want.cfg);
@@ -606,13 +650,17 @@ const char *dmath_status_string(dmath_status s)
 
 int dmath_last_error_arg(void) { return g_state.last_error_arg; }
 
-int dmath_num_configs(void) { return kNumCfg; }
+int dmath_num_configs(void) { return kNumCfg + kNumWaveK; }
 
-const char *dmath_config_name(int i) { return (i >= 0 && i < kNumCfg) ? desc(i).name : nullptr; }
+const char *dmath_config_name(int i)
+{
+    if (i >= kNumCfg && i < kNumCfg + kNumWaveK) return wavek_desc(i - kNumCfg).name;
+    return (i >= 0 && i < kNumCfg) ? desc(i).name : nullptr;
+}
 
 dmath_status dmath_set_override(int tile_config, int split_k)
 {
-    if (tile_config >= kNumCfg) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (tile_config >= kNumCfg + kNumWaveK) return fail(DMATH_ERR_INVALID_ARG, 1);
     if (split_k == 0 || split_k > 64) return fail(DMATH_ERR_INVALID_ARG, 2);
     g_state.force_cfg = tile_config < 0 ? -1 : tile_config;
     g_state.force_split = split_k < 0 ? -1 : split_k;
@@ -656,6 +704,7 @@ size_t dmath_gemm_workspace_bytes(dmath_op transA, dmath_op transB, int64_t M, i
     (void)transA;
     (void)transB;
     if (M <= 0 || N <= 0 || K <= 0) return 0;
+    if (wavek_choice(M, N, K) >= 0) return 0;  // K is split inside the workgroups: no scratch
     const Plan p = resolve_plan(M, N, K, 0, true);
     const CfgDesc &d = desc(p.cfg);
     return plan_bytes(p, ceil_div(M, d.BM) * ceil_div(N, d.BN), M, N);
@@ -690,7 +739,8 @@ dmath_status dmath_gemm_plan(dmath_op transA, dmath_op transB, int64_t M, int64_
     if (M < 0) return fail(DMATH_ERR_INVALID_ARG, 3);
     if (N < 0) return fail(DMATH_ERR_INVALID_ARG, 4);
     if (K < 0) return fail(DMATH_ERR_INVALID_ARG, 5);
-    const Plan p = (M == 0 || N == 0 || K == 0) ? Plan{-1, 0, 1} : resolve_plan(M, N, K, g_state.ws ? g_state.ws_bytes : 0, false);
+    Plan p = (M == 0 || N == 0 || K == 0) ? Plan{-1, 0, 1} : resolve_plan(M, N, K, g_state.ws ? g_state.ws_bytes : 0, false);
+    if (p.cfg >= 0 && wavek_choice(M, N, K) >= 0) p = Plan{kNumCfg + wavek_choice(M, N, K), 0, 1};
     if (tile_config) *tile_config = p.cfg;
     if (split_k) *split_k = p.splits;
     return DMATH_OK;
@@ -968,7 +1018,7 @@ static dmath_status run_conv(bool bwd_data, int64_t N, int64_t C, int64_t H, int
     const size_t split_off = copy_filters ? wt_bytes : 0;
     Plan plan = resolve_plan(rows, cols, KK, ws_total - split_off, false);
     if (plan.splits > 1 && plan.dp_tiles == 0)  // the convolution has no plain split-K path: tail splits only
-        plan = choose_plan(rows, cols, KK, false, g_state.force_cfg, -1);
+        plan = choose_plan(rows, cols, KK, false, g_state.force_cfg < kNumCfg ? g_state.force_cfg : -1, -1);
     const CfgDesc &d = desc(plan.cfg);
     const int64_t tiles_m = ceil_div(rows, d.BM), tiles_n = ceil_div(cols, d.BN);
     if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 1);

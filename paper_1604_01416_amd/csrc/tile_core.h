@@ -72,8 +72,9 @@ constexpr int kNumCU = 256;  // MI355X: compute units
 constexpr int kNumXcd = 8;  // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 
 // Tile configuration.  WM = BM / WAVES_M and WN = BN / WAVES_N are the wave tile.
-// LKV selects the LDS image: 2 = rotated rows, no padding (the product layout); 0 = plain rows padded
-// by 4 floats with 4-byte transposing stores (kept as a comparison point for the counters).
+// LKV selects the LDS image: 0 = plain rows padded by 4 floats with 4-byte transposing stores (the faster
+// one, used by every product configuration); 2 = rotated rows, no padding, free of bank conflicts (kept
+// as the comparison point for the counters).
 template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int MIN_WAVES_PER_SIMD_, int LKV_ = 2>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_;
@@ -223,7 +224,9 @@ struct LoaderK {
 
 // Comparison variant for the unrotated, padded image (LD = BR + 4): 4 consecutive lanes per row,
 // 4-byte transposing stores (two-way bank conflicts on every store).
-template <int BR, int BK, int NT, int LD, bool VEC, class T = float>
+// KADV: K tiles between two consecutive tiles of this loader (1, or the number of waves that share a
+// K range tile by tile in the wave-split kernel).
+template <int BR, int BK, int NT, int LD, bool VEC, class T = float, int KADV = 1>
 struct LoaderK0 {
     static constexpr int QPR = BK / 4;
     static constexpr int NQ = (BR * QPR) / NT;
@@ -263,7 +266,7 @@ struct LoaderK0 {
     }
     // byte distance of k elements along K from a tile origin
     static __device__ __forceinline__ int64_t k_bytes(int64_t k, int64_t) { return k * ES; }
-    __device__ __forceinline__ void advance() { tile += BK * ES; }
+    __device__ __forceinline__ void advance() { tile += KADV * BK * ES; }
     template <int I>
     __device__ __forceinline__ void store_piece(float *S) const
     {
@@ -294,7 +297,7 @@ struct LoaderKSel<0, BR, BK, NT, LD, ROT, VEC, T> {
 // Used for A when transA == T and for B when transB == N.  Quads run along r; NT is a multiple of
 // the quads per k row, so a thread keeps one r quad and walks k.  16-byte global loads, 16-byte LDS
 // stores; the lanes served together write one contiguous (rotated) run of an image row.
-template <int BR, int BK, int NT, int LD, int ROT, bool VEC, class T = float>
+template <int BR, int BK, int NT, int LD, int ROT, bool VEC, class T = float, int KADV = 1>
 struct LoaderMN {
     static constexpr int QPR = BR / 4;
     static constexpr int NQ = (BK * QPR) / NT;
@@ -315,7 +318,7 @@ struct LoaderMN {
         krow = tid / QPR;
         const int rq = tid % QPR;
         tile = reinterpret_cast<const char *>(base + k0 * ld + r0);
-        tstride = (int64_t)BK * ld * ES;
+        tstride = (int64_t)KADV * BK * ld * ES;
         int64_t quad = rq * 4;  // VEC: R is a multiple of 4, a quad is wholly inside or wholly outside
         if (VEC) quad = r0 + quad + 4 <= R ? quad : R - 4 - r0;
 #pragma unroll
@@ -448,7 +451,16 @@ __device__ __forceinline__ void mma_groups_from(Frag<Cfg> &cur, const float *As,
 // already running: each MFMA is followed by at most a few of them, in a fixed order pinned with
 // scheduling barriers: first the fragment reads of the next k group, then the LDS stores of the
 // staged tile, then the global loads of the tile after it.
-template <class Cfg, int CS, class RL, class CL>
+// What separates the K tiles of a pipeline.  A workgroup that shares its LDS stages needs a barrier; a
+// pipeline owned by a single wave needs none: the LDS executes one wave's accesses in program order.
+struct BlockSync {
+    static __device__ __forceinline__ void sync() { __syncthreads(); }
+};
+struct WaveSync {
+    static __device__ __forceinline__ void sync() { __builtin_amdgcn_wave_barrier(); }
+};
+
+template <class Cfg, int CS, class Sync, class RL, class CL>
 __device__ __forceinline__ void steady_iter(RL &rl, CL &cl, Frag<Cfg> &cur, floatx16 (&acc)[Cfg::MB][Cfg::NB],
                                             float *smem, const int (&a_off)[Cfg::KGROUPS],
                                             const int (&b_off)[Cfg::KGROUPS])
@@ -502,7 +514,7 @@ __device__ __forceinline__ void steady_iter(RL &rl, CL &cl, Frag<Cfg> &cur, floa
         });
         cur = nxt;
     });
-    __syncthreads();
+    Sync::sync();
 }
 
 // Software pipeline over the K range of one tile.  T full K tiles, then an optional partial one of
@@ -512,14 +524,16 @@ __device__ __forceinline__ void steady_iter(RL &rl, CL &cl, Frag<Cfg> &cur, floa
 // t+1 is already visible while tile t is computed, which is what allows the fragment prefetch across
 // the barrier and the branch-free steady state (steady_iter, unrolled over the stage ring); the first
 // and last tiles, and 2-stage configurations, go through the generic loop with its conditions.
-template <class Cfg, class RowLoader, class ColLoader>
+// tid: index of the thread among the Cfg::NT threads that run this pipeline (the workgroup's threads, or
+// one wave's lanes when every wave of the workgroup runs a pipeline of its own on a part of K).
+template <class Cfg, class RowLoader, class ColLoader, class Sync = BlockSync>
 __device__ __forceinline__ void mainloop(RowLoader &rl, ColLoader &cl, int T, int krem,
-                                         floatx16 (&acc)[Cfg::MB][Cfg::NB], float *smem)
+                                         floatx16 (&acc)[Cfg::MB][Cfg::NB], float *smem, int tid = threadIdx.x)
 {
     constexpr int S = Cfg::STAGES;
     constexpr bool kAhead = S >= 3;
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
     const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM;
     const int wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
     const int i = lane & 31, h = lane >> 5;
@@ -543,7 +557,7 @@ __device__ __forceinline__ void mainloop(RowLoader &rl, ColLoader &cl, int T, in
         load_tile(rl);
         load_tile(cl);
     }
-    __syncthreads();
+    Sync::sync();
 
     Frag<Cfg> cur;
     if (T > 0) load_frag<Cfg, 0>(cur, smem, smem + Cfg::A_FLOATS, a_off, b_off);
@@ -551,7 +565,7 @@ __device__ __forceinline__ void mainloop(RowLoader &rl, ColLoader &cl, int T, in
     if constexpr (kAhead) {
         // S iterations at a time keep the stage of tile t equal to 0 at the top of the loop
         while (t + 2 * S - 1 < T) {
-            static_for<S>([&](auto sc) { steady_iter<Cfg, decltype(sc)::value>(rl, cl, cur, acc, smem, a_off, b_off); });
+            static_for<S>([&](auto sc) { steady_iter<Cfg, decltype(sc)::value, Sync>(rl, cl, cur, acc, smem, a_off, b_off); });
             t += S;
         }
     }
@@ -574,7 +588,7 @@ __device__ __forceinline__ void mainloop(RowLoader &rl, ColLoader &cl, int T, in
                                 a_off, b_off);
         cs = ns;
         fill = (fill + 1 == S) ? 0 : fill + 1;
-        __syncthreads();
+        Sync::sync();
         if (!kAhead && more) load_frag<Cfg, 0>(cur, An, An + Cfg::A_FLOATS, a_off, b_off);
     }
     if (krem > 0) {
@@ -582,7 +596,7 @@ __device__ __forceinline__ void mainloop(RowLoader &rl, ColLoader &cl, int T, in
         cl.load_tail(krem);
         store_tile(rl, smem);
         store_tile(cl, smem + Cfg::A_FLOATS);
-        __syncthreads();
+        Sync::sync();
         load_frag<Cfg, 0>(cur, smem, smem + Cfg::A_FLOATS, a_off, b_off);
         mma_groups_from<Cfg, 0>(cur, smem, smem + Cfg::A_FLOATS, nullptr, nullptr, acc, a_off, b_off);
     }

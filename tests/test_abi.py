@@ -103,8 +103,9 @@ def test_workspace_and_override_api(dm):
     assert dm.dmath_gemm_workspace_bytes(0, 0, 0, 4, 4) == 0
     big = dm.dmath_gemm_workspace_bytes(0, 0, 4096, 4096, 4096)
     assert big == 0                                                  # enough tiles: no split-K
-    skinny = dm.dmath_gemm_workspace_bytes(0, 0, 256, 4096, 4096)
-    assert skinny >= 2 * 256 * 4096 * 4                              # at least two slices of the output
+    assert dm.dmath_gemm_workspace_bytes(0, 0, 256, 4096, 4096) == 0 # K is split inside the workgroups
+    skinny = dm.dmath_gemm_workspace_bytes(0, 0, 128, 2048, 4096)    # too few tiles for that: slices
+    assert skinny >= 2 * 128 * 2048 * 4                              # at least two slices of the output
     assert dm.dmath_set_override(dm.dmath_num_configs(), 1) == dm.ERR_INVALID_ARG
     assert dm.dmath_set_override(0, 0) == dm.ERR_INVALID_ARG
     assert dm.dmath_set_override(0, 4) == dm.OK

@@ -83,7 +83,7 @@ def test_gemm_small_auto(dm, torch, tA, tB, M, N, K):
                   seed=M * 3 + K)
 
 
-@pytest.mark.parametrize("cfg", range(6))
+@pytest.mark.parametrize("cfg", range(7))
 @pytest.mark.parametrize("tA,tB", TRANS)
 def test_gemm_every_config_aligned_and_unaligned(dm, torch, cfg, tA, tB):
     if cfg >= dm.dmath_num_configs():
@@ -109,6 +109,46 @@ def test_gemm_split_k(dm, torch, cfg, split, tA, tB):
     run_gemm_case(dm, torch, tA, tB, 67, 93, 515, alpha=1.0, beta=0.0, ld_extra=(1, 1, 1), lead=(1, 1, 1),
                   seed=split + 1, c_nan=True)
     run_gemm_case(dm, torch, tA, tB, 64, 128, 512, alpha=1.0, beta=1.0, seed=split + 2, ints=True, exact=True)
+
+
+WAVE_SPLIT = [6]   # configuration indices of the kernels that split K over the waves of a workgroup
+
+
+@pytest.mark.parametrize("cfg", WAVE_SPLIT)
+@pytest.mark.parametrize("tA,tB", TRANS)
+def test_gemm_wave_split_k_ranges(dm, torch, cfg, tA, tB):
+    """K from less than one K tile (most waves get nothing) through every remainder class of the round
+    robin over 8 waves: the partial last tile must land on the wave whose turn it is."""
+    assert "wavek" in dm.dmath_config_name(cfg)
+    dm.dmath_set_override(cfg, -1)
+    for K in (4, 8, 12, 60, 64, 68, 72, 124, 128, 132, 136, 200, 516, 1032):      # 16-byte loads
+        run_gemm_case(dm, torch, tA, tB, 72, 132, K, alpha=1.25, beta=0.5, ld_extra=(4, 0, 4), seed=K)
+    for K in (1, 7, 9, 63, 65, 127, 129, 135, 137, 515, 1031):                     # element loads
+        run_gemm_case(dm, torch, tA, tB, 70, 131, K, alpha=1.0, beta=0.0, ld_extra=(1, 2, 3), lead=(1, 2, 3),
+                      seed=K, c_nan=True)
+    run_gemm_case(dm, torch, tA, tB, 130, 200, 1096, alpha=1.0, beta=1.0, seed=3, ints=True, exact=True)
+
+
+def test_gemm_wave_split_is_the_plan_for_skinny_products_and_repeats_its_bits(dm, torch):
+    """The fully connected layer's forward and backward-data products get the wave-split kernel by
+    themselves (no workspace needed), integer entries come out exact at that launch shape, and two runs
+    give the same bits."""
+    for tA, tB in ((0, 0), (0, 1)):
+        st, cfg, split = dm.dmath_gemm_plan(tA, tB, 256, 4096, 4096)
+        assert st == dm.OK and cfg in WAVE_SPLIT and split == 1, (cfg, split)
+        assert dm.dmath_gemm_workspace_bytes(tA, tB, 256, 4096, 4096) == 0
+        run_gemm_case(dm, torch, tA, tB, 256, 4096, 4096, alpha=1.0, beta=1.0, seed=50 + tB, ints=True, exact=True)
+    rng = np.random.default_rng(52)
+    A = rng.uniform(-1, 1, (256, 4096)).astype(np.float32)
+    B = rng.uniform(-1, 1, (4096, 4096)).astype(np.float32)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    outs = []
+    for _ in range(3):
+        dC = torch.empty((256, 4096), device="cuda")
+        dm.check(dm.dmath_gemm(0, 0, 256, 4096, 4096, 1.0, dA, 4096, dB, 4096, 0.0, dC, 4096))
+        torch.cuda.synchronize()
+        outs.append(dC.cpu().numpy())
+    assert all(np.array_equal(outs[0].view(np.uint32), o.view(np.uint32)) for o in outs[1:])
 
 
 @pytest.mark.parametrize("tA,tB", [(0, 0), (1, 1)])
