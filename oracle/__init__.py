@@ -29,7 +29,8 @@ _hp = ctypes.POINTER(ctypes.c_uint16)
 def _load():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # DMATH_ORACLE_SANITIZE=1: the ASan + UBSan build (the process must preload the sanitizer runtime)
+        path = _build.build(force=False, sanitize=os.environ.get("DMATH_ORACLE_SANITIZE") == "1")
         lib = ctypes.CDLL(path)
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_gemm.restype = ctypes.c_int

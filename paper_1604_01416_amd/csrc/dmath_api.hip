@@ -402,16 +402,19 @@ int64_t hgemm_split_choice(int hidx, int64_t M, int64_t N, int64_t K, size_t ava
 }
 
 // Wave-split kernel (gemm_wavek_kernel.h) for this FP32 product, or -1.  Forced: configuration index
-// kNumCfg + v of dmath_set_override.  Automatic: the 64 x 64 tiles fill more than half of the compute
-// units but no more than one round of them, and K is long enough to give 8 waves a pipeline each; such a
-// product used to be cut into K slices across workgroups, with the slices written to and re-read from a
-// workspace by a second kernel.
+// kNumCfg + v of dmath_set_override.  Automatic: one workgroup of 8 waves per compute unit and 64 x 64 tile,
+// so it pays when the 64 x 64 tiles fill whole rounds over the 256 compute units well (measured on
+// MI355X against the best tile configuration with its automatic split: 256 tiles 0.78-0.91 of its time
+// for K from 512 to 8192, 512 and 768 tiles 0.93-0.94, 1024 tiles equal; 192 of 256 equal, 320 and 384 of
+// 512 slower).  Such products used to be cut into K slices across workgroups, with the slices written
+// to and re-read from a workspace by a second kernel.
 int wavek_choice(int64_t M, int64_t N, int64_t K)
 {
     if (g_state.force_cfg >= kNumCfg) return g_state.force_cfg - kNumCfg;
     if (g_state.force_cfg >= 0 || g_state.force_split >= 1) return -1;
     const int64_t tiles = ceil_div(M, 64) * ceil_div(N, 64);
-    return (tiles > kNumCU / 2 && tiles <= kNumCU && K >= 1024) ? 0 : -1;
+    const int64_t rounds = ceil_div(tiles, kNumCU);
+    return (rounds <= 3 && tiles * 8 >= rounds * kNumCU * 7 && K >= 512) ? 0 : -1;
 }
 
 // Body of dmath_gemm (T = float) and dmath_hgemm (T = _Float16: same kernels, operands widened on the

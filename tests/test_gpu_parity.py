@@ -298,9 +298,16 @@ def test_config3_summa_chain(dm, torch):
     ref, mag = oracle.gemm_points(0, 0, m, m, kp * steps, 1.0, Acat, kp * steps, Bcat, m, 1.0, wl.arrays["C"], m,
                                   pi, pj)
     r = check_bound(out["C"][pi, pj], ref, mag, kp * steps, "config 3 chain")
-    # tighter, informative form: per-step rounding of a K=512 product plus 16 roundings of C
+    # The per-step form of the same bound, 16 times tighter: every call rounds a K = 512 product
+    # (4*512*2^-24 of its magnitude sum) and rounds C once when it stores it (2^-24 of a value that never
+    # exceeds |C0| + sum_k |A_k||B_k|).  A dropped k term (about 0.3 here) or a beta applied twice fails it.
     err = np.abs(out["C"][pi, pj].astype(np.float64) - ref)
-    print("config 3 max err/bound %.3g, max abs err %.3g" % (r, err.max()))
+    c0 = np.abs(wl.arrays["C"][pi, pj].astype(np.float64))
+    mag_ab = mag - c0
+    per_step = 4.0 * kp * 2.0 ** -24 * mag_ab + steps * 2.0 ** -24 * (c0 + mag_ab) + 1e-6
+    assert (err <= per_step).all(), "config 3 chain outside the per-step bound: %g" % (err / per_step).max()
+    print("config 3 max err/contract bound %.3g, max err/per-step bound %.3g, max abs err %.3g"
+          % (r, (err / per_step).max(), err.max()))
 
 
 def test_config4_fc_layer(dm, torch):
