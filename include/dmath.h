@@ -6,12 +6,16 @@
  * has every worker issue, per stage, one asynchronous dense multiply on blocks
  * it holds, accumulating into its block of C; its DNN pipeline adds forward
  * convolutions that run data-parallel with no communication (abstract, section
- * "Introduction").  This library is that per-GPU work and nothing else: FP32
- * in, FP32 accumulate (MFMA), FP32 out, on one gfx950 device.
+ * "Introduction").  This library is that per-GPU work and nothing else, on one
+ * gfx950 device, in the three storage precisions of section "Precisions": FP32
+ * (dmath_gemm, dmath_gemm_panels, the convolutions: FP32 in, FP32 MFMA accumulate,
+ * FP32 out), IEEE half storage with FP32 arithmetic (dmath_hgemm) and FP64
+ * (dmath_dgemm).
  *
  * General rules for every entry point
- *   - All matrix / tensor pointers are DEVICE pointers to FP32 data owned by the
- *     caller; scalars are passed by value from the host.
+ *   - All matrix / tensor pointers are DEVICE pointers owned by the caller, to
+ *     FP32 data unless the entry point says otherwise (binary16 bit patterns for
+ *     dmath_hgemm, FP64 for dmath_dgemm); scalars are passed by value from the host.
  *   - `stream` is a hipStream_t passed as void*; NULL means the default stream.
  *     Calls enqueue work on that stream and return without synchronising.
  *   - The library allocates no device memory.  Kernels that need scratch use the
@@ -62,7 +66,10 @@ typedef enum { DMATH_OP_N = 0, DMATH_OP_T = 1 } dmath_op;
  * with ldc >= max(1,N).  Leading dimensions let a block be a window of a larger
  * row panel.  Any 4-byte aligned pointer and any legal leading dimension work;
  * 16-byte aligned pointers with leading dimensions that are multiples of 4 take
- * the fast path.
+ * the fast path.  lda or ldb above 2^22 elements (a window of a row panel more than
+ * 4 Mi elements wide) is served by kernels with 64-bit offsets on one tile
+ * configuration (128 x 128; a configuration forced with dmath_set_override is
+ * ignored for such a call), not by the shape-tuned ones.
  *
  * M == 0 or N == 0: nothing happens.  K == 0 or alpha == 0: C = beta*C and A, B
  * are not read (they may be NULL).  beta == 0: C is write-only, its old contents
@@ -208,7 +215,12 @@ dmath_status dmath_gemm_panels(dmath_op transA, dmath_op transB,
  * matrix is never stored.  When a workspace of at least Kout*C*R*S*4 bytes is
  * registered (dmath_set_workspace), C is a multiple of 16 and R*S <= 32, the
  * filters are first copied into it in tap-major order, which makes the
- * generated operand cheaper to address; otherwise no workspace is touched.
+ * generated operand cheaper to address.  When the output tiles do not fill whole
+ * rounds over the compute units, the tiles of the last, partial round are cut into
+ * K slices whose partial sums and counters also live in the workspace (after the
+ * filter copy); with no workspace, or one too small, the call runs without either.
+ * A split-K factor forced with dmath_set_override does not apply to the forward
+ * and backward-data convolutions (only such tail tiles are ever split there).
  *
  * Empty outputs (N, Kout, P or Q zero) are a no-op; C == 0 or alpha == 0 gives
  * y = beta*y without reading x or w; beta == 0 makes y write-only.

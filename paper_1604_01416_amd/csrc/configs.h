@@ -20,13 +20,14 @@ template <> struct CfgAt<4> { typedef TileCfg<64, 64, 16, 2, 2, 3, 2, 0> type; }
 // Same tile as 2 with the rotated, bank-conflict-free LDS image: the comparison point for the counters.
 template <> struct CfgAt<5> { typedef TileCfg<256, 256, 16, 4, 2, 3, 2, 2> type; };
 constexpr int kNumCfg = 6;
+constexpr int kWideCfg = 3;   // the configuration that also has kernels with 64-bit per-thread offsets
 
 struct CfgDesc {
     const char *name;
     int BM, BN, BK, NT, lds_bytes;
-    int (*gemm)(const GemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);
+    int (*gemm)(const GemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, bool wide, hipStream_t);
     int (*conv)(const ConvArgs &, bool vec, int loader_kind, hipStream_t);
-    int (*hgemm)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t);  // fails on the rotated-image entry
+    int (*hgemm)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, bool vec, bool wide, hipStream_t);  // fails on the rotated-image entry
     int (*gemm_panels)(const GemmPanelArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);
     int (*conv_bwd_filter)(const ConvFilterGradArgs &, bool quad_in_image, bool quad_in_row, hipStream_t);  // fails on the rotated-image entry
 };

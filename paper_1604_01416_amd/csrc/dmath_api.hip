@@ -20,11 +20,11 @@ struct ThreadState {
     size_t ws_bytes = 0;
     int force_cfg = -1;
     int force_split = -1;
-    int hgemm_path = -1;
+    int hgemm_path = -1;        // -1 automatic, 0 FP32 matrix instruction on widened operands, 1.. a tile of the FP16-input kernels
     bool hgemm_no_dma = false;  // dmath_set_hgemm_path(path + 16): the register-only variant of path
     bool hgemm_no_k64 = false;  // dmath_set_hgemm_path(path + 32): global -> LDS loads with the K tile of 32
     bool hgemm_no_mi16 = false; // dmath_set_hgemm_path(path + 64): the K = 64 kernel on the 32x32x16 instruction
-    int dgemm_cfg = -1;   // -1 automatic, else index of the FP64 tile configuration  // -1 automatic, 0 FP32 matrix instruction on widened operands, 1 FP16-input instruction
+    int dgemm_cfg = -1;   // -1 automatic, else index of the FP64 tile configuration
     int last_error_arg = 0;
     unsigned long long *clock_probe = nullptr;
 };
@@ -304,10 +304,13 @@ unsigned stagger_ticks(const CfgDesc &d, int64_t tiles, int splits)
 
 // The plan a call will really use: the automatic one, or the forced configuration / split factor, and
 // always one whose scratch fits into `avail` bytes (measure_only: as if the workspace were unlimited).
-Plan resolve_plan(int64_t M, int64_t N, int64_t K, size_t avail, bool measure_only)
+// wide: a leading dimension needs the kernels with 64-bit per-thread offsets, which exist for one tile
+// configuration only (it overrides a forced one).
+Plan resolve_plan(int64_t M, int64_t N, int64_t K, size_t avail, bool measure_only, bool wide = false)
 {
     const ThreadState &st = g_state;
-    const int only = st.force_cfg < kNumCfg ? st.force_cfg : -1;  // a forced wave-split kernel only concerns dmath_gemm
+    // a forced wave-split kernel only concerns dmath_gemm
+    const int only = wide ? kWideCfg : (st.force_cfg < kNumCfg ? st.force_cfg : -1);
     Plan p = choose_plan(M, N, K, true, only, st.force_split, measure_only ? ~(size_t)0 : avail);
     const CfgDesc &d = desc(p.cfg);
     if (!measure_only && plan_bytes(p, ceil_div(M, d.BM) * ceil_div(N, d.BN), M, N) > avail)
@@ -460,7 +463,9 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
 
-    if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, lda > ((int64_t)1 << 22) ? 8 : 10);
+    // The tile loaders keep 32-bit per-thread byte offsets (up to 256 rows of ld elements of 4 bytes); a
+    // block that is a window of a wider row panel runs on the instantiations with 64-bit offsets.
+    const bool wide = lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22);
     if constexpr (kHalf) {
         // The FP16-input matrix instruction computes the same FP32 sums of exact products 16 times
         // faster; its kernel needs whole K tiles and 16-byte chunks everywhere.
@@ -468,8 +473,8 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
         const HCfgDesc &h = hcfg_desc(hidx);
         const bool fits = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0 && K % h.BK == 0 &&
                           (a_k || M % 8 == 0) && (b_k || N % 8 == 0);
-        if (g_state.hgemm_path >= 1 && !fits) return fail(DMATH_ERR_UNSUPPORTED, 0);
-        if (fits && g_state.hgemm_path != 0 && g_state.force_cfg < 0) {
+        if (g_state.hgemm_path >= 1 && (!fits || wide)) return fail(DMATH_ERR_UNSUPPORTED, 0);
+        if (fits && !wide && g_state.hgemm_path != 0 && g_state.force_cfg < 0) {
             const int64_t tiles_m = ceil_div(M, h.BM), tiles_n = ceil_div(N, h.BN), tiles = tiles_m * tiles_n;
             if (tiles * 64 > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
             const int64_t s = hgemm_split_choice(hidx, M, N, K, ws ? ws_bytes : 0);
@@ -524,7 +529,7 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     }
 
     if constexpr (!kHalf) {
-        const int wk = wavek_choice(M, N, K);
+        const int wk = wide ? -1 : wavek_choice(M, N, K);
         if (wk >= 0) {
             const int64_t tiles_m = ceil_div(M, 64), tiles_n = ceil_div(N, 64);
             if (tiles_m * tiles_n > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
@@ -554,12 +559,12 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
         }
     }
     if (strict) {
-        const Plan want = resolve_plan(M, N, K, 0, true);
+        const Plan want = resolve_plan(M, N, K, 0, true, wide);
         const CfgDesc &wd = desc(want.cfg);
         if (plan_bytes(want, ceil_div(M, wd.BM) * ceil_div(N, wd.BN), M, N) > (ws ? ws_bytes : 0))
             return fail(DMATH_ERR_WORKSPACE, 0);
     }
-    const Plan plan = resolve_plan(M, N, K, ws ? ws_bytes : 0, false);
+    const Plan plan = resolve_plan(M, N, K, ws ? ws_bytes : 0, false, wide);
     const CfgDesc &d = desc(plan.cfg);
     const int64_t tiles_m = ceil_div(M, d.BM), tiles_n = ceil_div(N, d.BN);
     if (tiles_m * tiles_n * plan.splits > (int64_t)0x7fffffff) return fail(DMATH_ERR_UNSUPPORTED, 3);
@@ -590,9 +595,9 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     g.stagger_ticks = stagger_ticks(d, tiles_m * tiles_n, plan.splits);
     int rc;
     if constexpr (kHalf)
-        rc = d.hgemm(g, a_k, b_k, vec, stream);
+        rc = d.hgemm(g, a_k, b_k, vec, wide, stream);
     else
-        rc = d.gemm(g, a_k, b_k, vec, stream);
+        rc = d.gemm(g, a_k, b_k, vec, wide, stream);
     if (rc == (int)hipErrorInvalidValue) return fail(DMATH_ERR_UNSUPPORTED, 0);
     if (rc != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
     if (g.split.plain) {
@@ -893,12 +898,12 @@ dmath_status dmath_gemm_panels(dmath_op transA, dmath_op transB, int64_t M, int6
         hipLaunchKernelGGL((void (*)(float *, int64_t, int64_t, int64_t, float))scale_kernel, dim3(blocks), dim3(256), 0, stream, C, ldc, M, N, beta);
         return hipGetLastError() == hipSuccess ? DMATH_OK : fail(DMATH_ERR_LAUNCH, 0);
     }
-    if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return fail(DMATH_ERR_UNSUPPORTED, lda > ((int64_t)1 << 22) ? 9 : 11);
-
-    // Every tile configuration uses the same K tile; a panel with a ragged last K tile, or operands
-    // that rule out 16-byte loads, are run as one accumulating dmath_gemm per panel instead.
+    // Every tile configuration uses the same K tile; a panel with a ragged last K tile, operands that
+    // rule out 16-byte loads, or leading dimensions beyond the 32-bit per-thread offsets of the fused
+    // kernel are run as one accumulating dmath_gemm per panel instead.
     const int bk = desc(0).BK;
-    if (K % bk != 0 || !vec || npanels == 1) {
+    const bool wide = lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22);
+    if (K % bk != 0 || !vec || npanels == 1 || wide) {
         for (int64_t p = 0; p < npanels; ++p) {
             const dmath_status st = dmath_gemm(transA, transB, M, N, K, alpha, A[p], lda, B[p], ldb, p == 0 ? beta : 1.0f,
                                                C, ldc, stream_);
@@ -1015,8 +1020,11 @@ static dmath_status run_conv(bool bwd_data, int64_t N, int64_t C, int64_t H, int
     if (bwd_data && !room) return fail(DMATH_ERR_WORKSPACE, 0);
     // backward-data as a forward convolution of dy with the flipped filters: stride 1 and pads inside the filter
     const bool as_forward = bwd_data && stride_h == 1 && stride_w == 1 && pad_h <= R - 1 && pad_w <= S - 1;
+    // padding the kernel sees; the tap-major loader shifts its buffer descriptor down by pad_h*W + pad_w
+    // elements and needs the whole shifted range below 2^31 bytes (its halo sentinel is offset 2^31)
+    const int64_t kpad_h = as_forward ? R - 1 - pad_h : pad_h, kpad_w = as_forward ? S - 1 - pad_w : pad_w;
     const bool tap_shape = (!bwd_data || as_forward) && room && RS <= 32 && chans % 16 == 0 &&
-                           N * chans * in_h * in_w * 4 + (R * in_w + S) * 4 < lim;
+                           N * chans * in_h * in_w * 4 + (kpad_h * in_w + kpad_w) * 4 + (R * in_w + S) * 4 < lim;
     const bool copy_filters = bwd_data || tap_shape;
     const size_t split_off = copy_filters ? wt_bytes : 0;
     Plan plan = resolve_plan(rows, cols, KK, ws_total - split_off, false);

@@ -26,21 +26,21 @@ struct GemmArgsT {
 typedef GemmArgsT<float> GemmArgs;
 typedef GemmArgsT<_Float16> HGemmArgs;
 
-template <class Cfg, bool ROWS_K, bool VEC, class T = float>
+template <class Cfg, bool ROWS_K, bool VEC, class T = float, class OffT = uint32_t>
 struct RowLoaderSel {
-    typedef typename LoaderKSel<Cfg::LKV, Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC, T>::type type;
+    typedef typename LoaderKSel<Cfg::LKV, Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC, T, OffT>::type type;
 };
-template <class Cfg, bool VEC, class T>
-struct RowLoaderSel<Cfg, false, VEC, T> {
-    typedef LoaderMN<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC, T> type;
+template <class Cfg, bool VEC, class T, class OffT>
+struct RowLoaderSel<Cfg, false, VEC, T, OffT> {
+    typedef LoaderMN<Cfg::BM, Cfg::BK, Cfg::NT, Cfg::LDA, Cfg::ROT, VEC, T, 1, OffT> type;
 };
-template <class Cfg, bool COLS_K, bool VEC, class T = float>
+template <class Cfg, bool COLS_K, bool VEC, class T = float, class OffT = uint32_t>
 struct ColLoaderSel {
-    typedef typename LoaderKSel<Cfg::LKV, Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC, T>::type type;
+    typedef typename LoaderKSel<Cfg::LKV, Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC, T, OffT>::type type;
 };
-template <class Cfg, bool VEC, class T>
-struct ColLoaderSel<Cfg, false, VEC, T> {
-    typedef LoaderMN<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC, T> type;
+template <class Cfg, bool VEC, class T, class OffT>
+struct ColLoaderSel<Cfg, false, VEC, T, OffT> {
+    typedef LoaderMN<Cfg::BN, Cfg::BK, Cfg::NT, Cfg::LDB, Cfg::ROT, VEC, T, 1, OffT> type;
 };
 
 // Epilogue of a product whose result is a row-major matrix: out = alpha*acc + beta*out with edge
@@ -217,7 +217,9 @@ __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::M
 
 // A_KCONTIG: A stored M x K (transA == N).  B_KCONTIG: B stored N x K (transB == T).
 // VEC: every 16-byte global load of A and B is aligned and wholly inside the matrix.
-template <class Cfg, bool A_KCONTIG, bool B_KCONTIG, bool VEC, class ElemT = float>
+// OffT: uint32_t, or uint64_t when a leading dimension is too large for 32-bit per-thread byte offsets
+// (a block that is a window of a row panel more than 2^22 elements wide).
+template <class Cfg, bool A_KCONTIG, bool B_KCONTIG, bool VEC, class ElemT = float, class OffT = uint32_t>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(const GemmArgsT<ElemT> g)
 {
     __shared__ __attribute__((aligned(16))) float smem[Cfg::STAGES * Cfg::STAGE_FLOATS];
@@ -246,8 +248,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
     slice_range(ktiles_total, (int)(g.K - (int64_t)ktiles_total * Cfg::BK), w.slice, w.nslice, kt0, T, krem);
     const int64_t k0 = (int64_t)kt0 * Cfg::BK;
 
-    typename RowLoaderSel<Cfg, A_KCONTIG, VEC, ElemT>::type rl;
-    typename ColLoaderSel<Cfg, B_KCONTIG, VEC, ElemT>::type cl;
+    typename RowLoaderSel<Cfg, A_KCONTIG, VEC, ElemT, OffT>::type rl;
+    typename ColLoaderSel<Cfg, B_KCONTIG, VEC, ElemT, OffT>::type cl;
     rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x);
     cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x);
 
@@ -270,29 +272,43 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
 }
 
 // Host side: pick the instantiation for the operand orientations and alignment, and launch.
+// wide: a leading dimension of A or B is above 2^22, the kernel needs 64-bit per-thread offsets; only
+// the 128 x 128 configuration with the padded LDS image carries those instantiations (the host plans
+// such calls on it), every other one answers hipErrorInvalidValue.
 // Returns the hipError_t of the launch as int.
 template <class Cfg, class T = float>
-int launch_gemm_cfg(const GemmArgsT<T> &g, bool a_kcontig, bool b_kcontig, bool vec, hipStream_t stream)
+int launch_gemm_cfg(const GemmArgsT<T> &g, bool a_kcontig, bool b_kcontig, bool vec, bool wide, hipStream_t stream)
 {
+    constexpr bool kHasWide = Cfg::BM == 128 && Cfg::BN == 128 && Cfg::LKV == 0;
     // half-precision storage is offered on the padded LDS image only
     if constexpr (!std::is_same<T, float>::value && Cfg::LKV != 0) {
         return (int)hipErrorInvalidValue;
     } else {
+    if (wide && !kHasWide) return (int)hipErrorInvalidValue;
     const int tiles = g.tiles_m * g.tiles_n;
     const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
-#define DMATH_LAUNCH(AK, BK_, V) \
-    hipLaunchKernelGGL((gemm_tile_kernel<Cfg, AK, BK_, V, T>), grid, block, 0, stream, g)
-    if (vec) {
-        if (a_kcontig && b_kcontig) DMATH_LAUNCH(true, true, true);
-        else if (a_kcontig) DMATH_LAUNCH(true, false, true);
-        else if (b_kcontig) DMATH_LAUNCH(false, true, true);
-        else DMATH_LAUNCH(false, false, true);
-    } else {
-        if (a_kcontig && b_kcontig) DMATH_LAUNCH(true, true, false);
-        else if (a_kcontig) DMATH_LAUNCH(true, false, false);
-        else if (b_kcontig) DMATH_LAUNCH(false, true, false);
-        else DMATH_LAUNCH(false, false, false);
+#define DMATH_LAUNCH(AK, BK_, V, OFF) \
+    hipLaunchKernelGGL((gemm_tile_kernel<Cfg, AK, BK_, V, T, OFF>), grid, block, 0, stream, g)
+#define DMATH_LAUNCH_ALL(OFF) \
+    if (vec) { \
+        if (a_kcontig && b_kcontig) DMATH_LAUNCH(true, true, true, OFF); \
+        else if (a_kcontig) DMATH_LAUNCH(true, false, true, OFF); \
+        else if (b_kcontig) DMATH_LAUNCH(false, true, true, OFF); \
+        else DMATH_LAUNCH(false, false, true, OFF); \
+    } else { \
+        if (a_kcontig && b_kcontig) DMATH_LAUNCH(true, true, false, OFF); \
+        else if (a_kcontig) DMATH_LAUNCH(true, false, false, OFF); \
+        else if (b_kcontig) DMATH_LAUNCH(false, true, false, OFF); \
+        else DMATH_LAUNCH(false, false, false, OFF); \
     }
+    if constexpr (kHasWide) {
+        if (wide) {
+            DMATH_LAUNCH_ALL(uint64_t)
+            return (int)hipGetLastError();
+        }
+    }
+    DMATH_LAUNCH_ALL(uint32_t)
+#undef DMATH_LAUNCH_ALL
 #undef DMATH_LAUNCH
     return (int)hipGetLastError();
     }

@@ -135,7 +135,8 @@ __device__ __forceinline__ typename VecOf<U>::type gather_column(const floatx4 (
 // main loop can issue them one at a time between MFMAs; advance() moves to the next K tile.  Global
 // addresses are a workgroup-uniform tile pointer (kept in scalar registers, advanced once per tile)
 // plus per-thread 32-bit byte offsets that never change, so the K loop spends no vector ALU work on
-// addressing.  The host guarantees leading dimensions small enough for those offsets (ld <= 2^22).
+// addressing.  The host guarantees leading dimensions small enough for those offsets (ld <= 2^22), or
+// picks the instantiation with 64-bit offsets.
 //
 // ---------------------------------------------------------------------------------------------
 // Loader for an operand stored contiguously along k: element (r, k) at base[r*ld + k].
@@ -226,7 +227,8 @@ struct LoaderK {
 // 4-byte transposing stores (two-way bank conflicts on every store).
 // KADV: K tiles between two consecutive tiles of this loader (1, or the number of waves that share a
 // K range tile by tile in the wave-split kernel).
-template <int BR, int BK, int NT, int LD, bool VEC, class T = float, int KADV = 1>
+// OffT: type of the per-thread byte offsets: uint32_t (leading dimensions up to 2^22) or uint64_t.
+template <int BR, int BK, int NT, int LD, bool VEC, class T = float, int KADV = 1, class OffT = uint32_t>
 struct LoaderK0 {
     static constexpr int QPR = BK / 4;
     static constexpr int NQ = (BR * QPR) / NT;
@@ -234,7 +236,7 @@ struct LoaderK0 {
     static constexpr int ES = (int)sizeof(T);
     static_assert((BR * QPR) % NT == 0 && NQ >= 1, "tile must split evenly over the threads");
     const char *tile;
-    uint32_t off[NQ];
+    OffT off[NQ];
     floatx4 v[NQ];
     int row0, kq;
 
@@ -247,7 +249,7 @@ struct LoaderK0 {
         for (int it = 0; it < NQ; ++it) {
             int64_t lr = row0 + it * (NT / QPR);
             lr = r0 + lr < R ? lr : R - 1 - r0;
-            off[it] = (uint32_t)((lr * ld + kq * 4) * ES);
+            off[it] = (OffT)((lr * ld + kq * 4) * ES);
         }
     }
     template <int I>
@@ -284,20 +286,20 @@ struct LoaderK0 {
     }
 };
 
-template <int LKV, int BR, int BK, int NT, int LD, int ROT, bool VEC, class T = float>
+template <int LKV, int BR, int BK, int NT, int LD, int ROT, bool VEC, class T = float, class OffT = uint32_t>
 struct LoaderKSel {
-    typedef LoaderK<BR, BK, NT, LD, ROT, VEC> type;  // FP32 storage only
+    typedef LoaderK<BR, BK, NT, LD, ROT, VEC> type;  // FP32 storage, 32-bit offsets only
 };
-template <int BR, int BK, int NT, int LD, int ROT, bool VEC, class T>
-struct LoaderKSel<0, BR, BK, NT, LD, ROT, VEC, T> {
-    typedef LoaderK0<BR, BK, NT, LD, VEC, T> type;
+template <int BR, int BK, int NT, int LD, int ROT, bool VEC, class T, class OffT>
+struct LoaderKSel<0, BR, BK, NT, LD, ROT, VEC, T, OffT> {
+    typedef LoaderK0<BR, BK, NT, LD, VEC, T, 1, OffT> type;
 };
 
 // Loader for an operand stored contiguously along its own index: element (r, k) at base[k*ld + r].
 // Used for A when transA == T and for B when transB == N.  Quads run along r; NT is a multiple of
 // the quads per k row, so a thread keeps one r quad and walks k.  16-byte global loads, 16-byte LDS
 // stores; the lanes served together write one contiguous (rotated) run of an image row.
-template <int BR, int BK, int NT, int LD, int ROT, bool VEC, class T = float, int KADV = 1>
+template <int BR, int BK, int NT, int LD, int ROT, bool VEC, class T = float, int KADV = 1, class OffT = uint32_t>
 struct LoaderMN {
     static constexpr int QPR = BR / 4;
     static constexpr int NQ = (BK * QPR) / NT;
@@ -307,7 +309,7 @@ struct LoaderMN {
     static_assert((BK * QPR) % NT == 0 && NQ >= 1 && NT % QPR == 0, "tile must split evenly over the threads");
     const char *tile;   // &base[k*ld + r0], uniform over the workgroup
     int64_t tstride;    // bytes per K tile: BK * ld * ES
-    uint32_t off[NQ];   // byte offset of k row krow + it*KSTEP, column of the quad (VEC) or 0 (scalar path)
+    OffT off[NQ];       // byte offset of k row krow + it*KSTEP, column of the quad (VEC) or 0 (scalar path)
     uint32_t c[4];      // scalar path: byte offsets of the four elements (clamped to the last valid one)
     floatx4 v[NQ];
     int lds[NQ];
@@ -329,7 +331,7 @@ struct LoaderMN {
 #pragma unroll
         for (int it = 0; it < NQ; ++it) {
             const int k = krow + it * KSTEP;
-            off[it] = (uint32_t)((k * ld + (VEC ? quad : 0)) * ES);
+            off[it] = (OffT)((k * ld + (VEC ? quad : 0)) * ES);
             lds[it] = k * LD + rot_col<BR, ROT>(rq * 4, k);
         }
     }

@@ -111,6 +111,48 @@ def test_gemm_split_k(dm, torch, cfg, split, tA, tB):
     run_gemm_case(dm, torch, tA, tB, 64, 128, 512, alpha=1.0, beta=1.0, seed=split + 2, ints=True, exact=True)
 
 
+def _windowed(torch, mat, ld):
+    """mat (rows x cols, numpy) as a window of a device row panel of width ld; the padding is never defined."""
+    rows, cols = mat.shape
+    flat = torch.empty(rows * ld, dtype=torch.from_numpy(mat).dtype, device="cuda")
+    flat.view(rows, ld)[:, :cols] = torch.from_numpy(mat).cuda()
+    return flat
+
+
+@pytest.mark.parametrize("tA,tB", TRANS)
+@pytest.mark.parametrize("ld", [1 << 22, (1 << 22) + 4, (1 << 22) + 5])
+def test_gemm_block_of_a_very_wide_row_panel(dm, torch, tA, tB, ld):
+    """Leading dimensions at and beyond 2^22 elements, where the per-thread byte offsets of the tile loaders
+    no longer fit 32 bits and the kernels with 64-bit offsets take over (16-byte and element loads)."""
+    M, N, K = 70, 44, 36
+    rng = np.random.default_rng(ld % 97 + 2 * tA + tB)
+    A = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+    B = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    C0 = rng.standard_normal((M, N)).astype(np.float32)
+    As, Bs = (A.T if tA else A).copy(), (B.T if tB else B).copy()
+    dA, dB = _windowed(torch, As, ld), _windowed(torch, Bs, ld)
+    dC = torch.from_numpy(C0).cuda()
+    dm.check(dm.dmath_gemm(tA, tB, M, N, K, 0.5, dA, ld, dB, ld, 2.0, dC, N))
+    torch.cuda.synchronize()
+    ref, mag = oracle.gemm(tA, tB, M, N, K, 0.5, As, As.shape[1], Bs, Bs.shape[1], 2.0, C0, N)
+    check_bound(dC.cpu().numpy(), ref, mag, K, "wide ld %d t%d%d" % (ld, tA, tB))
+    # the same product through the panel entry point (it falls back to one call per panel) and in half storage
+    dC2 = torch.from_numpy(C0).cuda()
+    dm.check(dm.dmath_gemm_panels(tA, tB, M, N, K, 0.5, [dA, dA], ld, [dB, dB], ld, 2.0, dC2, N))
+    torch.cuda.synchronize()
+    ref2, mag2 = oracle.gemm_panels(tA, tB, M, N, K, 0.5, [As, As], As.shape[1], [Bs, Bs], Bs.shape[1], 2.0, C0, N)
+    check_bound(dC2.cpu().numpy(), ref2, mag2, 2 * K, "wide ld panels")
+    del dA, dB
+    Ah, Bh, Ch = As.astype(np.float16), Bs.astype(np.float16), C0.astype(np.float16)
+    dAh, dBh = _windowed(torch, Ah, ld), _windowed(torch, Bh, ld)
+    dCh = torch.from_numpy(Ch).cuda()
+    dm.check(dm.dmath_hgemm(tA, tB, M, N, K, 1.0, dAh, ld, dBh, ld, 1.0, dCh, N))
+    torch.cuda.synchronize()
+    refh, magh = oracle.hgemm(tA, tB, M, N, K, 1.0, Ah, Ah.shape[1], Bh, Bh.shape[1], 1.0, Ch, N)
+    err = np.abs(dCh.cpu().numpy().astype(np.float64) - refh)
+    assert (err <= oracle.half_bound(K, magh, refh)).all()
+
+
 WAVE_SPLIT = [6]   # configuration indices of the kernels that split K over the waves of a workgroup
 
 
