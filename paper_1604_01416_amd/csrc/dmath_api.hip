@@ -151,9 +151,12 @@ __global__ void zero_u32_kernel(unsigned *p, int n)
 // (transposed == 1): rows = C, chans = Kout, source w[ch][row][tap].  flip reverses the tap index
 // (r, s) -> (R-1-r, S-1-s).  tap_major: destination k = ((cb*RS + tap)*BK + cc) for channel cb*BK + cc
 // (the order LoaderConvTap walks); else k = ch*RS + tap.
+// Also clears the ncounters tile counters of a split plan (or none), which saves that plan its own
+// clearing launch.
 __global__ void conv_filter_copy_kernel(const float *w, float *wt, int64_t rows, int chans, int RS, int BK,
-                                        int transposed, int flip, int tap_major)
+                                        int transposed, int flip, int tap_major, unsigned *counters, int ncounters)
 {
+    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < ncounters; c += gridDim.x * blockDim.x) counters[c] = 0u;
     const int64_t KK = (int64_t)chans * RS, total = rows * KK;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
         const int64_t row = e / KK;
@@ -319,8 +322,11 @@ Plan resolve_plan(int64_t M, int64_t N, int64_t K, size_t avail, bool measure_on
 }
 
 // Fills the SplitPlan of a launch from a plan and the scratch area [ws, ws + plan_bytes), and resets
-// the counters on the stream.  Returns false if the reset could not be launched.
-bool prepare_split(const Plan &p, int64_t tiles, int64_t M, int64_t N, void *ws, hipStream_t stream, SplitPlan &out)
+// the counters on the stream (clear_counters == false: the caller has a kernel of its own in front of
+// the launch that clears out.counters[0 .. tiles - dp_tiles)).  Returns false if the reset could not be
+// launched.
+bool prepare_split(const Plan &p, int64_t tiles, int64_t M, int64_t N, void *ws, hipStream_t stream, SplitPlan &out,
+                   bool clear_counters = true)
 {
     out.dp_tiles = p.dp_tiles;
     out.splits = p.splits;
@@ -344,6 +350,7 @@ bool prepare_split(const Plan &p, int64_t tiles, int64_t M, int64_t N, void *ws,
     out.partials = static_cast<float *>(ws);
     out.counters = reinterpret_cast<unsigned *>(static_cast<char *>(ws) +
                                                 align256(split_tiles * p.splits * (size_t)d.BM * d.BN * sizeof(float)));
+    if (!clear_counters) return true;
     hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)ceil_div((int64_t)split_tiles, 256)), dim3(256), 0, stream,
                        out.counters, (int)split_tiles);
     return hipGetLastError() == hipSuccess;
@@ -1062,18 +1069,21 @@ static dmath_status run_conv(bool bwd_data, int64_t N, int64_t C, int64_t H, int
     a.yvec = (aligned16(out) && out_pix % 4 == 0) ? 1 : 0;
     a.x_bytes = N * chans * in_h * in_w * 4;
     bool vec = aligned16(w) && KK % 4 == 0;
+    // the filter copy, when there is one, also clears the counters of the split tail tiles
+    if (!prepare_split(plan, tiles_m * tiles_n, rows, cols, static_cast<char *>(g_state.ws) + split_off, stream, a.split,
+                       !copy_filters))
+        return fail(DMATH_ERR_LAUNCH, 0);
     if (copy_filters) {
         float *wt = static_cast<float *>(g_state.ws);
         const int64_t total = rows * KK;
         const int blocks = (int)(ceil_div(total, 256) < 2048 ? ceil_div(total, 256) : 2048);
+        const int ncounters = a.split.counters != nullptr ? (int)(tiles_m * tiles_n - a.split.dp_tiles) : 0;
         hipLaunchKernelGGL(conv_filter_copy_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, rows, (int)chans, (int)RS,
-                           d.BK, bwd_data ? 1 : 0, as_forward ? 1 : 0, tap ? 1 : 0);
+                           d.BK, bwd_data ? 1 : 0, as_forward ? 1 : 0, tap ? 1 : 0, a.split.counters, ncounters);
         if (hipGetLastError() != hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
         a.w = wt;
         vec = KK % 4 == 0;  // the workspace is 16-byte aligned
     }
-    if (!prepare_split(plan, tiles_m * tiles_n, rows, cols, static_cast<char *>(g_state.ws) + split_off, stream, a.split))
-        return fail(DMATH_ERR_LAUNCH, 0);
     if (d.conv(a, vec, kind, stream) != (int)hipSuccess) return fail(DMATH_ERR_LAUNCH, 0);
     return DMATH_OK;
 }

@@ -633,22 +633,27 @@ struct WorkItem {
 
 __device__ __forceinline__ int xcd_contiguous_id(int bid, int total);
 
+// The K slices of split tiles take the FIRST workgroup ids, the whole tiles the rest.  A slice is short
+// (a fraction of the K range, then its partial sums go to the workspace and the last one to arrive adds
+// them up): run at the end of the launch its fill, drain and combination would be all a compute unit has
+// to do, run at the start they overlap the whole tiles resident beside it.
 __device__ __forceinline__ WorkItem work_item(int bid, int tiles, const SplitPlan &sp)
 {
     WorkItem w;
-    if (bid < sp.dp_tiles) {
-        w.tile = xcd_contiguous_id(bid, sp.dp_tiles);
+    const int nsplit = (tiles - sp.dp_tiles) * sp.splits;   // workgroups that own a slice
+    if (bid >= nsplit) {
+        // bid - nsplit, not bid: the dies then still get contiguous runs of tile ids (only which die
+        // gets which run rotates)
+        w.tile = xcd_contiguous_id(bid - nsplit, sp.dp_tiles);
         w.slice = 0;
         w.nslice = 1;
         w.sq = 0;
     } else {
-        const int q = bid - sp.dp_tiles;
-        w.sq = q / sp.splits;
-        w.slice = q - w.sq * sp.splits;
+        w.sq = bid / sp.splits;
+        w.slice = bid - w.sq * sp.splits;
         w.nslice = sp.splits;
         w.tile = sp.dp_tiles + w.sq;
     }
-    (void)tiles;
     return w;
 }
 
