@@ -36,13 +36,13 @@ MEASURED_HBM_TRAFFIC_BYTES = {
     # per step: sum over the kernels of a step of FETCH_SIZE KiB x 2.0 (copy factor) + WRITE_SIZE KiB x 1.0
     "gemm4096": int((196779.4 * 2.0 + 65536.5) * 1024),                         # profiles/gemm_nn_4096_tile_kernel.md
     "gemm256": int((838.2 * 2.0 + 256.2) * 1024),                               # profiles/gemm_nn_256_tile_kernel.md
-    "summa": int(16 * (259110.2 * 2.0 + 262144.5) * 1024),                      # profiles/summa_update_8192x8192x512_tile_kernel.md
+    "summa": int(16 * (258977.1 * 2.0 + 262144.5) * 1024),                      # profiles/summa_update_8192x8192x512_tile_kernel.md
     "summa_fused": int((1704117.8 * 2.0 + 262144.5) * 1024),                    # profiles/summa_fused_8192x8192x512_x16_panels_kernel.md
-    "fc": int(((67708.4 + 70015.1 + 12458.3 + 2 * 8208.6) * 2.0
-               + 2 * 16384.5 + 65536.5 + 2 * 4096.0) * 1024),                   # profiles/fc_4096_batch256_kernels.md
-    "conv": int(((94222.2 + 1813.8) * 2.0 + 119617.7 + 2304.0) * 1024),         # profiles/conv3x3_n128_c256_k256_28x28_kernels.md
-    "conv_bwd_data": int(((94333.7 + 5717.7) * 2.0 + 119641.9 + 2304.0) * 1024),   # profiles/conv3x3_..._bwd_data_kernels.md
-    "conv_bwd_filter": int(((156909.8 + 32272.7) * 2.0 + 64512.0 + 2304.0) * 1024),  # profiles/conv3x3_..._bwd_filter_kernels.md
+    "fc": int(((49207.9 + 49210.5 + 12462.8) * 2.0
+               + 2 * 4096.5 + 65536.5) * 1024),                                 # profiles/fc_4096_batch256_kernels.md
+    "conv": int(((100885.2 + 1815.1) * 2.0 + 117789.7 + 2304.1) * 1024),        # profiles/conv3x3_n128_c256_k256_28x28_kernels.md
+    "conv_bwd_data": int(((101089.3 + 5719.1) * 2.0 + 117788.9 + 2304.1) * 1024),  # profiles/conv3x3_..._bwd_data_kernels.md
+    "conv_bwd_filter": int(((156765.3 + 32274.5) * 2.0 + 64512.0 + 2304.0) * 1024),  # profiles/conv3x3_..._bwd_filter_kernels.md
     "hgemm4096": int((98406.3 * 2.0 + 32768.5) * 1024),                         # profiles/hgemm_nn_4096_half_storage_mi16_dma64_kernel.md
     "fc_half": int(((2 * 8212.6 + 33922.3 + 6242.6 + 33920.1) * 2.0
                     + 2 * 2048.0 + 2 * 16384.5 + 32768.5) * 1024),              # profiles/fc_4096_batch256_half_storage_kernels.md
