@@ -61,6 +61,9 @@ def _device_arrays(torch, arrays):
     return {k: torch.from_numpy(v).cuda() for k, v in arrays.items()}
 
 
+LAUNCH_BOUND = ("gemm256", "fc", "fc_nn", "fc_nt", "fc_tn", "fc_half")   # steps of 10 - 200 us
+
+
 def _time_steps(torch, step, steps, warmup, per_step=True, before_step=None):
     """warmup untimed steps, then exactly `steps` timed ones between synchronisations.
 
@@ -317,7 +320,9 @@ def main():
         probe = torch.zeros((args.warmup + args.steps, 32), dtype=torch.int64, device="cuda")
         rows_of_probe = [probe[i] for i in range(args.warmup + args.steps)]
         dm.check(dm.dmath_set_clock_probe(rows_of_probe[-1]))
-        if not args.graph:   # a captured launch keeps the pointer it was captured with
+        # (a captured launch keeps the pointer it was captured with; launch-bound workloads would notice
+        # the extra host call per step: both keep the last row for every launch)
+        if not args.graph and args.workload not in LAUNCH_BOUND:
             def before_step(i):
                 dm.dmath_set_clock_probe(rows_of_probe[i + args.warmup])
     if args.graph:   # the same kernels, launched by one graph replay per step
@@ -334,7 +339,7 @@ def main():
         eager_step, step = step, captured.replay
     # one event per step where a step is long enough not to notice it (an event costs about a microsecond
     # on the stream); launch-bound workloads get five batches instead
-    per_step = args.workload not in ("gemm256", "fc", "fc_nn", "fc_nt", "fc_tn", "fc_half") and not args.graph
+    per_step = args.workload not in LAUNCH_BOUND and not args.graph
     timing = _time_steps(torch, step, args.steps, args.warmup, per_step=per_step, before_step=before_step)
     ms_ev, ms_wall = timing["ms"], timing["ms_host"]
     tflops = flop / ms_ev / 1e9
@@ -345,20 +350,34 @@ def main():
                max(1, round((j + 1) * len(spans) / nb) - round(j * len(spans) / nb)) for j in range(nb)]
     measured_clock_ghz = None
     clock_per_step = None
+    kernel_us = []
+    launch_floor_us = None
     if probe is not None:
         dm.check(dm.dmath_set_clock_probe(None))
         clock_per_step = []
+        kernel_us = []
         for row in probe.cpu().tolist():
             p = [int(v) for v in row]
             per_die = [(p[4 * d + 2] - p[4 * d]) / (p[4 * d + 3] - p[4 * d + 1]) * 0.1
                        for d in range(8) if p[4 * d + 3] > p[4 * d + 1]]
             clock_per_step.append(sum(per_die) / len(per_die) if per_die else None)
+            if launches == 1:   # span of the launch on the device: first start to last end of those workgroups
+                starts = [p[4 * d + 1] for d in range(8) if p[4 * d + 3] > p[4 * d + 1]]
+                ends = [p[4 * d + 3] for d in range(8) if p[4 * d + 3] > p[4 * d + 1]]
+                kernel_us.append((max(ends) - min(starts)) / 100.0 if starts else None)
         timed = [c for c in clock_per_step[args.warmup:] if c is not None]
         if timed:
             measured_clock_ghz = {"mean": sum(timed) / len(timed), "min": min(timed), "max": max(timed),
                                   "first_timed_step": timed[0], "last_timed_step": timed[-1],
                                   "first_warmup_step": clock_per_step[0]}
 
+    if args.workload == "gemm256":
+        # what a launch costs when the kernel has next to nothing to do: a 64^3 product (one workgroup),
+        # queued the same way
+        fa, fb, fc_ = (torch.zeros((64, 64), device="cuda") for _ in range(3))
+        floor = _time_steps(torch, lambda: dm.check(dm.dmath_gemm(0, 0, 64, 64, 64, 1.0, fa, 64, fb, 64, 0.0, fc_, 64)),
+                            args.steps, args.warmup, per_step=False)
+        launch_floor_us = floor["ms"] * 1e3
     # The oracle on this machine's host cores on a bounded sample, and the output of the timed launches held
     # against it (beta == 0 workloads recompute the same C every step; an accumulating first call is run
     # once more from the stored C0).
@@ -423,6 +442,9 @@ def main():
         "pct_of_fp32_mfma_peak": 100.0 * tflops / peak if dtype == "f32" else None,
         "pct_of_mfma_peak": 100.0 * tflops / peak,
         "measured_shader_clock_ghz": measured_clock_ghz,
+        "kernel_us_device_stamps": (lambda t: sum(t) / len(t) if t else None)(
+            [k for k in kernel_us[args.warmup:] if k is not None]),   # workgroups 0..7, 100 MHz counter
+        "launch_floor_us": launch_floor_us,
         "pct_of_mfma_peak_at_measured_clock":
             None if not measured_clock_ghz
             else 100.0 * tflops / (peak * measured_clock_ghz["mean"] / 2.4),

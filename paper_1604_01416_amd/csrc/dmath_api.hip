@@ -309,15 +309,45 @@ unsigned stagger_ticks(const CfgDesc &d, int64_t tiles, int splits)
 // always one whose scratch fits into `avail` bytes (measure_only: as if the workspace were unlimited).
 // wide: a leading dimension needs the kernels with 64-bit per-thread offsets, which exist for one tile
 // configuration only (it overrides a forced one).
+// The search costs a few microseconds of host time, which is as long as a small product runs on the
+// device, and a caller repeats its shapes: each thread remembers the plans of the last shapes it asked for.
+struct PlanKey {
+    int64_t M, N, K;
+    size_t avail;
+    int only, force_split;
+    bool operator==(const PlanKey &o) const
+    {
+        return M == o.M && N == o.N && K == o.K && avail == o.avail && only == o.only && force_split == o.force_split;
+    }
+};
+struct PlanCache {
+    static constexpr int kSlots = 32;
+    PlanKey key[kSlots];
+    Plan plan[kSlots];
+    bool used[kSlots] = {};
+};
+thread_local PlanCache g_plan_cache;
+
 Plan resolve_plan(int64_t M, int64_t N, int64_t K, size_t avail, bool measure_only, bool wide = false)
 {
     const ThreadState &st = g_state;
     // a forced wave-split kernel only concerns dmath_gemm
     const int only = wide ? kWideCfg : (st.force_cfg < kNumCfg ? st.force_cfg : -1);
-    Plan p = choose_plan(M, N, K, true, only, st.force_split, measure_only ? ~(size_t)0 : avail);
+    if (measure_only) avail = ~(size_t)0;
+    const PlanKey key = {M, N, K, avail, only, st.force_split};
+    const uint64_t hash = ((uint64_t)M * 0x9e3779b97f4a7c15ull) ^ ((uint64_t)N * 0xc2b2ae3d27d4eb4full) ^
+                          ((uint64_t)K * 0x165667b19e3779f9ull) ^ (uint64_t)avail ^ ((uint64_t)(only + 1) << 40) ^
+                          ((uint64_t)(st.force_split + 1) << 48);
+    const int slot = (int)((hash ^ (hash >> 29) ^ (hash >> 47)) % PlanCache::kSlots);
+    PlanCache &pc = g_plan_cache;
+    if (pc.used[slot] && pc.key[slot] == key) return pc.plan[slot];
+    Plan p = choose_plan(M, N, K, true, only, st.force_split, avail);
     const CfgDesc &d = desc(p.cfg);
-    if (!measure_only && plan_bytes(p, ceil_div(M, d.BM) * ceil_div(N, d.BN), M, N) > avail)
+    if (plan_bytes(p, ceil_div(M, d.BM) * ceil_div(N, d.BN), M, N) > avail)
         p = choose_plan(M, N, K, false, only, -1);  // no room: best plan that needs no scratch
+    pc.key[slot] = key;
+    pc.plan[slot] = p;
+    pc.used[slot] = true;
     return p;
 }
 
@@ -415,15 +445,23 @@ int64_t hgemm_split_choice(int hidx, int64_t M, int64_t N, int64_t K, size_t ava
 // kNumCfg + v of dmath_set_override.  Automatic: one workgroup of 8 waves per compute unit and 64 x 64 tile,
 // so it pays when the 64 x 64 tiles fill whole rounds over the 256 compute units well (measured on
 // MI355X against the best tile configuration with its automatic split: 256 tiles 0.78-0.91 of its time
-// for K from 512 to 8192, 512 and 768 tiles 0.93-0.94, 1024 tiles equal; 192 of 256 equal, 320 and 384 of
-// 512 slower).  Such products used to be cut into K slices across workgroups, with the slices written
-// to and re-read from a workspace by a second kernel.
+// for K from 512 to 8192, 512 and 768 tiles 0.93-0.94, 1024 tiles equal; 192 of 256 equal at K = 4096, 320
+// and 384 of 512 slower; with K up to 256 any tile count up to 256 is 0.94-0.98 of the 64 x 64 tile kernel,
+// at K = 512 from 100 tiles on 0.90, at K = 1024 from 144 tiles on 0.90, 196 tiles 0.64).  Such products
+// used to be cut into K slices across workgroups, with the slices written to and re-read from a workspace
+// by a second kernel.
 int wavek_choice(int64_t M, int64_t N, int64_t K)
 {
     if (g_state.force_cfg >= kNumCfg) return g_state.force_cfg - kNumCfg;
     if (g_state.force_cfg >= 0 || g_state.force_split >= 1) return -1;
     const int64_t tiles = ceil_div(M, 64) * ceil_div(N, 64);
     const int64_t rounds = ceil_div(tiles, kNumCU);
+    if (rounds == 1) {
+        // Less than a round: the fewer tiles, the sooner cutting K across workgroups (more compute units
+        // at work) beats cutting it across the waves of few workgroups.  Measured thresholds.
+        const int64_t min_tiles = K <= 256 ? 1 : K <= 512 ? 96 : K <= 1024 ? 144 : 224;
+        return tiles >= min_tiles ? 0 : -1;
+    }
     return (rounds <= 3 && tiles * 8 >= rounds * kNumCU * 7 && K >= 512) ? 0 : -1;
 }
 
