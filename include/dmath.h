@@ -131,14 +131,11 @@ dmath_status dmath_gemm_noalloc(dmath_op transA, dmath_op transB,
  * exact in FP32 and it accumulates in FP32, so it computes the same sums (in another order) at 16 times
  * the FP32 matrix rate.  Every other case runs the FP32 matrix instruction on operands widened on the
  * fly.  dmath_set_hgemm_path forces one of them for this thread's later calls: -1 automatic, 0 the
- * FP32 instruction; 1, 2, 3 the FP16-input instruction with the 256 x 256 tile of 8 waves, the 256 x 256
- * tile of 4 waves, the 128 x 128 tile (automatic: 1 for large outputs, 3 for small ones; forced:
- * UNSUPPORTED when the conditions do not hold); adding 16 to 1, 2 or 3 selects the variant of that
- * kernel that stages every operand through registers (by default a product with both operands stored
- * along k, transA == N and transB == T, loads them global -> LDS directly, with a K tile of 64 when K
- * is a multiple of 64 and the tile has such a kernel, and then on the 16x16x32 form of the instruction
- * where the tile has that kernel; adding 32 keeps the direct loads at a K tile of 32, adding 64 keeps
- * the K tile of 64 on the 32x32x16 form); a tile configuration forced with dmath_set_override also
+ * FP32 instruction; 1, 2 the FP16-input instruction with the 256 x 256 tile of 8 waves or the 128 x 128
+ * tile of 4 waves (automatic: 1 for large outputs, 2 for small ones; forced: UNSUPPORTED when the
+ * conditions do not hold).  With K a multiple of 64 the FP16-input kernel loads whole 128-byte lines
+ * global -> LDS and runs on the 16x16x32 form of the instruction, otherwise it stages a K tile of 32
+ * through registers on the 32x32x16 form.  A tile configuration forced with dmath_set_override also
  * selects the FP32 instruction.
  */
 dmath_status dmath_hgemm(dmath_op transA, dmath_op transB,

@@ -20,10 +20,7 @@ struct ThreadState {
     size_t ws_bytes = 0;
     int force_cfg = -1;
     int force_split = -1;
-    int hgemm_path = -1;        // -1 automatic, 0 FP32 matrix instruction on widened operands, 1.. a tile of the FP16-input kernels
-    bool hgemm_no_dma = false;  // dmath_set_hgemm_path(path + 16): the register-only variant of path
-    bool hgemm_no_k64 = false;  // dmath_set_hgemm_path(path + 32): global -> LDS loads with the K tile of 32
-    bool hgemm_no_mi16 = false; // dmath_set_hgemm_path(path + 64): the K = 64 kernel on the 32x32x16 instruction
+    int hgemm_path = -1;  // -1 automatic, 0 FP32 matrix instruction on widened operands, 1 / 2 a tile of the FP16-input kernels
     int dgemm_cfg = -1;   // -1 automatic, else index of the FP64 tile configuration
     int last_error_arg = 0;
     unsigned long long *clock_probe = nullptr;
@@ -420,7 +417,7 @@ static void *noalloc_scratch()
 int hgemm_tile_choice(int64_t M, int64_t N)
 {
     if (g_state.hgemm_path >= 1) return g_state.hgemm_path - 1;
-    return ceil_div(M, 256) * ceil_div(N, 256) < 96 ? 2 : 0;
+    return ceil_div(M, 256) * ceil_div(N, 256) < 96 ? 1 : 0;
 }
 
 int64_t hgemm_split_choice(int hidx, int64_t M, int64_t N, int64_t K, size_t avail)
@@ -432,7 +429,7 @@ int64_t hgemm_split_choice(int hidx, int64_t M, int64_t N, int64_t K, size_t ava
         s = g_state.force_split;
     else if (tiles < kNumCU / 2)
         s = kNumCU / tiles;
-    else if (hidx == 2 && tiles < kNumCU)
+    else if (hidx == 1 && tiles < kNumCU)
         s = 2 * kNumCU / tiles;  // two of the small workgroups fit a compute unit
     if (s > kMaxSplits) s = kMaxSplits;
     if (s > ktiles / 2) s = ktiles / 2;
@@ -546,16 +543,9 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
             g.split.counters = nullptr;
             g.split.plain = s > 1 ? 1 : 0;
             g.split.slice_stride = M * N;
-            // both operands stored along k: they go global -> LDS directly (unless the register-only kernel
-            // is asked for); mixed products measured slower that way
-            const bool dma = a_k && b_k && !g_state.hgemm_no_dma;
-            // with a K tile of 64 when there is such a kernel and K allows it: every cache line requested once
-            // (that kernel takes every orientation: an operand stored along its own index is read back
-            // with the transposing LDS read)
-            const bool k64 = h.launch_dma64 != nullptr && K % 64 == 0 && !g_state.hgemm_no_k64 && !g_state.hgemm_no_dma;
-            // ... and on the 16x16x32 form of the instruction, which sustains a higher clock under the power limit
-            const bool mi16 = k64 && h.launch_mi16 != nullptr && !g_state.hgemm_no_mi16;
-            if ((mi16 ? h.launch_mi16 : k64 ? h.launch_dma64 : dma ? h.launch_dma : h.launch)(g, a_k, b_k, stream) != (int)hipSuccess)
+            // K a multiple of 64: whole 128-byte lines per tile row, global -> LDS loads, the 16x16x32 form of
+            // the instruction (it sustains a higher clock under the power limit); else the K tile of 32
+            if ((K % 64 == 0 ? h.launch_mi16 : h.launch)(g, a_k, b_k, stream) != (int)hipSuccess)
                 return fail(DMATH_ERR_LAUNCH, 0);
             if (s > 1) {
                 const bool v4 = (N % 4 == 0) && g.cvec;
@@ -722,17 +712,8 @@ dmath_status dmath_set_override(int tile_config, int split_k)
 
 dmath_status dmath_set_hgemm_path(int path)
 {
-    const bool no_mi16 = path >= 64;
-    if (no_mi16) path -= 64;
-    const bool no_k64 = path >= 32;
-    if (no_k64) path -= 32;
-    const bool no_dma = path >= 16;
-    if (no_dma) path -= 16;
-    if (path < -1 || path > kNumHCfg || ((no_dma || no_k64 || no_mi16) && path < 1)) return fail(DMATH_ERR_INVALID_ARG, 1);
+    if (path < -1 || path > kNumHCfg) return fail(DMATH_ERR_INVALID_ARG, 1);
     g_state.hgemm_path = path;
-    g_state.hgemm_no_mi16 = no_mi16;
-    g_state.hgemm_no_dma = no_dma;
-    g_state.hgemm_no_k64 = no_k64;
     return DMATH_OK;
 }
 

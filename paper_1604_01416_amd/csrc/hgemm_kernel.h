@@ -3,13 +3,12 @@
 // instructions accumulate in FP32, so the arithmetic is the single-precision arithmetic on converted
 // operands that section "Precisions" of the paper describes, at the rate of the 16-bit matrix pipe.
 //
-// Four kernels, oldest first; the host (gemm_entry in dmath_api.hip) picks the last one that applies:
-//   hgemm_mfma16_kernel       K tile 32, operands staged through registers, every orientation (K % 32 == 0)
-//   hgemm_mfma16_dma_kernel   K tile 32, global -> LDS loads, both operands stored along k
-//   hgemm_mfma16_dma64_kernel K tile 64 (whole cache lines), global -> LDS loads, every orientation: an operand
-//                             stored along its own index is read back with the transposing LDS read (K % 64 == 0)
-//   hgemm_mi16_dma64_kernel   the same on the 16x16x32 instruction, which holds a higher clock under the power limit
-// The text below describes the first; each of the others is described where it is defined.
+// Two kernels; the host (gemm_entry in dmath_api.hip) picks by K:
+//   hgemm_mi16_dma64_kernel   K % 64 == 0: K tile 64 (whole cache lines), global -> LDS loads, every orientation (an
+//                             operand stored along its own index is read back with the transposing LDS read), on the
+//                             16x16x32 instruction, which holds a higher clock under the power limit
+//   hgemm_mfma16_kernel       K % 32 == 0 otherwise: K tile 32, operands staged through registers, 32x32x16 instruction
+// The text below describes the second; the first is described where it is defined.
 //
 // Operand layout of the instruction (checked on the device with one-hot operands): lane l holds, for
 // A, row l%32 and the 8 consecutive k = 8*(l/32) .. +7; for B, column l%32 and the same k; the 32x32
@@ -151,59 +150,6 @@ struct HLoaderN {
         pr[1] = v[SLOT][p][1][j];
         *reinterpret_cast<halfx2 *>(S + lds0 + (p * (NT / KP) * 8 + j) * LDK) = pr;
     }
-};
-
-// The same operand (contiguous along k) brought in by global -> LDS loads that bypass the registers:
-// global_load_lds_dwordx4 writes the 16 bytes of lane l at (wave-uniform LDS address) + 16*l (checked on
-// the device), so one instruction fills 16 consecutive 64-byte rows of the swizzled image and each lane
-// fetches the chunk that belongs at its position.  No staging registers, no LDS store instructions.
-template <int BR, int BK, int NT>
-struct HLoaderKDma {
-    static constexpr int NW = NT / 64;
-    static constexpr int NP = BR / (16 * NW);      // instructions per thread and tile
-    static constexpr int NFILL = NP;
-    static constexpr int LD = BK;
-    static_assert(BK == 32 && BR % (16 * NW) == 0 && NP >= 1, "16 rows of 64 bytes per wave instruction");
-    const char *tile;   // workgroup-uniform, kept in scalar registers
-    uint32_t off[NP];   // this lane's byte offsets from it
-    uint32_t wave_lds;  // byte offset of this wave's first row group inside the image
-
-    __device__ __forceinline__ void init(const _Float16 *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
-    {
-        const int wave = tid / 64, lane = tid % 64;
-        const int ch = (lane & 3) ^ ((lane >> 4) & 3);  // logical chunk stored at this lane's position
-        const uint64_t t0 = reinterpret_cast<uint64_t>(base + r0 * ld + k0);  // the same in every lane
-        tile = reinterpret_cast<const char *>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(t0 >> 32)) << 32) |
-                                              (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)t0));
-        wave_lds = (uint32_t)__builtin_amdgcn_readfirstlane(wave * 16 * LD * 2);
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            int64_t lr = (wave + p * NW) * 16 + lane / 4;
-            lr = r0 + lr < R ? lr : R - 1 - r0;
-            off[p] = (uint32_t)((lr * ld + ch * 8) * 2);
-        }
-    }
-    static __device__ __forceinline__ int frag_off(int row, int ks, int h)
-    {
-        return row * LD + (((2 * ks + h) ^ ((row >> 2) & 3)) * 8);
-    }
-    // image_lds: LDS byte address of this operand's image in the stage being filled.  LDS addresses are
-    // handled as integers here: through generic pointers every load paid a null check and a
-    // 64-bit add in scalar instructions, a dozen of them between two matrix instructions.
-    template <int I>
-    __device__ __forceinline__ void fill_piece(uint32_t image_lds) const
-    {
-        // Written as assembly on purpose: for the builtin form the compiler, which cannot tell which LDS
-        // bytes a global -> LDS load writes, waits for all of them (vmcnt(0)) before every later LDS
-        // read, which serialises the very loads this path is meant to keep in flight.  The waits are
-        // placed by hand instead (htile_iter_dma).  m0 = LDS byte address of lane 0's 16 bytes; the
-        // global address is the tile pointer in scalar registers plus the lane's 32-bit offset.
-        asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1"
-                     :
-                     : "v"(off[I]), "s"(tile), "s"(image_lds + wave_lds), "n"(I * NW * 16 * LD * 2)
-                     : "memory", "scc");
-    }
-    __device__ __forceinline__ void advance_fill() { tile += BK * 2; }
 };
 
 template <class Cfg, bool KCONTIG, int BR, int SLOTS>
@@ -502,164 +448,6 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_kernel(c
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 constexpr int waitcnt_vm_lds0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
-// One K tile of the kernel with global -> LDS loads.  k step 0: fragments of k step 1, and the stage
-// at LDS byte address fill_lds receives tile t + S - 1.  Then the barrier, before which every wave
-// waits until its own loads of tile t + 1 have landed (they were issued S - 2 iterations ago; the
-// WAIT_YOUNGER loads issued since may stay in flight).  k step 1: the next tile's first fragments.
-template <class Cfg, bool STEADY, class RL, class CL>
-__device__ __forceinline__ void htile_iter_dma(RL &rl, CL &cl, HFrag<Cfg> (&fr)[2], floatx16 (&acc)[Cfg::MB][Cfg::NB],
-                                               const _Float16 *cur, const _Float16 *nxt, uint32_t fill_lds,
-                                               const int (&a_off)[2], const int (&b_off)[2], bool do_fill = true,
-                                               bool has_next = true)
-{
-    if constexpr (STEADY) {
-        do_fill = true;
-        has_next = true;
-    }
-    constexpr int NMMA = Cfg::MB * Cfg::NB, NFRAG = Cfg::MB + Cfg::NB;
-    constexpr int NFILL = RL::NFILL + CL::NFILL;
-    constexpr int PER = (NFILL + NMMA - 1) / NMMA;
-    constexpr int A_H = Cfg::BM * RL::LD;
-    constexpr int WAIT_YOUNGER = (Cfg::STAGES - 2) * NFILL;
-    static_assert(Cfg::KSTEPS == 2 && NFRAG <= NMMA && WAIT_YOUNGER < 64, "slots and counter range");
-    static_for<NMMA>([&](auto qc) {
-        constexpr int q = decltype(qc)::value;
-        hmma_one<Cfg, q>(fr[0], acc);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (q < NFRAG) hload_frag_piece<Cfg, RL::LD, CL::LD, 1, q>(fr[1], cur, cur + A_H, a_off, b_off);
-        if (do_fill) {
-            static_for<PER>([&](auto ec) {
-                constexpr int st = q * PER + decltype(ec)::value;
-                if constexpr (st < RL::NFILL)
-                    rl.template fill_piece<st>(fill_lds);
-                else if constexpr (st < NFILL)
-                    cl.template fill_piece<st - RL::NFILL>(fill_lds + A_H * 2);
-            });
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    });
-    if (do_fill) {
-        rl.advance_fill();
-        cl.advance_fill();
-    }
-    if constexpr (STEADY)
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(WAIT_YOUNGER));
-    else
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    static_for<NMMA>([&](auto qc) {
-        constexpr int q = decltype(qc)::value;
-        hmma_one<Cfg, q>(fr[1], acc);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (q < NFRAG) {
-            if (has_next) hload_frag_piece<Cfg, RL::LD, CL::LD, 0, q>(fr[0], nxt, nxt + A_H, a_off, b_off);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    });
-}
-
-// The kernel for products with both operands stored along k: they go global -> LDS directly.
-// Cfg::STAGES LDS stages (4: a load has two iterations to land).  The steady loop is unrolled over the
-// stages so that every LDS address in it is a constant.  Same requirements as hgemm_mfma16_kernel.
-// A product with one operand direct and one through registers measured slower than the register
-// kernel (891 against 1101 TFLOP/s at 8192^3: the compiler's own waits for the register loads count
-// the direct loads too and drain them early), so there is no mixed form.
-template <class Cfg>
-__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma_kernel(const HGemmArgs g)
-{
-    typedef HLoaderKDma<Cfg::BM, Cfg::BK, Cfg::NT> RLT;
-    typedef HLoaderKDma<Cfg::BN, Cfg::BK, Cfg::NT> CLT;
-    constexpr int S = Cfg::STAGES;
-    constexpr int A_H = Cfg::BM * RLT::LD, B_H = Cfg::BN * CLT::LD, STAGE_H = A_H + B_H;
-    __shared__ __attribute__((aligned(1024))) _Float16 smem[S * STAGE_H];
-#if defined(__HIP_DEVICE_COMPILE__)
-    typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
-    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lds_ptr)smem;
-#else
-    const uint32_t smem_lds = 0;
-#endif
-
-    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
-        g.clock_probe[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();
-        g.clock_probe[blockIdx.x * 4 + 1] = __builtin_amdgcn_s_memrealtime();
-    }
-    const int tiles = g.tiles_m * g.tiles_n;
-    const WorkItem w = work_item(blockIdx.x, tiles, g.split);
-    int tm, tn;
-    tile_coords<8>(w.tile, g.tiles_m, g.tiles_n, tm, tn);
-    const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
-    int kt0, T, krem;
-    slice_range((int)(g.K / Cfg::BK), 0, w.slice, w.nslice, kt0, T, krem);
-    const int64_t k0 = (int64_t)kt0 * Cfg::BK;
-
-    RLT rl;
-    CLT cl;
-    rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x);
-    cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x);
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int a_row = (wave / Cfg::WAVES_N) * Cfg::WM + (lane & 31), b_row = (wave % Cfg::WAVES_N) * Cfg::WN + (lane & 31);
-    const int a_off[2] = {RLT::frag_off(a_row, 0, lane >> 5), RLT::frag_off(a_row, 1, lane >> 5)};
-    const int b_off[2] = {CLT::frag_off(b_row, 0, lane >> 5), CLT::frag_off(b_row, 1, lane >> 5)};
-
-    floatx16 acc[Cfg::MB][Cfg::NB];
-#pragma unroll
-    for (int bm = 0; bm < Cfg::MB; ++bm)
-#pragma unroll
-        for (int bn = 0; bn < Cfg::NB; ++bn)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
-
-    auto fill_all = [&](uint32_t stage_lds) {
-        static_for<RLT::NFILL>([&](auto ic) { rl.template fill_piece<decltype(ic)::value>(stage_lds); });
-        static_for<CLT::NFILL>([&](auto ic) { cl.template fill_piece<decltype(ic)::value>(stage_lds + A_H * 2); });
-        rl.advance_fill();
-        cl.advance_fill();
-    };
-
-    // Prologue: tiles 0 .. S-2 into stages 0 .. S-2, all landed before the first barrier.
-#pragma unroll
-    for (int s = 0; s < S - 1; ++s) {
-        if (s < T) fill_all(smem_lds + s * STAGE_H * 2);
-    }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-
-    HFrag<Cfg> fr[2];
-    if (T > 0)
-        static_for<Cfg::MB + Cfg::NB>([&](auto pc) {
-            hload_frag_piece<Cfg, RLT::LD, CLT::LD, 0, decltype(pc)::value>(fr[0], smem, smem + A_H, a_off, b_off);
-        });
-
-    int t = 0;
-    // steady state, one trip = S tiles (tile t + j is read from stage j): every iteration of the trip
-    // has a tile to fill and a next tile
-    while (t + 2 * S - 2 < T) {
-        static_for<S>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            htile_iter_dma<Cfg, true>(rl, cl, fr, acc, smem + j * STAGE_H, smem + ((j + 1) % S) * STAGE_H,
-                                      smem_lds + ((j + S - 1) % S) * STAGE_H * 2, a_off, b_off);
-        });
-        t += S;
-    }
-    // the last tiles of the range (t is a multiple of S here): the same iteration with its conditions
-    for (int cs = 0; t < T; ++t) {
-        const int nx = cs + 1 == S ? 0 : cs + 1, fill = cs == 0 ? S - 1 : cs - 1;
-        htile_iter_dma<Cfg, false>(rl, cl, fr, acc, smem + cs * STAGE_H, smem + nx * STAGE_H,
-                                   smem_lds + fill * STAGE_H * 2, a_off, b_off, t + S - 1 < T, t + 1 < T);
-        cs = nx;
-    }
-
-    if (!combine_slices<Cfg>(acc, g.split, w)) return;
-    hstore_tile<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
-    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
-        g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
-        g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
-    }
-}
-
 // ---------------------------------------------------------------------------------------------
 // The same product with a K tile of 64.  A row of a 32-wide K tile is 64 bytes, half a 128-byte
 // cache line: each line is then requested twice, by consecutive K tiles, and by the time of the
@@ -687,10 +475,8 @@ struct HTile64Cfg {
 // consecutive rows; lane l writes position l%8 of row l/8 and fetches the logical chunk
 // pos ^ ((row >> 1) & 7), so that the 16 lanes of a fragment read (16 consecutive rows, one logical
 // chunk) fall into 16 different 16-byte bank groups of the 256-byte LDS line.
-// W0: first row of the wave's tile is W0-strided per wave index (see the kernel); NBLK blocks of 32 rows.
-// MI: 32 for the 32x32x16 matrix instruction (fragments of 32 rows, four k steps of 16 per tile), 16 for
-// 16x16x32 (fragments of 16 rows, two k steps of 32).
-template <int BR, int NT, int NBLK, int MI = 32>
+// NBLK blocks of 16 rows per wave; fragments of 16 rows, two k steps of 32 per tile (16x16x32 instruction).
+template <int BR, int NT, int NBLK>
 struct HLoaderKDma64 {
     static constexpr int NW = NT / 64;
     static constexpr int NP = BR / (8 * NW);  // instructions per thread and tile
@@ -700,7 +486,7 @@ struct HLoaderKDma64 {
     const char *tile;   // workgroup-uniform, kept in scalar registers
     uint32_t off[NP];   // this lane's byte offsets from it
     uint32_t wave_lds;  // byte offset of this wave's first row group inside the image
-    uint32_t foff[4];   // byte offset of the lane's fragment of block 0, per k step
+    uint32_t foff[2];   // byte offset of the lane's fragment of block 0, per k step
 
     // w0: first row of this wave's part of the tile
     __device__ __forceinline__ void init(const _Float16 *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid, int w0)
@@ -718,33 +504,34 @@ struct HLoaderKDma64 {
             lr = r0 + lr < R ? lr : R - 1 - r0;
             off[p] = (uint32_t)((lr * ld + ch * 8) * 2);
         }
-        if constexpr (MI == 32) {
-            const int row = w0 + (lane & 31), h = lane >> 5;
+        const int row = w0 + (lane & 15), q = lane >> 4;  // lane holds k = 32*ks + 8*q .. +7 of its row
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) foff[ks] = (uint32_t)(row * 128 + (((2 * ks + h) ^ ((row >> 1) & 7)) * 16));
-        } else {
-            const int row = w0 + (lane & 15), q = lane >> 4;  // lane holds k = 32*ks + 8*q .. +7 of its row
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) foff[ks] = (uint32_t)(row * 128 + (((4 * ks + q) ^ ((row >> 1) & 7)) * 16));
-        }
+        for (int ks = 0; ks < 2; ++ks) foff[ks] = (uint32_t)(row * 128 + (((4 * ks + q) ^ ((row >> 1) & 7)) * 16));
     }
     template <int I>
     __device__ __forceinline__ void fill_piece(uint32_t image_lds) const
     {
-        // assembly for the reason given in HLoaderKDma::fill_piece
+        // Written as assembly on purpose: for the builtin form the compiler, which cannot tell which LDS
+        // bytes a global -> LDS load writes, waits for all of them (vmcnt(0)) before every later LDS
+        // read, which serialises the very loads this path is meant to keep in flight.  The waits are
+        // placed by hand instead (htile_iter_mi16).  m0 = LDS byte address of lane 0's 16 bytes (the 16
+        // bytes of lane l land at that address + 16*l, checked on the device); the global address is the
+        // tile pointer in scalar registers plus the lane's 32-bit offset.  LDS addresses are handled as
+        // integers: through generic pointers every load paid a null check and a 64-bit add in scalar
+        // instructions, a dozen of them between two matrix instructions.
         asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1"
                      :
                      : "v"(off[I]), "s"(tile), "s"(image_lds + wave_lds), "n"(I * NW * 8 * 128)
                      : "memory", "scc");
     }
     __device__ __forceinline__ void advance_fill(int64_t) { tile += 64 * 2; }
-    // the lane's 8 halves of block BLK (32 rows), k step KS: 8 consecutive k of one row
+    // the lane's 8 halves of block BLK (16 rows), k step KS: 8 consecutive k of one row
     template <int KS, int BLK>
     __device__ __forceinline__ halfx8 read_frag(uint32_t image_lds) const
     {
 #if defined(__HIP_DEVICE_COMPILE__)
         typedef const __attribute__((address_space(3))) halfx8 *lp;
-        return *(lp)(uintptr_t)(image_lds + foff[KS] + BLK * MI * 128);
+        return *(lp)(uintptr_t)(image_lds + foff[KS] + BLK * 16 * 128);
 #else
         (void)image_lds;
         return halfx8{};
@@ -762,9 +549,9 @@ struct HLoaderKDma64 {
 // position l of the unit); position r*16 + (c ^ 4r) holds chunk c (8 x) of row r, so that the 4 rows x
 // 32 bytes of a 16-lane group, and the two groups that share a pass, use different banks.
 // Unit (k/4, x/128) is unit number (k/4)*(BR/128) + x/128.
-// For the 16x16x32 instruction (MI == 16) the two 16-lane groups that share a pass read k rows 8 apart, not
-// columns 16 apart: the chunk position is also XORed with 2*((k >> 3) & 1) to keep them on different banks.
-template <int BR, int NT, int NBLK, int MI = 32>
+// For the 16x16x32 instruction the two 16-lane groups that share a pass read k rows 8 apart: the chunk
+// position is also XORed with 2*((k >> 3) & 1) to keep them on different banks.
+template <int BR, int NT, int NBLK>
 struct HLoaderNDma64 {
     static constexpr int NW = NT / 64;
     static constexpr int XH = BR / 128;             // units per row group
@@ -789,29 +576,19 @@ struct HLoaderNDma64 {
         for (int p = 0; p < NP; ++p) {
             const int u = wave + p * NW;
             const int k = (u / XH) * 4 + r;
-            const int c = (lane % 16) ^ (4 * r) ^ (MI == 16 ? 2 * ((k >> 3) & 1) : 0);
+            const int c = (lane % 16) ^ (4 * r) ^ (2 * ((k >> 3) & 1));
             int64_t x = (u % XH) * 128 + c * 8;
             x = x0 + x + 8 <= X ? x : X - 8 - x0;  // past the edge: the last whole chunk (never used)
             off[p] = (uint32_t)((k * ld + x) * 2);
         }
         // source address this lane supplies to the transposing read of block b (k step 0, k 0..3 of its 8)
-        if constexpr (MI == 32) {
-            const int kk = 8 * (lane / 32) + (lane % 16) / 4;
+        // the group of 16 lanes l/16 reads k = 8*(l/16) .. +3 (then +4 .. +7) of 16 columns
+        const int kk = 8 * (lane / 16) + (lane % 16) / 4;
 #pragma unroll
-            for (int b = 0; b < NBLK; ++b) {
-                const int x = w0 + b * 32 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
-                const int u = (kk / 4) * XH + x / 128, rr = kk % 4, cc = (x % 128) / 8;
-                foff[b] = (uint32_t)(u * 1024 + (rr * 16 + (cc ^ (4 * rr))) * 16 + (x % 8) * 2);
-            }
-        } else {
-            // the group of 16 lanes l/16 reads k = 8*(l/16) .. +3 (then +4 .. +7) of 16 columns
-            const int kk = 8 * (lane / 16) + (lane % 16) / 4;
-#pragma unroll
-            for (int b = 0; b < NBLK; ++b) {
-                const int x = w0 + b * 16 + 4 * (lane % 4);
-                const int u = (kk / 4) * XH + x / 128, rr = kk % 4, cc = (x % 128) / 8;
-                foff[b] = (uint32_t)(u * 1024 + (rr * 16 + (cc ^ (4 * rr) ^ (2 * ((kk >> 3) & 1)))) * 16 + (x % 8) * 2);
-            }
+        for (int b = 0; b < NBLK; ++b) {
+            const int x = w0 + b * 16 + 4 * (lane % 4);
+            const int u = (kk / 4) * XH + x / 128, rr = kk % 4, cc = (x % 128) / 8;
+            foff[b] = (uint32_t)(u * 1024 + (rr * 16 + (cc ^ (4 * rr) ^ (2 * ((kk >> 3) & 1)))) * 16 + (x % 8) * 2);
         }
     }
     template <int I>
@@ -830,8 +607,8 @@ struct HLoaderNDma64 {
         typedef short shortx4 __attribute__((ext_vector_type(4)));
         typedef short shortx8 __attribute__((ext_vector_type(8)));
         typedef __attribute__((address_space(3))) shortx4 *lp;
-        // k step KS starts 4 (MI == 16: 8) row groups further, the second half of the lane's 8 k one row group further
-        const uint32_t a = image_lds + foff[BLK] + KS * (MI == 32 ? 4 : 8) * XH * 1024;
+        // k step KS starts 8 row groups further, the second half of the lane's 8 k one row group further
+        const uint32_t a = image_lds + foff[BLK] + KS * 8 * XH * 1024;
         const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(uintptr_t)a);
         const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(uintptr_t)(a + XH * 1024));
         const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -843,193 +620,14 @@ struct HLoaderNDma64 {
     }
 };
 
-template <bool KCONTIG, int BR, int NT, int NBLK, int MI = 32>
+template <bool KCONTIG, int BR, int NT, int NBLK>
 struct HLoader64Sel {
-    typedef HLoaderKDma64<BR, NT, NBLK, MI> type;
+    typedef HLoaderKDma64<BR, NT, NBLK> type;
 };
-template <int BR, int NT, int NBLK, int MI>
-struct HLoader64Sel<false, BR, NT, NBLK, MI> {
-    typedef HLoaderNDma64<BR, NT, NBLK, MI> type;
+template <int BR, int NT, int NBLK>
+struct HLoader64Sel<false, BR, NT, NBLK> {
+    typedef HLoaderNDma64<BR, NT, NBLK> type;
 };
-
-// Fragment piece P of k step KS in the order the matrix instructions need them: block row 0 of A,
-// the block columns of B, then the other block rows of A.
-template <class Cfg, int KS, int P, class RL, class CL>
-__device__ __forceinline__ void hload_frag_piece64(HFrag<Cfg> &f, const RL &rl, const CL &cl, uint32_t a_lds, uint32_t b_lds)
-{
-    if constexpr (P == 0)
-        f.a[0] = rl.template read_frag<KS, 0>(a_lds);
-    else if constexpr (P <= Cfg::NB)
-        f.b[P - 1] = cl.template read_frag<KS, P - 1>(b_lds);
-    else
-        f.a[P - Cfg::NB] = rl.template read_frag<KS, P - Cfg::NB>(a_lds);
-}
-
-// One K tile of 64.  k steps 0..2 run on the current stage and read the fragments of the following
-// step.  Then the one barrier of the iteration, before which a wave waits for its own loads of the
-// next tile and for its last fragment reads of this one: after it the other stage is complete and the
-// current stage is free.  k step 3 reads the next tile's first fragments and issues the first half of
-// the loads of tile t + 2 into the current stage; the second half follows during k step 0 of the next
-// iteration.  All of a tile's loads in one k step overran the load queue (64 KB is 1024 cycles of
-// first-level cache bandwidth, a k step lasts 512) and the waves stalled at issue: spread, +4 % at 4096^3.
-// cur_lds / nxt_lds: LDS byte addresses of the two stages.
-template <class Cfg, bool STEADY, class RL, class CL>
-__device__ __forceinline__ void htile_iter_dma64(RL &rl, CL &cl, HFrag<Cfg> (&fr)[2], floatx16 (&acc)[Cfg::MB][Cfg::NB],
-                                                 uint32_t cur_lds, uint32_t nxt_lds, int64_t lda, int64_t ldb,
-                                                 bool do_fill = true, bool has_next = true)
-{
-    if constexpr (STEADY) {
-        do_fill = true;
-        has_next = true;
-    }
-    constexpr int NMMA = Cfg::MB * Cfg::NB, NFRAG = Cfg::MB + Cfg::NB;
-    constexpr int NFILL = RL::NFILL + CL::NFILL;
-    constexpr uint32_t B_IMG = Cfg::A_HALVES * 2;
-    static_assert(Cfg::KSTEPS == 4 && NFRAG <= NMMA, "fragment reads fit between the matrix instructions of a k step");
-    // loads of a tile: first half during k step 3 (into the stage just freed), second half during k step 0
-    // of the next iteration, STRIDE matrix instructions apart
-    constexpr int HALF = NFILL / 2, STRIDE = NMMA / HALF;
-    static_assert(NFILL % 2 == 0 && NMMA % HALF == 0, "loads spread evenly over two k steps");
-    auto fill_one = [&](auto stc, uint32_t stage_lds) {
-        constexpr int st = decltype(stc)::value;
-        if constexpr (st < RL::NFILL)
-            rl.template fill_piece<st>(stage_lds);
-        else if constexpr (st < NFILL)
-            cl.template fill_piece<st - RL::NFILL>(stage_lds + B_IMG);
-    };
-    static_for<3>([&](auto kc) {
-        constexpr int ks = decltype(kc)::value;
-        static_for<NMMA>([&](auto qc) {
-            constexpr int q = decltype(qc)::value;
-            hmma_one<Cfg, q>(fr[ks & 1], acc);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (q < NFRAG) hload_frag_piece64<Cfg, ks + 1, q>(fr[(ks + 1) & 1], rl, cl, cur_lds, cur_lds + B_IMG);
-            if constexpr (ks == 0 && q % STRIDE == STRIDE - 1) {
-                if (has_next) fill_one(std::integral_constant<int, HALF + q / STRIDE>{}, nxt_lds);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        if constexpr (ks == 0) {
-            if (has_next) {
-                rl.advance_fill(lda);
-                cl.advance_fill(ldb);
-            }
-        }
-    });
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    static_for<NMMA>([&](auto qc) {
-        constexpr int q = decltype(qc)::value;
-        hmma_one<Cfg, q>(fr[1], acc);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (q < NFRAG) {
-            if (has_next) hload_frag_piece64<Cfg, 0, q>(fr[0], rl, cl, nxt_lds, nxt_lds + B_IMG);
-        }
-        if constexpr (q % STRIDE == STRIDE - 1) {
-            if (do_fill) fill_one(std::integral_constant<int, q / STRIDE>{}, cur_lds);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    });
-}
-
-// Needs K a multiple of 64 and the alignment of hgemm_mfma16_kernel (an operand stored along its own
-// index: a multiple of 8 rows / columns).  All four orientations.
-template <class Cfg, bool A_KCONTIG, bool B_KCONTIG>
-__global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mfma16_dma64_kernel(const HGemmArgs g)
-{
-    typedef typename HLoader64Sel<A_KCONTIG, Cfg::BM, Cfg::NT, Cfg::MB>::type RLT;
-    typedef typename HLoader64Sel<B_KCONTIG, Cfg::BN, Cfg::NT, Cfg::NB>::type CLT;
-    constexpr int A_H = Cfg::A_HALVES, STAGE_H = Cfg::STAGE_HALVES;
-    constexpr uint32_t STAGE_B = STAGE_H * 2;
-    __shared__ __attribute__((aligned(1024))) _Float16 smem[2 * STAGE_H];
-#if defined(__HIP_DEVICE_COMPILE__)
-    typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
-    const uint32_t smem_lds = (uint32_t)(uintptr_t)(lds_ptr)smem;
-#else
-    const uint32_t smem_lds = 0;
-#endif
-
-    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
-        g.clock_probe[blockIdx.x * 4 + 0] = __builtin_readcyclecounter();
-        g.clock_probe[blockIdx.x * 4 + 1] = __builtin_amdgcn_s_memrealtime();
-    }
-    const int tiles = g.tiles_m * g.tiles_n;
-    const WorkItem w = work_item(blockIdx.x, tiles, g.split);
-    int tm, tn;
-    tile_coords<8>(w.tile, g.tiles_m, g.tiles_n, tm, tn);
-    const int64_t m0 = (int64_t)tm * Cfg::BM, n0 = (int64_t)tn * Cfg::BN;
-    int kt0, T, krem;
-    slice_range((int)(g.K / Cfg::BK), 0, w.slice, w.nslice, kt0, T, krem);
-    const int64_t k0 = (int64_t)kt0 * Cfg::BK;
-
-    const int wave = threadIdx.x >> 6;
-    RLT rl;
-    CLT cl;
-    rl.init(g.A, g.lda, m0, g.M, k0, threadIdx.x, (wave / Cfg::WAVES_N) * Cfg::WM);
-    cl.init(g.B, g.ldb, n0, g.N, k0, threadIdx.x, (wave % Cfg::WAVES_N) * Cfg::WN);
-
-    floatx16 acc[Cfg::MB][Cfg::NB];
-#pragma unroll
-    for (int bm = 0; bm < Cfg::MB; ++bm)
-#pragma unroll
-        for (int bn = 0; bn < Cfg::NB; ++bn)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.0f;
-
-    constexpr int NFILL = RLT::NFILL + CLT::NFILL;
-    auto fill_range = [&](auto loc, auto hic, uint32_t stage_lds) {  // pieces LO .. HI-1 of the tile at the fill pointers
-        constexpr int LO = decltype(loc)::value, HI = decltype(hic)::value;
-        static_for<HI - LO>([&](auto ic) {
-            constexpr int st = LO + decltype(ic)::value;
-            if constexpr (st < RLT::NFILL)
-                rl.template fill_piece<st>(stage_lds);
-            else
-                cl.template fill_piece<st - RLT::NFILL>(stage_lds + A_H * 2);
-        });
-    };
-    typedef std::integral_constant<int, 0> I0;
-    typedef std::integral_constant<int, NFILL> IAll;
-
-    // Prologue: tile 0 landed in stage 0 and visible to all waves; tile 1 on its way into stage 1.
-    if (T > 0) {
-        fill_range(I0(), IAll(), smem_lds);
-        rl.advance_fill(g.lda);
-        cl.advance_fill(g.ldb);
-    }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(0));
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    // the first half of tile 1; iteration 0 issues the second half and moves the pointers on
-    if (T > 1) fill_range(I0(), std::integral_constant<int, NFILL / 2>(), smem_lds + STAGE_B);
-
-    HFrag<Cfg> fr[2];
-    if (T > 0)
-        static_for<Cfg::MB + Cfg::NB>([&](auto pc) {
-            hload_frag_piece64<Cfg, 0, decltype(pc)::value>(fr[0], rl, cl, smem_lds, smem_lds + A_H * 2);
-        });
-
-    int t = 0;
-    // steady state, two tiles per trip (stage addresses are constants): both have a tile to fill
-    while (t + 3 < T) {
-        htile_iter_dma64<Cfg, true>(rl, cl, fr, acc, smem_lds, smem_lds + STAGE_B, g.lda, g.ldb);
-        htile_iter_dma64<Cfg, true>(rl, cl, fr, acc, smem_lds + STAGE_B, smem_lds, g.lda, g.ldb);
-        t += 2;
-    }
-    // the last tiles (t is even here): the same iteration with its conditions
-    for (; t < T; ++t) {
-        const uint32_t cs = (uint32_t)(t & 1);
-        htile_iter_dma64<Cfg, false>(rl, cl, fr, acc, smem_lds + cs * STAGE_B, smem_lds + (cs ^ 1u) * STAGE_B, g.lda, g.ldb,
-                                     t + 2 < T, t + 1 < T);
-    }
-
-    if (!combine_slices<Cfg>(acc, g.split, w)) return;
-    hstore_tile<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
-    if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
-        g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
-        g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
-    }
-}
 
 // ---------------------------------------------------------------------------------------------
 // The K = 64 kernel on v_mfma_f32_16x16x32_f16.  Same tile, loads and LDS images (the image of an operand
@@ -1222,13 +820,74 @@ __device__ __forceinline__ void hstore_tile16_lds(const floatx4 (&acc)[Cfg::WM /
 #endif
 }
 
+// The same for beta != 0: the result must be rounded once, from alpha*acc + beta*old, so the wave stages
+// FP32 values, one block row (16 rows of its tile) at a time, in the same region of its own, and the copy
+// loop reads 8 of them per lane, adds the 8 old halves it fetched with one 16-byte load before the
+// staging began, rounds and stores 16 bytes.  The arithmetic is that of the direct epilogue, bit for bit.
+// FP32 rows are padded by 16 bytes: the four row groups of a 4-byte write fall on different banks.
+template <class Cfg>
+struct HEpilogueLdsBeta {
+    static constexpr int ROWB = Cfg::WN * 4 + 16;                 // bytes per staged row
+    static constexpr int BYTES = (Cfg::NT / 64) * 16 * ROWB;      // all waves, one block row each
+    static constexpr int CH = Cfg::WN / 8, RPI = 64 / CH;         // 8-element chunks per row, rows per instruction
+    static constexpr int IT = 16 / RPI;                           // copy instructions per block row
+    static_assert(64 % CH == 0 && 16 % RPI == 0, "whole rows per instruction");
+};
+
+template <class Cfg>
+__device__ __forceinline__ void hstore_tile16_lds_beta(const floatx4 (&acc)[Cfg::WM / 16][Cfg::WN / 16], _Float16 *C,
+                                                       int64_t ldc, float alpha, float beta, int64_t m0, int64_t n0,
+                                                       uint32_t smem_lds)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef HEpilogueLdsBeta<Cfg> E;
+    constexpr int MB16 = Cfg::WM / 16, NB16 = Cfg::WN / 16;
+    typedef __attribute__((address_space(3))) float *lp32;
+    typedef __attribute__((address_space(3))) const floatx4 *lp128;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int wm0 = (wave / Cfg::WAVES_N) * Cfg::WM, wn0 = (wave % Cfg::WAVES_N) * Cfg::WN;
+    const uint32_t region = smem_lds + (uint32_t)wave * (16 * E::ROWB);
+    const uint32_t wr = region + (uint32_t)(4 * g) * E::ROWB + (uint32_t)i * 4;
+    const int row = lane / E::CH, ch = lane % E::CH;
+    const uint32_t rd = region + (uint32_t)row * E::ROWB + (uint32_t)ch * 32;
+    _Float16 *dst = C + (m0 + wm0 + row) * ldc + (n0 + wn0 + ch * 8);
+#pragma unroll
+    for (int bm = 0; bm < MB16; ++bm) {
+        halfx8 old[E::IT];
+#pragma unroll
+        for (int it = 0; it < E::IT; ++it)
+            old[it] = *reinterpret_cast<const halfx8 *>(dst + (int64_t)(16 * bm + it * E::RPI) * ldc);
+#pragma unroll
+        for (int bn = 0; bn < NB16; ++bn)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) *(lp32)(uintptr_t)(wr + r * E::ROWB + 64 * bn) = alpha * acc[bm][bn][r];
+        // the region is this wave's own and the LDS serves one wave's accesses in order: its writes only
+        // have to have landed before its reads, and the next block row's writes follow this one's reads
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lds0(63));
+#pragma unroll
+        for (int it = 0; it < E::IT; ++it) {
+            const floatx4 lo = *(lp128)(uintptr_t)(rd + it * E::RPI * E::ROWB);
+            const floatx4 hi = *(lp128)(uintptr_t)(rd + it * E::RPI * E::ROWB + 16);
+            halfx8 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                o[j] = (_Float16)__builtin_fmaf(beta, (float)old[it][j], lo[j]);
+                o[4 + j] = (_Float16)__builtin_fmaf(beta, (float)old[it][4 + j], hi[j]);
+            }
+            *reinterpret_cast<halfx8 *>(dst + (int64_t)(16 * bm + it * E::RPI) * ldc) = o;
+        }
+    }
+#endif
+}
+
 // Needs K a multiple of 64, the alignment of hgemm_mfma16_kernel, and a plain split-K plan (raw slices).
 template <class Cfg, bool A_KCONTIG, bool B_KCONTIG>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mi16_dma64_kernel(const HGemmArgs g)
 {
     constexpr int MB16 = Cfg::WM / 16, NB16 = Cfg::WN / 16;
-    typedef typename HLoader64Sel<A_KCONTIG, Cfg::BM, Cfg::NT, MB16, 16>::type RLT;
-    typedef typename HLoader64Sel<B_KCONTIG, Cfg::BN, Cfg::NT, NB16, 16>::type CLT;
+    typedef typename HLoader64Sel<A_KCONTIG, Cfg::BM, Cfg::NT, MB16>::type RLT;
+    typedef typename HLoader64Sel<B_KCONTIG, Cfg::BN, Cfg::NT, NB16>::type CLT;
     constexpr int A_H = Cfg::A_HALVES, STAGE_H = Cfg::STAGE_HALVES;
     constexpr uint32_t STAGE_B = STAGE_H * 2;
     constexpr int NMMA = MB16 * NB16, NFILL = RLT::NFILL + CLT::NFILL, SP = NMMA / NFILL;
@@ -1240,7 +899,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mi16_dma64_kern
     typedef __attribute__((address_space(3))) _Float16 *lds_ptr;
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(lds_ptr)smem;
 #else
-    const uint32_t smem_lds = 0;
+    const uint32_t smem_lds = 0;  // host pass: the body is never run
+    (void)smem;
 #endif
 
     if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
@@ -1314,8 +974,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mi16_dma64_kern
 
     // cvec here: C 16-byte aligned with ldc a multiple of 8 (set by the host for this kernel)
     const bool raw = g.split.plain && w.nslice > 1;
-    if (!raw && g.beta == 0.0f && g.cvec == 2 && T > 0 && m0 + Cfg::BM <= g.M && n0 + Cfg::BN <= g.N)
+    static_assert(HEpilogueLdsBeta<Cfg>::BYTES <= SMEM_H * 2, "the staging regions fit into the stages");
+    const bool through_lds = !raw && g.cvec == 2 && T > 0 && m0 + Cfg::BM <= g.M && n0 + Cfg::BN <= g.N;
+    if (through_lds && g.beta == 0.0f)
         hstore_tile16_lds<Cfg>(acc, g.C, g.ldc, g.alpha, m0, n0, smem_lds);
+    else if (through_lds)
+        hstore_tile16_lds_beta<Cfg>(acc, g.C, g.ldc, g.alpha, g.beta, m0, n0, smem_lds);
     else
         hstore_tile16<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
     if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
@@ -1342,33 +1006,6 @@ int launch_hgemm_mi16_dma64(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, 
 }
 
 template <class Cfg>
-int launch_hgemm_mfma16_dma64(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
-{
-    if (g.K % Cfg::BK != 0) return (int)hipErrorInvalidValue;
-    const int tiles = g.tiles_m * g.tiles_n;
-    const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
-    if (a_kcontig && b_kcontig)
-        hipLaunchKernelGGL((hgemm_mfma16_dma64_kernel<Cfg, true, true>), grid, block, 0, stream, g);
-    else if (a_kcontig)
-        hipLaunchKernelGGL((hgemm_mfma16_dma64_kernel<Cfg, true, false>), grid, block, 0, stream, g);
-    else if (b_kcontig)
-        hipLaunchKernelGGL((hgemm_mfma16_dma64_kernel<Cfg, false, true>), grid, block, 0, stream, g);
-    else
-        hipLaunchKernelGGL((hgemm_mfma16_dma64_kernel<Cfg, false, false>), grid, block, 0, stream, g);
-    return (int)hipGetLastError();
-}
-
-template <class Cfg>
-int launch_hgemm_mfma16_dma(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
-{
-    if (!(a_kcontig && b_kcontig)) return (int)hipErrorInvalidValue;
-    const int tiles = g.tiles_m * g.tiles_n;
-    const dim3 grid((unsigned)(g.split.dp_tiles + (tiles - g.split.dp_tiles) * g.split.splits)), block(Cfg::NT);
-    hipLaunchKernelGGL((hgemm_mfma16_dma_kernel<Cfg>), grid, block, 0, stream, g);
-    return (int)hipGetLastError();
-}
-
-template <class Cfg>
 int launch_hgemm_mfma16(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipStream_t stream)
 {
     const int tiles = g.tiles_m * g.tiles_n;
@@ -1387,12 +1024,10 @@ int launch_hgemm_mfma16(const HGemmArgs &g, bool a_kcontig, bool b_kcontig, hipS
 struct HCfgDesc {
     const char *name;
     int BM, BN, BK, NT, lds_bytes;
-    int (*launch)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);      // all loads through registers
-    int (*launch_dma)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);  // operands stored along k: global -> LDS
-    int (*launch_dma64)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);  // the same with a K tile of 64 (K % 64 == 0), or null
-    int (*launch_mi16)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);   // K tile of 64 on the 16x16x32 instruction, or null
+    int (*launch)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);       // K tile of 32, loads through registers
+    int (*launch_mi16)(const HGemmArgs &, bool a_kcontig, bool b_kcontig, hipStream_t);  // K % 64 == 0: K tile of 64, global -> LDS
 };
-constexpr int kNumHCfg = 3;
+constexpr int kNumHCfg = 2;
 const HCfgDesc &hcfg_desc(int i);  // defined in hgemm_instance.hip
 
 }  // namespace dmath

@@ -767,17 +767,18 @@ def test_hgemm_4096_sampled(dm, torch):
 
 @pytest.mark.parametrize("tA,tB", TRANS)
 @pytest.mark.parametrize("K", [32, 64, 96, 128, 160, 192, 224, 256, 288, 320, 384, 448, 512, 640])
-@pytest.mark.parametrize("path", [1, 2, 3, 17, 19, 33, 65, 67])
+@pytest.mark.parametrize("path", [1, 2])
 def test_hgemm_fp16_instruction_k_ranges(dm, torch, tA, tB, K, path):
-    """The FP16-input matrix-instruction kernels (8-wave and 4-wave tile; register staging, global -> LDS loads
-    with K tiles of 32 and of 64, the latter on both forms of the instruction) over every prologue / steady / drain combination of K tiles."""
+    """The FP16-input matrix-instruction kernels (256 x 256 and 128 x 128 tile; K a multiple of 64: global -> LDS
+    loads on the 16x16x32 instruction, else register staging with a K tile of 32) over every prologue / steady /
+    drain combination of K tiles."""
     dm.dmath_set_hgemm_path(path)
     run_hgemm_case(dm, torch, tA, tB, 264, 520, K, ints=True, exact=True, beta=1.0, seed=K + tA)
     run_hgemm_case(dm, torch, tA, tB, 264, 520, K, alpha=0.75, beta=-0.5, seed=K + tB, ld_extra=(8, 16, 3))
 
 
 @pytest.mark.parametrize("tA,tB", TRANS)
-@pytest.mark.parametrize("path", [1, 2, 3, 18, 33, 65, 67])
+@pytest.mark.parametrize("path", [1, 2])
 def test_hgemm_fp16_instruction_shapes(dm, torch, tA, tB, path):
     dm.dmath_set_hgemm_path(path)
     m_odd = 37 if tA == 0 else 40          # an operand stored along its own index needs a multiple of 8
@@ -800,20 +801,21 @@ def test_hgemm_fp16_instruction_conditions(dm, torch):
     assert dm.dmath_hgemm(0, 0, 64, 60, 64, 1.0, t, 64, t, 64, 0.0, t, 64) == dm.ERR_UNSUPPORTED      # N % 8, B along n
     assert dm.dmath_hgemm(0, 0, 64, 64, 64, 1.0, t[1:], 64, t, 64, 0.0, t, 64) == dm.ERR_UNSUPPORTED  # alignment
     assert dm.dmath_hgemm(0, 0, 64, 64, 64, 1.0, t, 68, t, 64, 0.0, t, 64) == dm.ERR_UNSUPPORTED      # lda % 8
-    assert dm.dmath_set_hgemm_path(4) == dm.ERR_INVALID_ARG and dm.dmath_set_hgemm_path(16) == dm.ERR_INVALID_ARG
+    assert dm.dmath_set_hgemm_path(3) == dm.ERR_INVALID_ARG and dm.dmath_set_hgemm_path(-2) == dm.ERR_INVALID_ARG
     dm.dmath_set_hgemm_path(0)             # the widening kernel takes all of them
     run_hgemm_case(dm, torch, 0, 0, 64, 64, 64, seed=1)
     dm.dmath_set_hgemm_path(-1)
     run_hgemm_case(dm, torch, 0, 0, 64, 60, 48, seed=2)
 
 
-def test_hgemm_paths_agree_on_integers(dm, torch):
+@pytest.mark.parametrize("K", [320, 352])   # K tile of 64 on the 16x16x32 instruction; K tile of 32 on 32x32x16
+def test_hgemm_paths_agree_on_integers(dm, torch, K):
     rng = np.random.default_rng(21)
-    M, N, K = 520, 392, 320
+    M, N = 520, 392
     A = torch.from_numpy(rng.integers(-2, 3, size=(M, K)).astype(np.float16)).cuda()
     B = torch.from_numpy(rng.integers(-2, 3, size=(K, N)).astype(np.float16)).cuda()
     out = []
-    for path in (0, 1, 2, 3, 17):
+    for path in (0, 1, 2):
         dm.dmath_set_hgemm_path(path)
         C = torch.zeros((M, N), dtype=torch.float16, device="cuda")
         dm.check(dm.dmath_hgemm(0, 0, M, N, K, 1.0, A, K, B, N, 0.0, C, N))
@@ -977,7 +979,7 @@ def test_random_hgemm_shapes_on_the_fp16_instruction(dm, torch, seed):
         M, N = 8 * int(rng.integers(1, 90)), 8 * int(rng.integers(1, 90))
         K = 32 * int(rng.integers(1, 20))
         tA, tB = int(rng.integers(0, 2)), int(rng.integers(0, 2))
-        dm.dmath_set_hgemm_path(int(rng.choice([-1, 1, 2, 3, 17, 18, 19])))
+        dm.dmath_set_hgemm_path(int(rng.choice([-1, 1, 2])))
         dm.dmath_set_override(-1, int(rng.choice([-1, -1, 2, 5])))
         run_hgemm_case(dm, torch, tA, tB, M, N, K, alpha=float(rng.choice([1.0, 0.5])), beta=float(rng.choice([0.0, 1.0])),
                        ld_extra=tuple(8 * int(rng.integers(0, 3)) for _ in range(3)),
@@ -1132,7 +1134,7 @@ def test_paper_table_sizes_sampled(dm, torch, n):
 
 
 @pytest.mark.parametrize("tA,tB", TRANS)
-@pytest.mark.parametrize("path", [1, 3])
+@pytest.mark.parametrize("path", [1, 2])
 def test_hgemm_epilogue_through_lds(dm, torch, tA, tB, path):
     """beta == 0, 16-byte aligned C with ldc a multiple of 8 and tiles wholly inside C: the 16x16x32 kernels round
     the tile to half in LDS and store whole row pieces.  520 columns leave a ragged tile column on the other path."""
