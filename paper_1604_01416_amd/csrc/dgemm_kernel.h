@@ -9,6 +9,8 @@
 // alignment, any leading dimension, any M, N, K).
 //
 // LDS image per stage, as in the FP32 kernel: As[BK][LDA], Bs[BK][LDB] doubles (k-major), LD = B + 2.
+// (The 16-byte fragment reads still show 4 conflict cycles each on the counters, with this pitch and
+// with B + 8 alike; they are hidden: 64 of the 4096 cycles a K tile takes.)
 // A wave owns MB x NB blocks of 16x16; block bm covers tile rows wm0 + 32*(bm/2) + 2*i + bm%2 for lane
 // row index i, so that a lane's two values of a block pair are adjacent in the image (one 16-byte
 // read, 16 lanes reading 256 contiguous bytes) and a lane owns pairs of adjacent columns of C.
@@ -52,8 +54,13 @@ struct DLoaderK {
 
     __device__ __forceinline__ void init(const double *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int tid)
     {
-        row0 = tid / PPR;
-        kq = tid % PPR;
+        // The 16 lanes whose 8-byte stores the LDS serves in one cycle take 4 k pairs x 4 rows: their
+        // addresses (2*kq + e)*LD + row with LD = 2 mod 8 then fall on banks 8*(kq%4) + 2*(row%4) + {0, 1},
+        // all 32 once.  (With 8 k pairs x 2 rows, pairs kq and kq + 4 met on the same banks: 4 conflict
+        // cycles on every store by the counters, a third of all conflict cycles of the kernel.)
+        static_assert(PPR == 8 && LD % 8 == 2, "bank layout of the transposing stores");
+        kq = (tid & 3) | ((tid >> 2) & 4);
+        row0 = ((tid >> 2) & 3) | ((tid >> 3) & ~3);
         tile = base + r0 * ld + k0;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
