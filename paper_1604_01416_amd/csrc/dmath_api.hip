@@ -203,7 +203,7 @@ const CfgModel kModel[kNumCfg] = {
     {0.935, 0.93, 19.0, 2},  // 256x128
     {0.938, 0.93, 18.0, 2},  // 128x256
     {0.989, 0.989, 36.0, 1}, // 256x256
-    {0.946, 0.93, 14.0, 3},  // 128x128
+    {0.930, 0.92, 14.0, 3},  // 128x128
     {0.800, 0.60, 8.0, 6},   // 64x64
     {0.970, 0.97, 36.0, 1},  // 256x256, rotated image (measured slower than 2; offered, never preferred)
 };
@@ -279,6 +279,10 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool allow_split, int only_cfg
             for (int v = 0; v < (s > 1 && full > 0 && full < tiles ? 2 : 1); ++v) {
                 const Plan cand_plan = {c, (int)dps[v], s};
                 if (s > 1 && plan_bytes(cand_plan, tiles, M, N) > avail) continue;
+                // A split tail is combined inside the launch, and every combination invalidates the L2 of
+                // its die under the whole tiles resident there: fine for a tail of a few dozen tiles, ruinous
+                // for one of most of a round (173 tail tiles in 4 slices each: 807 us against 548 us unsplit).
+                if (s > 1 && dps[v] > 0 && (tiles - dps[v]) * s > 2 * kNumCU) continue;
                 const double cost = plan_cost(c, tiles, dps[v], s, K);
                 if (cost < best_cost) {
                     best_cost = cost;
@@ -444,7 +448,8 @@ int64_t hgemm_split_choice(int hidx, int64_t M, int64_t N, int64_t K, size_t ava
 // MI355X against the best tile configuration with its automatic split: 256 tiles 0.78-0.91 of its time
 // for K from 512 to 8192, 512 and 768 tiles 0.93-0.94, 1024 tiles equal; 192 of 256 equal at K = 4096, 320
 // and 384 of 512 slower; with K up to 256 any tile count up to 256 is 0.94-0.98 of the 64 x 64 tile kernel,
-// at K = 512 from 100 tiles on 0.90, at K = 1024 from 144 tiles on 0.90, 196 tiles 0.64).  Such products
+// at K = 512 from 100 tiles on 0.90, at K = 1024 from 144 tiles on 0.90, 196 tiles 0.64; K = 1540 - 1728 with
+// 209 - 219 tiles 0.79 - 0.83).  Such products
 // used to be cut into K slices across workgroups, with the slices written to and re-read from a workspace
 // by a second kernel.
 int wavek_choice(int64_t M, int64_t N, int64_t K)
@@ -456,7 +461,7 @@ int wavek_choice(int64_t M, int64_t N, int64_t K)
     if (rounds == 1) {
         // Less than a round: the fewer tiles, the sooner cutting K across workgroups (more compute units
         // at work) beats cutting it across the waves of few workgroups.  Measured thresholds.
-        const int64_t min_tiles = K <= 256 ? 1 : K <= 512 ? 96 : K <= 1024 ? 144 : 224;
+        const int64_t min_tiles = K <= 256 ? 1 : K <= 512 ? 96 : K <= 1024 ? 144 : K <= 2048 ? 192 : 224;
         return tiles >= min_tiles ? 0 : -1;
     }
     return (rounds <= 3 && tiles * 8 >= rounds * kNumCU * 7 && K >= 512) ? 0 : -1;
