@@ -218,6 +218,28 @@ def test_gemm_tail_tiles_split(dm, torch, tA, tB):
     assert np.array_equal(outs[0], outs[1])
 
 
+def test_gemm_tail_slices_never_read_stale_partial_sums(dm, torch):
+    """The K slices of tail tiles leave their sums in the workspace and the last slice to arrive reads them from
+    whichever die it runs on.  Calls with different operands reuse the same workspace addresses back to back, so a
+    slice sum served from a cache that still holds the previous call's value would show: integer operands, every
+    call bit-exact against the oracle, sizes shrinking and growing so that old sums lie under new ones."""
+    dm.dmath_set_override(3, -1)
+    shapes = [(2176, 2048, 768), (2176, 2048, 768), (1664, 2688, 768), (2176, 2048, 768), (2304, 2176, 640), (1792, 2560, 1024)]
+    for i, (M, N, K) in enumerate(shapes):
+        st, cfg, split = dm.dmath_gemm_plan(0, 1, M, N, K)
+        assert st == dm.OK and cfg == 3 and split > 1, (M, N, K, cfg, split)   # a split tail
+        rng = np.random.default_rng(900 + i)
+        A = workloads.small_ints(rng, (M, K))
+        B = workloads.small_ints(rng, (N, K))
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        dC = torch.full((M, N), float("nan"), device="cuda")
+        for rep in range(2):
+            dm.check(dm.dmath_gemm(0, 1, M, N, K, 1.0, dA, K, dB, K, 0.0, dC, N))
+        torch.cuda.synchronize()
+        ref, _ = oracle.gemm(0, 1, M, N, K, 1.0, A, K, B, K)
+        assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref), (i, M, N, K)
+
+
 def test_gemm_quick_returns_and_nan_conventions(dm, torch):
     rng = np.random.default_rng(5)
     M, N, K = 70, 50, 40
