@@ -282,7 +282,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
                     for (int j = 0; j < kEpiRows; ++j) {
                         const int r = r0 + j;
                         const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
-                        old[j] = *reinterpret_cast<const CV *>(a.y + yoff[0] + (row < a.Kout ? row : a.Kout - 1) * a.PQ);
+                        old[j] = __builtin_nontemporal_load(reinterpret_cast<const CV *>(a.y + yoff[0] + (row < a.Kout ? row : a.Kout - 1) * a.PQ));
                     }
 #pragma unroll
                     for (int j = 0; j < kEpiRows; ++j) {
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
                         CV o;
 #pragma unroll
                         for (int bn = 0; bn < 4; ++bn) o[bn] = __builtin_fmaf(a.beta, old[j][bn], a.alpha * acc[bm][bn][r]);
-                        if (row < a.Kout) *reinterpret_cast<CV *>(a.y + yoff[0] + row * a.PQ) = o;
+                        if (row < a.Kout) __builtin_nontemporal_store(o, reinterpret_cast<CV *>(a.y + yoff[0] + row * a.PQ));
                     }
                 }
             }
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
                     CV o;
 #pragma unroll
                     for (int bn = 0; bn < 4; ++bn) o[bn] = out[bn];
-                    *reinterpret_cast<CV *>(dst) = o;
+                    __builtin_nontemporal_store(o, reinterpret_cast<CV *>(dst));   // written once (see store_tile_rowmajor)
                 }
             } else {
 #pragma unroll
