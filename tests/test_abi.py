@@ -114,6 +114,47 @@ def test_workspace_and_override_api(dm):
     assert dm.dmath_set_override(-1, -1) == dm.OK
 
 
+def test_plans_over_random_shapes_are_stable_and_bounded(dm):
+    """Host logic of the plan choice: every shape gets a valid configuration, asking twice (the second answer
+    comes from the per-thread plan cache) and asking again after other shapes gives the same plan, a forced
+    configuration is honoured and forgotten again, and split tails stay at two slices per compute unit."""
+    import numpy as np
+    rng = np.random.default_rng(11)
+    ncfg = dm.dmath_num_configs()
+    tile = {0: (256, 128), 1: (128, 256), 2: (256, 256), 3: (128, 128), 4: (64, 64), 5: (256, 256), 6: (64, 64)}
+    shapes = [(int(2 ** rng.uniform(3, 14)), int(2 ** rng.uniform(3, 14)), int(2 ** rng.uniform(3, 15))) for _ in range(300)]
+    first = {}
+    for (M, N, K) in shapes:
+        st, cfg, split = dm.dmath_gemm_plan(0, 0, M, N, K)
+        assert st == dm.OK and 0 <= cfg < ncfg and 1 <= split <= 64, (M, N, K, cfg, split)
+        assert dm.dmath_gemm_plan(0, 0, M, N, K) == (st, cfg, split)
+        first[(M, N, K)] = (cfg, split)
+        need = dm.dmath_gemm_workspace_bytes(0, 0, M, N, K)
+        if cfg == 6:
+            assert need == 0 and split == 1          # K is split inside the workgroups
+    # without a workspace nothing may be split across workgroups ...
+    assert all(s == 1 for (_, s) in first.values())
+    # ... and with the room a plan asks for, a split tail is never more than two slices per compute unit
+    for (M, N, K) in shapes:
+        need = dm.dmath_gemm_workspace_bytes(0, 0, M, N, K)
+        if need == 0:
+            continue
+        assert dm.dmath_set_workspace(1 << 20, need) == dm.OK      # any aligned address: nothing is launched here
+        st, cfg, split = dm.dmath_gemm_plan(0, 0, M, N, K)
+        assert st == dm.OK and split >= 2 and cfg != 6, (M, N, K, cfg, split)
+        bm, bn = tile[cfg]
+        tiles = -(-M // bm) * -(-N // bn)
+        if tiles > 256 and need < split * M * N * 4:             # only the tail is split
+            assert (tiles - tiles // 256 * 256) * split <= 512, (M, N, K, cfg, split, tiles)
+        assert dm.dmath_set_workspace(None, 0) == dm.OK
+    for (M, N, K) in shapes[:50]:                              # the cache keeps forced and automatic plans apart
+        assert dm.dmath_set_override(3, -1) == dm.OK
+        assert dm.dmath_gemm_plan(0, 0, M, N, K)[1] == 3
+        assert dm.dmath_set_override(-1, -1) == dm.OK
+        st, cfg, split = dm.dmath_gemm_plan(0, 0, M, N, K)
+        assert (cfg, split) == first[(M, N, K)], (M, N, K)
+
+
 def test_hgemm_workspace_query_is_host_side_only():
     from paper_1604_01416_amd import dmath as dm
     assert dm.dmath_hgemm_workspace_bytes(0, 0, 0, 16, 16) == 0
