@@ -36,10 +36,10 @@ MEASURED_HBM_TRAFFIC_BYTES = {
     # per step: sum over the kernels of a step of FETCH_SIZE KiB x 2.0 (copy factor) + WRITE_SIZE KiB x 1.0
     "gemm4096": int((196779.4 * 2.0 + 65536.5) * 1024),                         # profiles/gemm_nn_4096_tile_kernel.md
     "gemm256": int((820.7 * 2.0 + 256.2) * 1024),                               # profiles/gemm_nn_256_wavek_kernel.md
-    "summa": int(16 * (258977.1 * 2.0 + 262144.5) * 1024),                      # profiles/summa_update_8192x8192x512_tile_kernel.md
-    "summa_fused": int((1704117.8 * 2.0 + 262144.5) * 1024),                    # profiles/summa_fused_8192x8192x512_x16_panels_kernel.md
-    "fc": int(((49207.9 + 49210.5 + 12462.8) * 2.0
-               + 2 * 4096.5 + 65536.5) * 1024),                                 # profiles/fc_4096_batch256_kernels.md
+    "summa": int(16 * (231599.7 * 2.0 + 262144.5) * 1024),                      # profiles/summa_update_8192x8192x512_tile_kernel.md
+    "summa_fused": int((1704078.9 * 2.0 + 262243.2) * 1024),                    # profiles/summa_fused_8192x8192x512_x16_panels_kernel.md
+    "fc": int(((49207.9 + 49210.5 + 12461.6) * 2.0
+               + 2 * 4096.5 + 65612.7) * 1024),                                 # profiles/fc_4096_batch256_kernels.md
     "conv": int(((101194.2 + 1815.1) * 2.0 + 117779.1 + 2304.1) * 1024),        # profiles/conv3x3_n128_c256_k256_28x28_kernels.md
     "conv_bwd_data": int(((101166.4 + 5719.1) * 2.0 + 117791.6 + 2304.1) * 1024),  # profiles/conv3x3_..._bwd_data_kernels.md
     "conv_bwd_filter": int(((156765.3 + 32274.5) * 2.0 + 64512.0 + 2304.0) * 1024),  # profiles/conv3x3_..._bwd_filter_kernels.md
