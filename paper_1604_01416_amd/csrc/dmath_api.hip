@@ -200,8 +200,8 @@ struct CfgModel {
     int wg_per_cu;     // workgroups resident on a compute unit
 };
 const CfgModel kModel[kNumCfg] = {
-    {0.935, 0.93, 19.0, 2},  // 256x128
-    {0.938, 0.93, 18.0, 2},  // 128x256
+    {0.935, 0.93, 14.0, 2},  // 256x128
+    {0.938, 0.93, 13.0, 2},  // 128x256
     {0.989, 0.989, 36.0, 1}, // 256x256
     {0.930, 0.92, 14.0, 3},  // 128x128
     {0.800, 0.60, 8.0, 6},   // 64x64

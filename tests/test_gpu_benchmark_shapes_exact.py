@@ -5,7 +5,7 @@ order (tile order, K slices, wave-split reductions, panel walks) gives the exact
 match the FP64 oracle bit for bit: a dropped k term, a tile written twice or a misapplied beta cannot
 hide inside a rounding bound.  The full-size configurations are compared on sampled outputs the oracle
 computes one by one (whole rows, columns and planes plus random points); configuration 4 on every
-element.  These are the launch configurations bench.py times (automatic plans, 64 MiB workspace).
+element.  These are the launch configurations bench.py times (automatic plans, 128 MiB workspace).
 """
 import numpy as np
 import pytest
@@ -27,7 +27,7 @@ def torch():
 def dm(torch):
     from paper_1604_01416_amd import dmath
     dmath.dmath_set_override(-1, -1)
-    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
     dmath.check(dmath.dmath_set_workspace(ws, ws.numel()))
     yield dmath
     torch.cuda.synchronize()
