@@ -1158,12 +1158,17 @@ def test_paper_table_sizes_sampled(dm, torch, n):
 @pytest.mark.parametrize("tA,tB", TRANS)
 @pytest.mark.parametrize("path", [1, 2])
 def test_hgemm_epilogue_through_lds(dm, torch, tA, tB, path):
-    """beta == 0, 16-byte aligned C with ldc a multiple of 8 and tiles wholly inside C: the 16x16x32 kernels round
-    the tile to half in LDS and store whole row pieces.  520 columns leave a ragged tile column on the other path."""
+    """16-byte aligned C with ldc a multiple of 8 and tiles wholly inside C: the 16x16x32 kernel stages the tile in LDS
+    and stores whole row pieces (beta == 0: rounded halves; beta != 0: FP32 values, old halves added on the way out).
+    520 columns leave a ragged tile column on the other path."""
     dm.dmath_set_hgemm_path(path)
     run_hgemm_case(dm, torch, tA, tB, 512, 768, 192, ints=True, exact=True, seed=11 + path)
     run_hgemm_case(dm, torch, tA, tB, 512, 520, 128, alpha=-1.5, seed=12 + path, ld_extra=(8, 8, 8))
     run_hgemm_case(dm, torch, tA, tB, 264, 512, 64, seed=13 + path, ld_extra=(0, 0, 16), lead=(0, 0, 8))
+    # beta != 0 on the same tiles: FP32 values staged block row by block row, old halves added, rounded once
+    run_hgemm_case(dm, torch, tA, tB, 512, 768, 192, ints=True, exact=True, beta=1.0, seed=14 + path)
+    run_hgemm_case(dm, torch, tA, tB, 512, 520, 128, alpha=0.75, beta=-0.5, seed=15 + path, ld_extra=(8, 8, 8))
+    run_hgemm_case(dm, torch, tA, tB, 264, 512, 256, alpha=1.0, beta=2.0, seed=16 + path, ld_extra=(0, 0, 16), lead=(0, 0, 8))
 
 
 @pytest.mark.parametrize("tA,tB", TRANS)
