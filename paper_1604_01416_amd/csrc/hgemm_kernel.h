@@ -788,7 +788,7 @@ struct HEpilogueLds {
 
 template <class Cfg>
 __device__ __forceinline__ void hstore_tile16_lds(const floatx4 (&acc)[Cfg::WM / 16][Cfg::WN / 16], _Float16 *C, int64_t ldc,
-                                                  float alpha, int64_t m0, int64_t n0, uint32_t smem_lds)
+                                                  float alpha, int64_t m0, int64_t n0, uint32_t smem_lds, bool nt)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef HEpilogueLds<Cfg> E;
@@ -815,7 +815,10 @@ __device__ __forceinline__ void hstore_tile16_lds(const floatx4 (&acc)[Cfg::WM /
 #pragma unroll
     for (int it = 0; it < Cfg::WM / E::RPI; ++it) {
         const halfx8 v = *(lp128)(uintptr_t)(rd + it * E::RPI * E::ROWB);
-        *reinterpret_cast<halfx8 *>(dst + (int64_t)it * E::RPI * ldc) = v;
+        if (nt)
+            __builtin_nontemporal_store(v, reinterpret_cast<halfx8 *>(dst + (int64_t)it * E::RPI * ldc));
+        else
+            *reinterpret_cast<halfx8 *>(dst + (int64_t)it * E::RPI * ldc) = v;
     }
 #endif
 }
@@ -837,7 +840,7 @@ struct HEpilogueLdsBeta {
 template <class Cfg>
 __device__ __forceinline__ void hstore_tile16_lds_beta(const floatx4 (&acc)[Cfg::WM / 16][Cfg::WN / 16], _Float16 *C,
                                                        int64_t ldc, float alpha, float beta, int64_t m0, int64_t n0,
-                                                       uint32_t smem_lds)
+                                                       uint32_t smem_lds, bool nt)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef HEpilogueLdsBeta<Cfg> E;
@@ -875,7 +878,10 @@ __device__ __forceinline__ void hstore_tile16_lds_beta(const floatx4 (&acc)[Cfg:
                 o[j] = (_Float16)__builtin_fmaf(beta, (float)old[it][j], lo[j]);
                 o[4 + j] = (_Float16)__builtin_fmaf(beta, (float)old[it][4 + j], hi[j]);
             }
-            *reinterpret_cast<halfx8 *>(dst + (int64_t)(16 * bm + it * E::RPI) * ldc) = o;
+            if (nt)
+                __builtin_nontemporal_store(o, reinterpret_cast<halfx8 *>(dst + (int64_t)(16 * bm + it * E::RPI) * ldc));
+            else
+                *reinterpret_cast<halfx8 *>(dst + (int64_t)(16 * bm + it * E::RPI) * ldc) = o;
         }
     }
 #endif
@@ -975,11 +981,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void hgemm_mi16_dma64_kern
     // cvec here: C 16-byte aligned with ldc a multiple of 8 (set by the host for this kernel)
     const bool raw = g.split.plain && w.nslice > 1;
     static_assert(HEpilogueLdsBeta<Cfg>::BYTES <= SMEM_H * 2, "the staging regions fit into the stages");
-    const bool through_lds = !raw && g.cvec == 2 && T > 0 && m0 + Cfg::BM <= g.M && n0 + Cfg::BN <= g.N;
+    const bool through_lds = !raw && g.cvec >= 2 && T > 0 && m0 + Cfg::BM <= g.M && n0 + Cfg::BN <= g.N;
+    const bool nt = g.cvec == 3;   // large result: stores with the non-temporal hint (set by the host)
     if (through_lds && g.beta == 0.0f)
-        hstore_tile16_lds<Cfg>(acc, g.C, g.ldc, g.alpha, m0, n0, smem_lds);
+        hstore_tile16_lds<Cfg>(acc, g.C, g.ldc, g.alpha, m0, n0, smem_lds, nt);
     else if (through_lds)
-        hstore_tile16_lds_beta<Cfg>(acc, g.C, g.ldc, g.alpha, g.beta, m0, n0, smem_lds);
+        hstore_tile16_lds_beta<Cfg>(acc, g.C, g.ldc, g.alpha, g.beta, m0, n0, smem_lds, nt);
     else
         hstore_tile16<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, m0, n0, g.split, w);
     if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
