@@ -200,10 +200,10 @@ struct CfgModel {
     int wg_per_cu;     // workgroups resident on a compute unit
 };
 const CfgModel kModel[kNumCfg] = {
-    {0.935, 0.93, 14.0, 2},  // 256x128
-    {0.938, 0.93, 13.0, 2},  // 128x256
+    {0.935, 0.93, 9.0, 2},  // 256x128
+    {0.938, 0.93, 8.0, 2},  // 128x256
     {0.989, 0.989, 36.0, 1}, // 256x256
-    {0.930, 0.92, 14.0, 3},  // 128x128
+    {0.930, 0.92, 9.0, 3},  // 128x128
     {0.800, 0.60, 8.0, 6},   // 64x64
     {0.970, 0.97, 36.0, 1},  // 256x256, rotated image (measured slower than 2; offered, never preferred)
 };
