@@ -42,9 +42,9 @@ MEASURED_HBM_TRAFFIC_BYTES = {
                + 2 * 4096.5 + 65612.7) * 1024),                                 # profiles/fc_4096_batch256_kernels.md
     "conv": int(((97615.8 + 1815.1) * 2.0 + 137522.4 + 2304.1) * 1024),        # profiles/conv3x3_n128_c256_k256_28x28_kernels.md
     "conv_bwd_data": int(((97004.2 + 5719.1) * 2.0 + 137523.3 + 2304.1) * 1024),  # profiles/conv3x3_..._bwd_data_kernels.md
-    "conv_bwd_filter": int(((156765.3 + 32274.5) * 2.0 + 64512.0 + 2304.0) * 1024),  # profiles/conv3x3_..._bwd_filter_kernels.md
-    "hgemm4096": int((98398.6 * 2.0 + 32768.5) * 1024),                         # profiles/hgemm_nn_4096_half_storage_mi16_dma64_kernel.md
-    "fc_half": int(((2 * 8212.6 + 33922.3 + 6242.6 + 33920.1) * 2.0
+    "conv_bwd_filter": int(((156773.1 + 32274.5) * 2.0 + 64512.0 + 2304.0) * 1024),  # profiles/conv3x3_..._bwd_filter_kernels.md
+    "hgemm4096": int((98398.5 * 2.0 + 32768.5) * 1024),                         # profiles/hgemm_nn_4096_half_storage_mi16_dma64_kernel.md
+    "fc_half": int(((2 * 8212.6 + 33934.3 + 6248.1 + 33933.8) * 2.0
                     + 2 * 2048.0 + 2 * 16384.5 + 32768.5) * 1024),              # profiles/fc_4096_batch256_half_storage_kernels.md
     "dgemm4096": int((665503.0 * 2.0 + 131694.3) * 1024),                       # profiles/dgemm_nn_4096_tile_kernel.md
 }

@@ -120,7 +120,10 @@ __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::M
                     }
 #pragma unroll
                     for (int bn = 0; bn < Cfg::NB; ++bn) o[bn] = out[bn];
-                    __builtin_nontemporal_store(o, reinterpret_cast<CV *>(dst));
+                    if (raw_slice)   // read back at once by the kernel that adds the slices: leave it in the caches
+                        *reinterpret_cast<CV *>(dst) = o;
+                    else
+                        __builtin_nontemporal_store(o, reinterpret_cast<CV *>(dst));
                 }
             } else {
 #pragma unroll
