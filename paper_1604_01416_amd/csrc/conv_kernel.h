@@ -32,7 +32,7 @@ struct ConvArgs {
     uint32_t magic_sh, magic_sw; // the same for the strides (backward-data form of the generic loader)
     float alpha, beta;
     int tiles_m, tiles_n;
-    int yvec;  // y is 16-byte aligned and P*Q is a multiple of 4
+    int yvec;  // y is 16-byte aligned and P*Q is a multiple of 4 (1), and y is large enough to be streamed (2)
     int64_t x_bytes;  // size of x, for the buffer descriptor of the tap-major loader
     SplitPlan split;
 };
@@ -282,7 +282,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
                     for (int j = 0; j < kEpiRows; ++j) {
                         const int r = r0 + j;
                         const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
-                        old[j] = __builtin_nontemporal_load(reinterpret_cast<const CV *>(a.y + yoff[0] + (row < a.Kout ? row : a.Kout - 1) * a.PQ));
+                        const CV *src = reinterpret_cast<const CV *>(a.y + yoff[0] + (row < a.Kout ? row : a.Kout - 1) * a.PQ);
+                        old[j] = a.yvec == 2 ? __builtin_nontemporal_load(src) : *src;
                     }
 #pragma unroll
                     for (int j = 0; j < kEpiRows; ++j) {
@@ -291,7 +292,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
                         CV o;
 #pragma unroll
                         for (int bn = 0; bn < 4; ++bn) o[bn] = __builtin_fmaf(a.beta, old[j][bn], a.alpha * acc[bm][bn][r]);
-                        if (row < a.Kout) __builtin_nontemporal_store(o, reinterpret_cast<CV *>(a.y + yoff[0] + row * a.PQ));
+                        if (row < a.Kout) {
+                            if (a.yvec == 2)
+                                __builtin_nontemporal_store(o, reinterpret_cast<CV *>(a.y + yoff[0] + row * a.PQ));
+                            else
+                                *reinterpret_cast<CV *>(a.y + yoff[0] + row * a.PQ) = o;
+                        }
                     }
                 }
             }
@@ -318,7 +324,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void conv_tile_kernel(cons
                     CV o;
 #pragma unroll
                     for (int bn = 0; bn < 4; ++bn) o[bn] = out[bn];
-                    __builtin_nontemporal_store(o, reinterpret_cast<CV *>(dst));   // written once (see store_tile_rowmajor)
+                    if (a.yvec == 2)   // a large result is streamed (see store_tile_rowmajor)
+                        __builtin_nontemporal_store(o, reinterpret_cast<CV *>(dst));
+                    else
+                        *reinterpret_cast<CV *>(dst) = o;
                 }
             } else {
 #pragma unroll

@@ -174,6 +174,9 @@ __global__ void conv_filter_copy_kernel(const float *w, float *wt, int64_t rows,
 }
 
 constexpr int kMaxSplits = 64;
+// A result of this many FP32 elements (32 MiB) or more is accessed with the non-temporal hint in the epilogue: it
+// is more than the eight L2 caches hold together, so no consumer would find it there anyway.
+constexpr int64_t kStreamElems = (int64_t)1 << 23;
 
 struct Plan {
     int cfg;
@@ -634,6 +637,7 @@ dmath_status gemm_entry(dmath_op transA, dmath_op transB, int64_t M, int64_t N, 
     g.tiles_n = (int)tiles_n;
     g.clock_probe = g_state.clock_probe;
     g.cvec = (quad_aligned(C) && ldc % 4 == 0) ? 1 : 0;
+    if (g.cvec && !kHalf && M * N >= kStreamElems) g.cvec = 2;
     if (!prepare_split(plan, tiles_m * tiles_n, M, N, ws, stream, g.split)) return fail(DMATH_ERR_LAUNCH, 0);
     g.stagger_ticks = stagger_ticks(d, tiles_m * tiles_n, plan.splits);
     int rc;
@@ -971,6 +975,7 @@ dmath_status dmath_gemm_panels(dmath_op transA, dmath_op transB, int64_t M, int6
         g.tiles_n = (int)tiles_n;
         g.clock_probe = g_state.clock_probe;
         g.cvec = (aligned16(C) && ldc % 4 == 0) ? 1 : 0;
+        if (g.cvec && M * N >= kStreamElems) g.cvec = 2;
         a.npanels = np;
         a.tiles_per_panel = (int)(K / d.BK);
         for (int p = 0; p < kMaxPanels; ++p) {
@@ -1094,6 +1099,7 @@ static dmath_status run_conv(bool bwd_data, int64_t N, int64_t C, int64_t H, int
     a.tiles_m = (int)tiles_m;
     a.tiles_n = (int)tiles_n;
     a.yvec = (aligned16(out) && out_pix % 4 == 0) ? 1 : 0;
+    if (a.yvec && rows * cols >= kStreamElems) a.yvec = 2;
     a.x_bytes = N * chans * in_h * in_w * 4;
     bool vec = aligned16(w) && KK % 4 == 0;
     // the filter copy, when there is one, also clears the counters of the split tail tiles

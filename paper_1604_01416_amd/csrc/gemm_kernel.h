@@ -18,7 +18,7 @@ struct GemmArgsT {
     int64_t M, N, K;
     float alpha, beta;
     int tiles_m, tiles_n;
-    int cvec;         // C rows allow aligned NB-wide vector access
+    int cvec;         // C rows allow aligned NB-wide vector access (1), and C is large enough to be streamed (2)
     SplitPlan split;
     unsigned stagger_ticks = 0;  // 0, or how long workgroups 256..511 wait before they start (100 MHz ticks)
     unsigned long long *clock_probe;  // optional: 4 stamps from each of workgroups 0..7 (see dmath_set_clock_probe)
@@ -47,14 +47,17 @@ struct ColLoaderSel<Cfg, false, VEC, T, OffT> {
 // predication.  Lane (i, h) owns, for block row bm and accumulator register r, the NB consecutive
 // columns n0 + wn0 + NB*i .. of row m0 + wm0 + MB*(8*(r/4) + 4*h + r%4) + bm.  A slice of a plain
 // split-K launch writes its raw sums to its M x N array in the workspace instead.
-// C is read once and written once per launch: the 16-byte accesses of the epilogue carry the non-temporal hint so
-// that they do not push the operand panels out of L2 under the workgroups still multiplying (config 3 call 502.8
-// -> 499.4 us, 4096 x 4096 x 256: 69.1 -> 68.5, 2048^3: 125.2 -> 123.7 us; 4096^3 unchanged).
+// stream_c: C is large (the host sets it from 32 MiB on, more than the L2 caches hold together): it is read once
+// and written once per launch and nobody finds it in a cache afterwards, so the 16-byte accesses of the epilogue
+// carry the non-temporal hint and do not push the operand panels out of L2 under the workgroups still multiplying
+// (config 3 call 502.8 -> 499.4 us, 4096 x 4096 x 256: 69.1 -> 68.5 us; 4096^3 unchanged).  A smaller result is
+// left in the caches for whoever consumes it next.
 constexpr int kEpiRows = 8;  // old values of C fetched per batch in the epilogue (4, 8 and 16 measure alike)
 template <class Cfg>
 __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::MB][Cfg::NB], float *C, int64_t ldc_,
                                                     int64_t M, int64_t N, float alpha_, float beta_, bool cvec,
-                                                    int64_t m0, int64_t n0, const SplitPlan &split, const WorkItem &w)
+                                                    int64_t m0, int64_t n0, const SplitPlan &split, const WorkItem &w,
+                                                    bool stream_c = false)
 {
     typedef typename VecOf<Cfg::NB>::type CV;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -80,7 +83,8 @@ __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::M
                     for (int j = 0; j < kEpiRows; ++j) {
                         const int r = r0 + j;
                         const int64_t row = m0 + wm0 + Cfg::MB * (8 * (r / 4) + 4 * h + (r % 4)) + bm;
-                        old[j] = __builtin_nontemporal_load(reinterpret_cast<const CV *>(Cz + (row < M ? row : M - 1) * ldc + col));
+                        const CV *src = reinterpret_cast<const CV *>(Cz + (row < M ? row : M - 1) * ldc + col);
+                        old[j] = stream_c ? __builtin_nontemporal_load(src) : *src;
                     }
 #pragma unroll
                     for (int j = 0; j < kEpiRows; ++j) {
@@ -89,7 +93,12 @@ __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::M
                         CV o;
 #pragma unroll
                         for (int bn = 0; bn < Cfg::NB; ++bn) o[bn] = __builtin_fmaf(beta, old[j][bn], alpha * acc[bm][bn][r]);
-                        if (row < M) __builtin_nontemporal_store(o, reinterpret_cast<CV *>(Cz + row * ldc + col));
+                        if (row < M) {
+                            if (stream_c)
+                                __builtin_nontemporal_store(o, reinterpret_cast<CV *>(Cz + row * ldc + col));
+                            else
+                                *reinterpret_cast<CV *>(Cz + row * ldc + col) = o;
+                        }
                     }
                 }
             }
@@ -120,10 +129,10 @@ __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::M
                     }
 #pragma unroll
                     for (int bn = 0; bn < Cfg::NB; ++bn) o[bn] = out[bn];
-                    if (raw_slice)   // read back at once by the kernel that adds the slices: leave it in the caches
-                        *reinterpret_cast<CV *>(dst) = o;
-                    else
+                    if (stream_c && !raw_slice)   // (a raw slice is read back at once by the kernel that adds the slices)
                         __builtin_nontemporal_store(o, reinterpret_cast<CV *>(dst));
+                    else
+                        *reinterpret_cast<CV *>(dst) = o;
                 }
             } else {
 #pragma unroll
@@ -144,7 +153,8 @@ __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::M
 template <class Cfg>
 __device__ __forceinline__ void store_tile_rowmajor(const floatx16 (&acc)[Cfg::MB][Cfg::NB], _Float16 *C, int64_t ldc,
                                                     int64_t M, int64_t N, float alpha, float beta, bool cvec,
-                                                    int64_t m0, int64_t n0, const SplitPlan &split, const WorkItem &w)
+                                                    int64_t m0, int64_t n0, const SplitPlan &split, const WorkItem &w,
+                                                    bool = false)
 {
     if (split.plain && w.nslice > 1) {
         store_tile_rowmajor<Cfg>(acc, static_cast<float *>(nullptr), N, M, N, 1.0f, 0.0f, false, m0, n0, split, w);
@@ -270,7 +280,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_tile_kernel(cons
     mainloop<Cfg>(rl, cl, T, krem, acc, smem);
     if (!combine_slices<Cfg>(acc, g.split, w)) return;
 
-    store_tile_rowmajor<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, g.cvec != 0, m0, n0, g.split, w);
+    store_tile_rowmajor<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, g.cvec != 0, m0, n0, g.split, w, g.cvec == 2);
     if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
         g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
         g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();

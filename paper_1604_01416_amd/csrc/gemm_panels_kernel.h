@@ -103,7 +103,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MIN_WAVES) void gemm_panels_tile_kern
     mainloop<Cfg>(rl, cl, T, 0, acc, smem);
     if (!combine_slices<Cfg>(acc, g.split, w)) return;
 
-    store_tile_rowmajor<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, g.cvec != 0, m0, n0, g.split, w);
+    store_tile_rowmajor<Cfg>(acc, g.C, g.ldc, g.M, g.N, g.alpha, g.beta, g.cvec != 0, m0, n0, g.split, w, g.cvec == 2);
     if (g.clock_probe != nullptr && blockIdx.x < kNumXcd && threadIdx.x == 0) {
         g.clock_probe[blockIdx.x * 4 + 2] = __builtin_readcyclecounter();
         g.clock_probe[blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
